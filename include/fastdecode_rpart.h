@@ -1,0 +1,152 @@
+/*
+ * fastdecode_rpart.h -- C ABI of the MI355X (gfx950) R-Part library.
+ *
+ * The R-Part is the per-sequence, parameter-free part of a decoder block in
+ * FastDecode (arXiv 2403.11421, Section 3.1): Eq. 2 (scores of the new token's
+ * query against every cached key, normalised by softmax) and Eq. 3 (weighted
+ * sum of the cached values).  Section 4.1 states the worker's contract that
+ * this ABI mirrors: receive Q_i, K_i, V_i for a batch of sequences, append
+ * K_i, V_i to each sequence's KV-cache, attend Q_i over the local cache,
+ * return O_i, and drop a sequence's cache when its generation ends.
+ *
+ * Conventions
+ *   - Every pointer marked "device" is HBM memory of the current HIP device,
+ *     owned by the caller; the library allocates nothing and frees nothing.
+ *   - Every call only enqueues work on `stream` (a hipStream_t passed as
+ *     void*; NULL = the default stream) and returns without synchronising,
+ *     unless stated otherwise.
+ *   - fp16 means IEEE 754 binary16; arithmetic is fp32 (Section 5.1: 16-bit
+ *     storage widened in registers).  `out` is rounded to nearest-even fp16.
+ *   - Return value: FD_OK or a negative FD_E* code.  Errors that the host can
+ *     see (null / misaligned pointers, bad shapes, workspace too small) are
+ *     returned before anything is enqueued.  Errors only the device can see
+ *     are OR-ed into the sticky word `*desc->status` (FD_ST_* bits).
+ *   - Calls that share a descriptor, a workspace or output buffers must be
+ *     ordered by the caller (same stream, or events).
+ */
+#ifndef FASTDECODE_RPART_H
+#define FASTDECODE_RPART_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FD_OK          0
+#define FD_EINVAL     (-1)  /* null/misaligned pointer, B<0, H<=0, d not in {64,128}, bad chunk_tokens */
+#define FD_EWORKSPACE (-2)  /* workspace smaller than fd_workspace_bytes(B,H,d,0)               */
+#define FD_EHIP       (-3)  /* a HIP runtime call or kernel launch failed                        */
+
+#define FD_ST_CAPACITY 1    /* append skipped for a sequence whose cache is full                 */
+#define FD_ST_BADLEN   2    /* a seq_lens entry was outside [0, seq_cap]; it was clamped         */
+
+/*
+ * KV-cache of one layer for B sequences (the paper prescribes no layout; this
+ * one makes every (sequence, head) stream a contiguous run of d*2-byte rows).
+ *
+ * Element i of the K row of sequence b, head h, token t is the fp16 at
+ *     k_base[ seq_off[b] + ((int64)h * seq_cap[b] + t) * d + i ]
+ * and likewise for V with v_base.  seq_off[b] must be a multiple of 8 elements
+ * (rows are read with 128-bit loads); blocks must not overlap.
+ */
+typedef struct fd_kv_desc {
+    void          *k_base;        /* device, fp16 slab holding every sequence's K block         */
+    void          *v_base;        /* device, fp16 slab holding every sequence's V block         */
+    const int64_t *seq_off;       /* device int64[B]: element offset of sequence b's block      */
+    const int32_t *seq_cap;       /* device int32[B]: capacity of sequence b in tokens          */
+    int32_t       *seq_lens;      /* device int32[B]: cached tokens; written by append / reset  */
+    int32_t       *status;        /* device int32[1]: sticky FD_ST_* bits; caller zeroes it     */
+    int32_t        B;             /* sequences                                                   */
+    int32_t        H;             /* attention heads (multi-head: one K/V head per query head)  */
+    int32_t        d;             /* head dimension, 64 or 128                                   */
+    int32_t        chunk_tokens;  /* split-K chunk length in tokens; 0 = chosen on the device   */
+} fd_kv_desc;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int fd_version(void);
+
+/* Static text for an FD_* return code. */
+const char *fd_strerror(int code);
+
+/*
+ * Bytes of workspace that fd_rpart_decode needs so that it can split contexts
+ * into chunks of about 256 tokens when at most `max_total_tokens` tokens are
+ * cached over all B sequences.  Any size >= fd_workspace_bytes(B,H,d,0) works:
+ * with less room the planner uses longer chunks.  Returns 0 on bad arguments.
+ */
+size_t fd_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t max_total_tokens);
+
+/*
+ * Append (Section 4.1): for every b, copy the d*H fp16 of k_new[b] and v_new[b]
+ * bit-for-bit into row seq_lens[b] of the sequence's K and V blocks, then
+ * seq_lens[b] += 1.  A sequence with seq_lens[b] >= seq_cap[b] is left
+ * untouched and FD_ST_CAPACITY is set in *desc->status.
+ *   k_new, v_new: device fp16 [B][H][d], 16-byte aligned.
+ */
+int fd_kv_append(const fd_kv_desc *desc, const void *k_new, const void *v_new, void *stream);
+
+/*
+ * Decode attention (Eq. 2 + Eq. 3) for one new token per sequence:
+ *   out[b,h,:] = sum_t softmax_t( q[b,h,:] . K[b,h,t,:] / sqrt(d) ) * V[b,h,t,:]
+ * over t in [0, seq_lens[b]) as seq_lens stands when the kernels run (so it
+ * includes a token appended earlier on the same stream).  seq_lens[b] == 0
+ * gives out[b,:,:] = 0.
+ *   q:   device fp16 [B][H][d], 16-byte aligned.
+ *   out: device fp16 [B][H][d], 16-byte aligned.
+ *   workspace: device, 256-byte aligned, workspace_bytes long; contents are
+ *     scratch (plan tables and split-K partial states) and need no initialisation.
+ * Equivalent to fd_rpart_plan, fd_rpart_partial, fd_rpart_merge in that order.
+ */
+int fd_rpart_decode(const fd_kv_desc *desc, const void *q, void *out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The three stages of fd_rpart_decode, exposed so that a harness can time them
+ * separately.  They must be enqueued in this order on one stream with the same
+ * descriptor and workspace.
+ *   plan:    reads seq_lens on the device, cuts every sequence into chunks and
+ *            writes the work-item table into the workspace.
+ *   partial: streams each chunk's K and V rows once; per (b,h,chunk) produces
+ *            the running max, the sum of exponentials and the unnormalised
+ *            weighted value sum; writes `out` directly for single-chunk sequences.
+ *   merge:   log-sum-exp merge of a sequence's chunk states, normalisation,
+ *            rounding to fp16; also writes zeros for empty sequences.
+ */
+int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_bytes, void *stream);
+int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
+                     void *workspace, size_t workspace_bytes, void *stream);
+int fd_rpart_merge(const fd_kv_desc *desc, void *out,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* fd_kv_append followed by fd_rpart_decode (one R-worker step of Section 4.1). */
+int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, const void *v_new,
+                  void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Drop cached sequences (Section 4.1: a worker may drop a sequence's cache when
+ * its generation ends): seq_lens[seq_ids[j]] = 0 for j < n.  seq_ids is a device
+ * int32[n]; NULL means all B sequences (n is then ignored).  Ids outside [0,B)
+ * are ignored.  The cache rows themselves are not cleared.
+ */
+int fd_kv_reset(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
+
+/*
+ * Copy the sticky status word to the host.  SYNCHRONISES `stream`.
+ * If `clear` is non-zero the device word is zeroed afterwards.
+ */
+int fd_read_status(const fd_kv_desc *desc, int32_t *host_status, int clear, void *stream);
+
+/*
+ * Copy what the last fd_rpart_plan on this workspace decided to the host:
+ * info[0] = work items (sequence chunks), info[1] = chunk length in tokens,
+ * info[2] = total cached tokens, info[3] = persistent workgroups launched.
+ * SYNCHRONISES `stream`.
+ */
+int fd_plan_info(const void *workspace, int32_t info[4], void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTDECODE_RPART_H */

@@ -1,0 +1,708 @@
+// R-Part of FastDecode (arXiv 2403.11421) for gfx950: KV append, ragged planner,
+// split-K streaming attention and log-sum-exp merge, behind the C ABI declared
+// in fastdecode_rpart.h.
+//
+// The path is a batched GEMV (Section 3.1: "still memory-bound"): one flop per
+// KV byte, so everything here is organised around streaming each K and V row
+// from HBM exactly once with 128-bit coalesced loads; no matrix cores.
+//
+// Lane mapping of the streaming kernel (d = 128): a row of K or V is 256 B =
+// 16 lanes x 16 B, so one wave64 load instruction covers 4 consecutive tokens
+// (1 KB contiguous).  Each lane keeps the 8 query elements of its column slice
+// in registers; the q.k dot product is finished by a 4-step DPP butterfly inside
+// the 16-lane row; each 16-lane row runs its own online softmax over "its"
+// tokens, so the value accumulation needs no cross-lane traffic in the loop.
+// d = 64 uses 8 lanes per row and 8 tokens per wave load.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fastdecode_rpart.h"
+
+namespace {
+
+constexpr int kVersion = 100;          // 0.1.0
+constexpr int kWaves = 4;              // waves per workgroup of the streaming kernel
+constexpr int kThreads = kWaves * 64;
+constexpr int kGranule = 64;           // chunk boundaries are multiples of this many tokens
+constexpr int kPlanThreads = 1024;
+constexpr int kHdrInts = 64;           // 256-byte header
+constexpr float kNegBig = -1.0e30f;    // "no token seen yet" running max (finite: no inf-inf)
+
+// header words
+enum { HDR_NITEMS = 0, HDR_TICKET = 1, HDR_CHUNK = 2, HDR_TOKENS = 3, HDR_GRID = 4 };
+
+struct WsLayout {
+    size_t off_item0;     // int32[B]  first item of sequence b
+    size_t off_nchunk;    // int32[B]  chunks of sequence b
+    size_t off_items;     // int4[max_items]  {b, t0, t1, n_chunks_of_b}
+    size_t off_part;      // float[max_items][H][d+2]  {acc[d], m, l}
+    int64_t max_items;
+    size_t min_bytes;     // bytes needed for max_items == B
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline WsLayout ws_layout(int B, int H, int d, size_t ws_bytes)
+{
+    WsLayout w;
+    size_t o = kHdrInts * sizeof(int32_t);
+    w.off_item0 = o;
+    o = align_up(o + (size_t)B * 4, 256);
+    w.off_nchunk = o;
+    o = align_up(o + (size_t)B * 4, 256);
+    w.off_items = o;
+    size_t per_item = 16 + (size_t)H * (size_t)(d + 2) * 4;
+    size_t slop = 512;                                   // alignment of the partial array
+    w.min_bytes = o + slop + (size_t)(B > 0 ? B : 1) * per_item;
+    if (ws_bytes < w.min_bytes) {
+        w.max_items = 0;
+        w.off_part = 0;
+        return w;
+    }
+    w.max_items = (int64_t)((ws_bytes - o - slop) / per_item);
+    if (w.max_items > (int64_t)0x3FFFFFFF) w.max_items = 0x3FFFFFFF;
+    w.off_part = align_up(o + (size_t)w.max_items * 16, 256);
+    return w;
+}
+
+// ---------------------------------------------------------------------------
+// Append (Section 4.1).  One workgroup per sequence: 2*H rows of d fp16 are
+// copied as raw 128-bit words, then one thread bumps the length.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void kv_append_kernel(
+    uint4 *__restrict__ k_base, uint4 *__restrict__ v_base,
+    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
+    int32_t *__restrict__ seq_lens, int32_t *__restrict__ status,
+    const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new, int H, int d)
+{
+    const int b = blockIdx.x;
+    const int L = seq_lens[b];
+    const int cap = seq_cap[b];
+    if (L < 0 || L >= cap) {
+        if (threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
+        return;
+    }
+    const int vpr = d / 8;                               // 16-byte words per row
+    const int n = H * vpr;
+    const int64_t blk = seq_off[b] / 8;                  // block offset in 16-byte words
+    const int64_t src0 = (int64_t)b * n;
+    for (int x = threadIdx.x; x < 2 * n; x += blockDim.x) {
+        const int which = x >= n;
+        const int y = which ? x - n : x;
+        const int h = y / vpr, c = y - h * vpr;
+        const int64_t dst = blk + ((int64_t)h * cap + L) * vpr + c;
+        if (which) v_base[dst] = v_new[src0 + y];
+        else       k_base[dst] = k_new[src0 + y];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) seq_lens[b] = L + 1;
+}
+
+__global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, const int32_t *__restrict__ ids,
+                                int n, int B)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n) return;
+    const int b = ids ? ids[j] : j;
+    if (b >= 0 && b < B) seq_lens[b] = 0;
+}
+
+// ---------------------------------------------------------------------------
+// Planner: one workgroup.  Reads the ragged lengths on the device, picks the
+// chunk length, and writes the work-item table.  Sequence b with L_b tokens is
+// cut into n_b = ceil(L_b / T) chunks of equal length rounded up to the granule.
+// ---------------------------------------------------------------------------
+__device__ inline int block_sum(int v, int *sm)
+{
+    // sum over the workgroup; result returned to all threads
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    int t = 0;
+    for (int w = 0; w < kPlanThreads / 64; ++w) t += sm[w];
+    return t;
+}
+
+__device__ inline int clamp_len(int L, int cap, int *bad)
+{
+    if (L < 0) { *bad = 1; return 0; }
+    if (L > cap) { *bad = 1; return cap > 0 ? cap : 0; }
+    return L;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(
+    const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
+    int32_t *__restrict__ status, int B, int H, int chunk_req, int grid, int max_items,
+    int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
+    int4 *__restrict__ items)
+{
+    __shared__ int sm[kPlanThreads];
+    const int tid = threadIdx.x;
+    const int per = (B + kPlanThreads - 1) / kPlanThreads;   // sequences per thread (contiguous)
+    const int b0 = tid * per;
+    const int b1 = min(B, b0 + per);
+
+    int bad = 0, mine = 0;
+    for (int b = b0; b < b1; ++b) mine += clamp_len(seq_lens[b], seq_cap[b], &bad);
+    const int total = block_sum(mine, sm);
+    if (bad) atomicOr(status, FD_ST_BADLEN);
+
+    // chunk length: explicit request, else aim at ~32 work units per resident
+    // workgroup so the tail of the dynamic schedule stays around a percent
+    int T;
+    if (chunk_req > 0) {
+        T = chunk_req;
+    } else {
+        const long long units = (long long)total * H;
+        long long t = units / ((long long)grid * 32);
+        T = (int)(t < 128 ? 128 : (t > 1024 ? 1024 : t));
+    }
+    T = (T + kGranule - 1) / kGranule * kGranule;
+
+    int count;
+    for (;;) {
+        int c = 0;
+        for (int b = b0; b < b1; ++b) {
+            const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+            c += (L + T - 1) / T;
+        }
+        count = block_sum(c, sm);
+        if (count <= max_items || T >= (1 << 30)) break;   // T >= longest sequence gives count <= B
+        T *= 2;
+    }
+
+    // exclusive scan of per-thread item counts
+    int c = 0;
+    for (int b = b0; b < b1; ++b) {
+        const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+        c += (L + T - 1) / T;
+    }
+    __syncthreads();
+    sm[tid] = c;
+    __syncthreads();
+    for (int off = 1; off < kPlanThreads; off <<= 1) {
+        const int v = tid >= off ? sm[tid - off] : 0;
+        __syncthreads();
+        sm[tid] += v;
+        __syncthreads();
+    }
+    int pos = sm[tid] - c;
+    for (int b = b0; b < b1; ++b) {
+        const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+        const int n = (L + T - 1) / T;
+        item0[b] = pos;
+        nchunk[b] = n;
+        if (n > 0) {
+            int len = (L + n - 1) / n;
+            len = (len + kGranule - 1) / kGranule * kGranule;   // <= T, so (n-1)*len < L
+            for (int k = 0; k < n; ++k) {
+                const int t0 = k * len;
+                const int t1 = min(L, t0 + len);
+                if (pos + k < max_items) items[pos + k] = make_int4(b, t0, t1, n);
+            }
+        }
+        pos += n;
+    }
+    if (tid == 0) {
+        hdr[HDR_NITEMS] = count <= max_items ? count : 0;
+        hdr[HDR_TICKET] = grid;          // tickets [0, grid) are taken statically by blockIdx
+        hdr[HDR_CHUNK] = T;
+        hdr[HDR_TOKENS] = total;
+        hdr[HDR_GRID] = grid;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Split-K streaming attention (Eq. 2 + Eq. 3 over one chunk of one (b,h)).
+// ---------------------------------------------------------------------------
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+
+template <int CTRL>
+__device__ inline float dpp_xadd(float x)
+{
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true);
+    return x + __int_as_float(y);
+}
+
+// sum over the LPR consecutive lanes that hold one row; every lane gets the sum
+template <int LPR>
+__device__ inline float row_sum(float x)
+{
+    x = dpp_xadd<0xB1>(x);                  // quad_perm [1,0,3,2]
+    x = dpp_xadd<0x4E>(x);                  // quad_perm [2,3,0,1]
+    x = dpp_xadd<0x141>(x);                 // row_half_mirror: other quad of the 8
+    if (LPR == 16) x = dpp_xadd<0x140>(x);  // row_mirror: other half of the 16
+    return x;
+}
+
+__device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+__device__ inline half8 ld_stream(const char *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const half8 *>(p));
+}
+
+template <int D, int NL>
+struct Tile {
+    static constexpr int LPR = D / 8;          // lanes per row
+    static constexpr int RPW = 64 / LPR;       // rows (tokens) per wave load
+    static constexpr int TOK = RPW * NL;       // tokens per tile
+    static constexpr int BYTES = TOK * D * 2;  // bytes of K (or V) per tile
+    half8 k[NL], v[NL];
+
+    __device__ inline void load(const char *kp, const char *vp)
+    {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) k[j] = ld_stream(kp + j * 1024);
+#pragma unroll
+        for (int j = 0; j < NL; ++j) v[j] = ld_stream(vp + j * 1024);
+    }
+
+    // ragged tail: rows at or beyond `rem` re-read row rem-1 (in bounds) and are masked later
+    __device__ inline void load_tail(const char *kp, const char *vp, int row, int rem)
+    {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int t = j * RPW + row;
+            const int back = t < rem ? 0 : (t - (rem - 1)) * (D * 2);
+            k[j] = ld_stream(kp + j * 1024 - back);
+            v[j] = ld_stream(vp + j * 1024 - back);
+        }
+    }
+
+    template <bool MASKED>
+    __device__ inline void update(const float (&q)[8], float &m, float &l, float (&acc)[8],
+                                  int row, int rem) const
+    {
+        float s[NL];
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            float a = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) a = __builtin_fmaf((float)k[j][i], q[i], a);
+            a = row_sum<LPR>(a);
+            if (MASKED && j * RPW + row >= rem) a = kNegBig;
+            s[j] = a;
+        }
+        float tm = s[0];
+#pragma unroll
+        for (int j = 1; j < NL; ++j) tm = fmaxf(tm, s[j]);
+        const float mn = fmaxf(m, tm);
+        const float corr = fast_exp2(m - mn);
+        l *= corr;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] *= corr;
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            float p = fast_exp2(s[j] - mn);
+            if (MASKED && j * RPW + row >= rem) p = 0.f;
+            l += p;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(p, (float)v[j][i], acc[i]);
+        }
+        m = mn;
+    }
+};
+
+template <int D, int NL>
+__global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
+    const char *__restrict__ k_base, const char *__restrict__ v_base,
+    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
+    const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
+    int32_t *__restrict__ hdr, const int4 *__restrict__ items, float *__restrict__ partials,
+    float qscale)
+{
+    using T = Tile<D, NL>;
+    constexpr int LPR = T::LPR;
+    __shared__ float sm_acc[kWaves][D];
+    __shared__ float sm_m[kWaves], sm_l[kWaves];
+    __shared__ int sm_ticket;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int row = lane / LPR;
+    const int col = lane % LPR;
+    const int n_tickets = hdr[HDR_NITEMS] * H;
+
+    int ticket = blockIdx.x;
+    while (ticket < n_tickets) {
+        // fetch the next ticket early; its latency hides behind this item's streaming
+        int next_ticket = 0;
+        if (tid == 0) next_ticket = atomicAdd(&hdr[HDR_TICKET], 1);
+
+        const int item = ticket / H;
+        const int h = ticket - item * H;
+        const int4 it = items[item];
+        const int b = it.x, t0 = it.y, t1 = it.z, nch = it.w;
+        const int cap = seq_cap[b];
+        const int64_t row0 = seq_off[b] + ((int64_t)h * cap + t0) * D;      // elements
+        const char *kp = k_base + row0 * 2 + lane * 16;
+        const char *vp = v_base + row0 * 2 + lane * 16;
+
+        float qf[8];
+        {
+            const half8 qh = *reinterpret_cast<const half8 *>(q + ((int64_t)b * H + h) * D + col * 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qf[i] = (float)qh[i] * qscale;
+        }
+
+        float m = kNegBig, l = 0.f, acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+
+        const int ntok = t1 - t0;
+        const int n_full = ntok / T::TOK;
+        const int rem = ntok - n_full * T::TOK;
+
+        // full tiles w, w+4, ... : ping-pong register buffers, next tile in flight while computing
+        int t = wave;
+        T A, Bf;
+        if (t < n_full) A.load(kp + (int64_t)t * T::BYTES, vp + (int64_t)t * T::BYTES);
+        while (t < n_full) {
+            int tn = t + kWaves;
+            if (tn < n_full) Bf.load(kp + (int64_t)tn * T::BYTES, vp + (int64_t)tn * T::BYTES);
+            A.template update<false>(qf, m, l, acc, row, 0);
+            t = tn;
+            if (t >= n_full) break;
+            tn = t + kWaves;
+            if (tn < n_full) A.load(kp + (int64_t)tn * T::BYTES, vp + (int64_t)tn * T::BYTES);
+            Bf.template update<false>(qf, m, l, acc, row, 0);
+            t = tn;
+        }
+        if (rem > 0 && wave == (n_full % kWaves)) {
+            A.load_tail(kp + (int64_t)n_full * T::BYTES, vp + (int64_t)n_full * T::BYTES, row, rem);
+            A.template update<true>(qf, m, l, acc, row, rem);
+        }
+
+        // combine the rows of this wave (each 16- or 8-lane row saw different tokens)
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) {
+            const float mo = __shfl_xor(m, off);
+            const float lo = __shfl_xor(l, off);
+            const float M = fmaxf(m, mo);
+            const float a = fast_exp2(m - M), c = fast_exp2(mo - M);
+            l = l * a + lo * c;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], off) * c;
+            m = M;
+        }
+        if (lane < LPR) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) sm_acc[wave][lane * 8 + i] = acc[i];
+        }
+        if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; }
+        if (tid == 0) sm_ticket = next_ticket;
+        __syncthreads();
+
+        // combine the waves; write the final output or this chunk's partial state
+        if (tid < D) {
+            float M = sm_m[0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
+            float L = 0.f, o = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float a = fast_exp2(sm_m[w] - M);
+                L += a * sm_l[w];
+                o += a * sm_acc[w][tid];
+            }
+            if (nch == 1) {
+                out[((int64_t)b * H + h) * D + tid] = (_Float16)(o / L);
+            } else {
+                float *p = partials + ((int64_t)item * H + h) * (D + 2);
+                p[tid] = o;
+                if (tid == 0) { p[D] = M; p[D + 1] = L; }
+            }
+        }
+        ticket = sm_ticket;
+        __syncthreads();               // LDS is reused by the next item
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Log-sum-exp merge of a sequence's chunk states; one wave per (b,h).
+// States are in the base-2 exponent domain used by the streaming kernel.
+// ---------------------------------------------------------------------------
+template <int D>
+__global__ __launch_bounds__(256) void rpart_merge_kernel(
+    const int32_t *__restrict__ item0, const int32_t *__restrict__ nchunk,
+    const float *__restrict__ partials, _Float16 *__restrict__ out, int B, int H)
+{
+    constexpr int PER = D / 64;                       // output elements per lane
+    const int lane = threadIdx.x & 63;
+    const int64_t bh = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (bh >= (int64_t)B * H) return;
+    const int b = (int)(bh / H);
+    const int h = (int)(bh - (int64_t)b * H);
+    const int n = nchunk[b];
+    if (n == 1) return;                               // written by the streaming kernel
+    _Float16 *o = out + bh * D + lane * PER;
+    if (n == 0) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) o[i] = (_Float16)0.f;
+        return;
+    }
+    const float *p0 = partials + ((int64_t)item0[b] * H + h) * (D + 2);
+    const int64_t stride = (int64_t)H * (D + 2);
+    float M = kNegBig;
+    for (int c = 0; c < n; ++c) M = fmaxf(M, p0[c * stride + D]);
+    float L = 0.f, acc[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+    for (int c = 0; c < n; ++c) {
+        const float *p = p0 + c * stride;
+        const float w = fast_exp2(p[D] - M);
+        L += w * p[D + 1];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) acc[i] += w * p[lane * PER + i];
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) o[i] = (_Float16)(acc[i] / L);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+constexpr int kTileLoads = 8;                          // wave loads of K (and of V) per tile
+
+inline bool aligned(const void *p, size_t a) { return ((uintptr_t)p % a) == 0; }
+
+int check_desc(const fd_kv_desc *d)
+{
+    if (!d) return FD_EINVAL;
+    if (d->B < 0 || d->H <= 0 || (d->d != 64 && d->d != 128)) return FD_EINVAL;
+    if (d->chunk_tokens < 0) return FD_EINVAL;
+    if (d->B == 0) return FD_OK;
+    if (!d->k_base || !d->v_base || !d->seq_off || !d->seq_cap || !d->seq_lens || !d->status)
+        return FD_EINVAL;
+    if (!aligned(d->k_base, 16) || !aligned(d->v_base, 16) || !aligned(d->seq_off, 8) ||
+        !aligned(d->seq_cap, 4) || !aligned(d->seq_lens, 4) || !aligned(d->status, 4))
+        return FD_EINVAL;
+    return FD_OK;
+}
+
+int check_ws(const fd_kv_desc *d, const void *ws, size_t ws_bytes, WsLayout *w)
+{
+    if (!ws || !aligned(ws, 256)) return FD_EINVAL;
+    *w = ws_layout(d->B, d->H, d->d, ws_bytes);
+    if (w->max_items < d->B) return FD_EWORKSPACE;
+    return FD_OK;
+}
+
+template <int D>
+const void *partial_fn() { return (const void *)rpart_partial_kernel<D, kTileLoads>; }
+
+// persistent grid: every workgroup that can be resident at once, queried once per process
+int persistent_grid(int d)
+{
+    static int grid[2] = {0, 0};
+    const int k = d == 128;
+    if (grid[k] == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            return 0;
+        const void *fn = k ? partial_fn<128>() : partial_fn<64>();
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, 0) != hipSuccess)
+            return 0;
+        if (per_cu < 1) per_cu = 1;
+        grid[k] = cus * per_cu;
+    }
+    return grid[k];
+}
+
+int launched(void) { return hipGetLastError() == hipSuccess ? FD_OK : FD_EHIP; }
+
+} // namespace
+
+extern "C" {
+
+int fd_version(void) { return kVersion; }
+
+const char *fd_strerror(int code)
+{
+    switch (code) {
+    case FD_OK: return "ok";
+    case FD_EINVAL: return "invalid argument (null or misaligned pointer, bad shape)";
+    case FD_EWORKSPACE: return "workspace too small";
+    case FD_EHIP: return "HIP runtime call or kernel launch failed";
+    default: return "unknown error code";
+    }
+}
+
+size_t fd_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t max_total_tokens)
+{
+    if (B < 0 || H <= 0 || (d != 64 && d != 128) || max_total_tokens < 0) return 0;
+    WsLayout w = ws_layout(B, H, d, 0);
+    const size_t per_item = 16 + (size_t)H * (size_t)(d + 2) * 4;
+    const size_t extra = (size_t)((max_total_tokens + 255) / 256);
+    return align_up(w.min_bytes + extra * per_item, 256);
+}
+
+int fd_kv_append(const fd_kv_desc *desc, const void *k_new, const void *v_new, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
+    hipLaunchKernelGGL(kv_append_kernel, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
+                       (uint4 *)desc->k_base, (uint4 *)desc->v_base, desc->seq_off, desc->seq_cap,
+                       desc->seq_lens, desc->status, (const uint4 *)k_new, (const uint4 *)v_new,
+                       desc->H, desc->d);
+    return launched();
+}
+
+int fd_kv_reset(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (seq_ids && n < 0) return FD_EINVAL;
+    const int count = seq_ids ? n : desc->B;
+    if (count == 0) return FD_OK;
+    hipLaunchKernelGGL(kv_reset_kernel, dim3((count + 255) / 256), dim3(256), 0,
+                       (hipStream_t)stream, desc->seq_lens, seq_ids, count, desc->B);
+    return launched();
+}
+
+int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    WsLayout w;
+    rc = check_ws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    const int grid = persistent_grid(desc->d);
+    if (grid <= 0) return FD_EHIP;
+    char *ws = (char *)workspace;
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
+                       desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
+                       desc->chunk_tokens, grid, (int)w.max_items, (int32_t *)ws,
+                       (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
+                       (int4 *)(ws + w.off_items));
+    return launched();
+}
+
+int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
+    WsLayout w;
+    rc = check_ws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    const int grid = persistent_grid(desc->d);
+    if (grid <= 0) return FD_EHIP;
+    char *ws = (char *)workspace;
+    // scores are kept in the base-2 exponent domain: exp(x) = 2^(x * log2 e)
+    const float qscale = (float)(1.4426950408889634 / (desc->d == 128 ? 11.313708498984761 : 8.0));
+    if (desc->d == 128)
+        hipLaunchKernelGGL((rpart_partial_kernel<128, kTileLoads>), dim3(grid), dim3(kThreads), 0,
+                           (hipStream_t)stream, (const char *)desc->k_base,
+                           (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
+                           (const _Float16 *)q, (_Float16 *)out, desc->H, (int32_t *)ws,
+                           (const int4 *)(ws + w.off_items), (float *)(ws + w.off_part), qscale);
+    else
+        hipLaunchKernelGGL((rpart_partial_kernel<64, kTileLoads>), dim3(grid), dim3(kThreads), 0,
+                           (hipStream_t)stream, (const char *)desc->k_base,
+                           (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
+                           (const _Float16 *)q, (_Float16 *)out, desc->H, (int32_t *)ws,
+                           (const int4 *)(ws + w.off_items), (float *)(ws + w.off_part), qscale);
+    return launched();
+}
+
+int fd_rpart_merge(const fd_kv_desc *desc, void *out,
+                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!out || !aligned(out, 16)) return FD_EINVAL;
+    WsLayout w;
+    rc = check_ws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    char *ws = (char *)workspace;
+    const int64_t bh = (int64_t)desc->B * desc->H;
+    const dim3 grid((unsigned)((bh + 3) / 4));
+    if (desc->d == 128)
+        hipLaunchKernelGGL(rpart_merge_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream,
+                           (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
+                           (const float *)(ws + w.off_part), (_Float16 *)out, desc->B, desc->H);
+    else
+        hipLaunchKernelGGL(rpart_merge_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream,
+                           (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
+                           (const float *)(ws + w.off_part), (_Float16 *)out, desc->B, desc->H);
+    return launched();
+}
+
+int fd_rpart_decode(const fd_kv_desc *desc, const void *q, void *out,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    // validate everything before the first launch so that a failing call enqueues nothing
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
+    WsLayout w;
+    rc = check_ws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    rc = fd_rpart_plan(desc, workspace, workspace_bytes, stream);
+    if (rc != FD_OK) return rc;
+    rc = fd_rpart_partial(desc, q, out, workspace, workspace_bytes, stream);
+    if (rc != FD_OK) return rc;
+    return fd_rpart_merge(desc, out, workspace, workspace_bytes, stream);
+}
+
+int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, const void *v_new,
+                  void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !k_new || !v_new || !aligned(q, 16) || !aligned(out, 16) ||
+        !aligned(k_new, 16) || !aligned(v_new, 16))
+        return FD_EINVAL;
+    WsLayout w;
+    rc = check_ws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    rc = fd_kv_append(desc, k_new, v_new, stream);
+    if (rc != FD_OK) return rc;
+    return fd_rpart_decode(desc, q, out, workspace, workspace_bytes, stream);
+}
+
+int fd_read_status(const fd_kv_desc *desc, int32_t *host_status, int clear, void *stream)
+{
+    if (!desc || !desc->status || !host_status) return FD_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    if (hipMemcpyAsync(host_status, desc->status, sizeof(int32_t), hipMemcpyDeviceToHost, s) !=
+        hipSuccess)
+        return FD_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return FD_EHIP;
+    if (clear) {
+        if (hipMemsetAsync(desc->status, 0, sizeof(int32_t), s) != hipSuccess) return FD_EHIP;
+        if (hipStreamSynchronize(s) != hipSuccess) return FD_EHIP;
+    }
+    return FD_OK;
+}
+
+int fd_plan_info(const void *workspace, int32_t info[4], void *stream)
+{
+    if (!workspace || !info) return FD_EINVAL;
+    int32_t hdr[8];
+    hipStream_t s = (hipStream_t)stream;
+    if (hipMemcpyAsync(hdr, workspace, sizeof(hdr), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return FD_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return FD_EHIP;
+    info[0] = hdr[HDR_NITEMS];
+    info[1] = hdr[HDR_CHUNK];
+    info[2] = hdr[HDR_TOKENS];
+    info[3] = hdr[HDR_GRID];
+    return FD_OK;
+}
+
+} // extern "C"

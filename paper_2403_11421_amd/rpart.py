@@ -1,0 +1,167 @@
+"""ctypes binding over the C ABI in ``include/fastdecode_rpart.h``.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+``libfd_rpart.so``.  torch supplies device memory and the current stream.
+There is no fallback: a missing library raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+from . import build as _build
+
+FD_OK, FD_EINVAL, FD_EWORKSPACE, FD_EHIP = 0, -1, -2, -3
+FD_ST_CAPACITY, FD_ST_BADLEN = 1, 2
+
+_vp = ctypes.c_void_p
+
+
+class fd_kv_desc(ctypes.Structure):
+    _fields_ = [
+        ("k_base", _vp), ("v_base", _vp), ("seq_off", _vp), ("seq_cap", _vp),
+        ("seq_lens", _vp), ("status", _vp),
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("chunk_tokens", ctypes.c_int32),
+    ]
+
+
+class FdError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _build.LIB
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library; build it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB)
+    P = ctypes.POINTER(fd_kv_desc)
+    lib.fd_version.restype = ctypes.c_int
+    lib.fd_version.argtypes = []
+    lib.fd_strerror.restype = ctypes.c_char_p
+    lib.fd_strerror.argtypes = [ctypes.c_int]
+    lib.fd_workspace_bytes.restype = ctypes.c_size_t
+    lib.fd_workspace_bytes.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_int64]
+    lib.fd_kv_append.restype = ctypes.c_int
+    lib.fd_kv_append.argtypes = [P, _vp, _vp, _vp]
+    lib.fd_rpart_decode.restype = ctypes.c_int
+    lib.fd_rpart_decode.argtypes = [P, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.fd_rpart_plan.restype = ctypes.c_int
+    lib.fd_rpart_plan.argtypes = [P, _vp, ctypes.c_size_t, _vp]
+    lib.fd_rpart_partial.restype = ctypes.c_int
+    lib.fd_rpart_partial.argtypes = [P, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.fd_rpart_merge.restype = ctypes.c_int
+    lib.fd_rpart_merge.argtypes = [P, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.fd_rpart_step.restype = ctypes.c_int
+    lib.fd_rpart_step.argtypes = [P, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.fd_kv_reset.restype = ctypes.c_int
+    lib.fd_kv_reset.argtypes = [P, _vp, ctypes.c_int32, _vp]
+    lib.fd_read_status.restype = ctypes.c_int
+    lib.fd_read_status.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.c_int, _vp]
+    lib.fd_plan_info.restype = ctypes.c_int
+    lib.fd_plan_info.argtypes = [_vp, ctypes.POINTER(ctypes.c_int32), _vp]
+    _lib = lib
+    return lib
+
+
+EXPORTS = ("fd_version", "fd_strerror", "fd_workspace_bytes", "fd_kv_append", "fd_rpart_decode",
+           "fd_rpart_plan", "fd_rpart_partial", "fd_rpart_merge", "fd_rpart_step", "fd_kv_reset",
+           "fd_read_status", "fd_plan_info")
+
+
+def version() -> int:
+    return load().fd_version()
+
+
+def strerror(code: int) -> str:
+    return load().fd_strerror(code).decode()
+
+
+def workspace_bytes(B: int, H: int, d: int, max_total_tokens: int) -> int:
+    return int(load().fd_workspace_bytes(B, H, d, max_total_tokens))
+
+
+def _stream() -> Optional[int]:
+    return torch.cuda.current_stream().cuda_stream or None
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != FD_OK:
+        raise FdError(rc, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _ws(ws: torch.Tensor):
+    return ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def fd_kv_append(desc: fd_kv_desc, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
+    _check(load().fd_kv_append(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), _stream()),
+           "fd_kv_append")
+
+
+def fd_rpart_decode(desc: fd_kv_desc, q: torch.Tensor, out: torch.Tensor,
+                    workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpart_decode(ctypes.byref(desc), _ptr(q), _ptr(out), p, n, _stream()),
+           "fd_rpart_decode")
+
+
+def fd_rpart_plan(desc: fd_kv_desc, workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpart_plan(ctypes.byref(desc), p, n, _stream()), "fd_rpart_plan")
+
+
+def fd_rpart_partial(desc: fd_kv_desc, q: torch.Tensor, out: torch.Tensor,
+                     workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpart_partial(ctypes.byref(desc), _ptr(q), _ptr(out), p, n, _stream()),
+           "fd_rpart_partial")
+
+
+def fd_rpart_merge(desc: fd_kv_desc, out: torch.Tensor, workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpart_merge(ctypes.byref(desc), _ptr(out), p, n, _stream()), "fd_rpart_merge")
+
+
+def fd_rpart_step(desc: fd_kv_desc, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                  out: torch.Tensor, workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpart_step(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                p, n, _stream()), "fd_rpart_step")
+
+
+def fd_kv_reset(desc: fd_kv_desc, seq_ids: Optional[torch.Tensor] = None) -> None:
+    n = 0 if seq_ids is None else seq_ids.numel()
+    _check(load().fd_kv_reset(ctypes.byref(desc), _ptr(seq_ids), n, _stream()), "fd_kv_reset")
+
+
+def fd_read_status(desc: fd_kv_desc, clear: bool = False) -> int:
+    v = ctypes.c_int32(0)
+    _check(load().fd_read_status(ctypes.byref(desc), ctypes.byref(v), int(clear), _stream()),
+           "fd_read_status")
+    return v.value
+
+
+def fd_plan_info(workspace: torch.Tensor) -> dict:
+    info = (ctypes.c_int32 * 4)()
+    _check(load().fd_plan_info(workspace.data_ptr(), info, _stream()), "fd_plan_info")
+    return {"items": info[0], "chunk_tokens": info[1], "total_tokens": info[2], "grid": info[3]}

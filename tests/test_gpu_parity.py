@@ -1,0 +1,206 @@
+"""HIP path vs fp64 oracle through the C ABI (needs an MI355X).
+
+Bar: seq_lens and cache contents bit-exact; out within 2e-3 * max|V|.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rpart_oracle as O
+from paper_2403_11421_amd import rpart, workloads as W
+from tests.gpu_util import TOL, DeviceCase, check_step
+from tests.util import bits, f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _cfg(name, B, H, d, **kw):
+    return W.RPartConfig(name, B, H, d, "const", 0, 0, **kw)
+
+
+def test_c1_tiny_config():
+    cfg = W.CONFIGS["c1_tiny"]
+    case = DeviceCase(cfg, W.seq_lens(cfg))
+    err, maxv = check_step(case)
+    assert case.cache.seq_lens.cpu().tolist() == [129] * 4
+    print(f"c1 max|err|={err:.2e} max|V|={maxv:.2f}")
+
+
+EDGE_LENS = [0, 1, 2, 3, 4, 7, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 640,
+             1000, 1023, 1024, 1025, 2500]
+
+
+@pytest.mark.parametrize("d", [128, 64])
+@pytest.mark.parametrize("chunk", [0, 64, 128, 256, 1024, 4096])
+def test_edge_lengths_all_chunk_sizes(d, chunk):
+    cfg = _cfg("edges", len(EDGE_LENS), 3, d)
+    case = DeviceCase(cfg, EDGE_LENS, seed=11 + d, chunk_tokens=chunk)
+    check_step(case)
+    info = rpart.fd_plan_info(case.ws)
+    assert info["total_tokens"] == sum(EDGE_LENS) + len(EDGE_LENS)
+    if chunk:
+        assert info["chunk_tokens"] == max(64, chunk)
+        assert info["items"] == sum(math.ceil((L + 1) / max(64, chunk)) for L in EDGE_LENS)
+
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_step_entry_point_and_many_heads(d):
+    cfg = _cfg("step", 5, 40, d)
+    case = DeviceCase(cfg, [300, 17, 2049, 64, 999], seed=5)
+    check_step(case, use_step=True)
+
+
+def test_peaked_keys_small():
+    cfg = W.RPartConfig("peaked", 12, 8, 128, "uniform", 1, 1500, peaked_keys=True)
+    case = DeviceCase(cfg, W.seq_lens(cfg, seed=3), seed=3)
+    check_step(case)
+
+
+def test_minimal_workspace_forces_long_chunks():
+    cfg = _cfg("minws", 6, 4, 128)
+    lens = [5000, 100, 3000, 1, 700, 64]
+    case = DeviceCase(cfg, lens, seed=9, chunk_tokens=64)
+    n = rpart.workspace_bytes(cfg.B, cfg.H, cfg.d, 0)
+    case.ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    check_step(case)
+    info = rpart.fd_plan_info(case.ws)
+    assert info["items"] <= cfg.B + 1 and info["chunk_tokens"] >= 2048
+    with pytest.raises(rpart.FdError) as e:
+        rpart.fd_rpart_decode(case.cache.desc, case.q, case.out, case.ws[:n - 256])
+    assert e.value.code == rpart.FD_EWORKSPACE
+
+
+def test_decode_without_append_and_empty_sequences():
+    cfg = _cfg("empty", 4, 2, 128)
+    case = DeviceCase(cfg, [0, 10, 0, 300], seed=2)
+    rpart.fd_rpart_decode(case.cache.desc, case.q, case.out, case.ws)
+    torch.cuda.synchronize()
+    ref = case.oracle_inputs()
+    want, _, _ = O.rpart_decode(ref["K"], ref["V"], ref["seq_lens"], ref["q"])
+    got = case.out.cpu().double().numpy()
+    assert np.all(got[0] == 0) and np.all(got[2] == 0) and np.all(want[0] == 0)
+    assert np.abs(got - want).max() <= TOL * 5.0
+
+
+def test_single_token_is_bit_exact():
+    cfg = _cfg("one", 7, 5, 128)
+    case = DeviceCase(cfg, [0] * 7, seed=4)
+    check_step(case)
+    assert torch.equal(case.out, case.v_new)          # softmax over one token: weight 1
+
+
+def test_equal_keys_give_mean_of_v():
+    cfg = _cfg("mean", 2, 2, 128)
+    L = 700
+    case = DeviceCase(cfg, [L, L], seed=6, chunk_tokens=128)
+    for b in range(2):
+        blk = case.cache.block("K", b)
+        blk[:, :L, :] = blk[:, :1, :]
+    case.k_new.copy_(torch.stack([case.cache.block("K", b)[:, 0, :] for b in range(2)]))
+    check_step(case)
+    for b in range(2):
+        mean = case.cache.block("V", b)[:, :L + 1, :].double().mean(dim=1)
+        assert (case.out[b].double() - mean).abs().max() < 1e-3
+
+
+def test_chunk_size_independence_and_determinism():
+    cfg = _cfg("sweep", 3, 4, 128)
+    lens = [4000, 777, 2048]
+    outs = []
+    for chunk in (64, 192, 512, 1024, 4096, 0):
+        case = DeviceCase(cfg, lens, seed=8, chunk_tokens=chunk)
+        check_step(case)
+        first = case.out.clone()
+        rpart.fd_rpart_decode(case.cache.desc, case.q, case.out, case.ws)   # again, same state
+        torch.cuda.synchronize()
+        assert torch.equal(first, case.out)
+        outs.append(first.float())
+    for o in outs[1:]:
+        assert (o - outs[0]).abs().max() <= 2e-3     # one fp16 ulp at |out| < 1 is ~1e-3
+
+
+def test_capacity_overflow_sets_status_and_skips():
+    cfg = _cfg("full", 3, 2, 128)
+    case = DeviceCase(cfg, [10, 20, 30], seed=1, extra_cap=0)
+    case.cache.seq_lens.copy_(case.cache.seq_cap)             # every cache full
+    case.cache.seq_lens[1] = 20                                # ...except sequence 1 (cap 21)
+    before = (case.cache.k.clone(), case.cache.v.clone())
+    rpart.fd_kv_append(case.cache.desc, case.k_new, case.v_new)
+    torch.cuda.synchronize()
+    assert rpart.fd_read_status(case.cache.desc, clear=True) == rpart.FD_ST_CAPACITY
+    assert rpart.fd_read_status(case.cache.desc) == 0
+    assert case.cache.seq_lens.cpu().tolist() == [case.cache.caps[0], 21, case.cache.caps[2]]
+    k1 = case.cache.block("K", 1)
+    assert torch.equal(k1[:, 20, :], case.k_new[1])
+    for b in (0, 2):
+        n = cfg.H * case.cache.caps[b] * cfg.d
+        o = case.cache.offs[b]
+        assert torch.equal(case.cache.k[o:o + n], before[0][o:o + n])
+        assert torch.equal(case.cache.v[o:o + n], before[1][o:o + n])
+
+
+def test_bad_length_is_clamped_and_flagged():
+    cfg = _cfg("bad", 2, 2, 128)
+    case = DeviceCase(cfg, [50, 60], seed=1)
+    case.cache.seq_lens[0] = 10_000                            # beyond capacity
+    rpart.fd_rpart_decode(case.cache.desc, case.q, case.out, case.ws)
+    torch.cuda.synchronize()
+    assert rpart.fd_read_status(case.cache.desc, clear=True) & rpart.FD_ST_BADLEN
+    assert torch.isfinite(case.out.float()).all()
+
+
+def test_reset_drops_sequences():
+    cfg = _cfg("reset", 4, 2, 64)
+    case = DeviceCase(cfg, [100, 200, 300, 400], seed=1)
+    rpart.fd_kv_reset(case.cache.desc, torch.tensor([2, 0, 99, -1], dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert case.cache.seq_lens.cpu().tolist() == [0, 200, 0, 400]
+    check_step(case)                                           # dropped ones restart at 1 token
+    assert case.cache.seq_lens.cpu().tolist() == [1, 201, 1, 401]
+    rpart.fd_kv_reset(case.cache.desc)
+    torch.cuda.synchronize()
+    assert case.cache.seq_lens.cpu().tolist() == [0, 0, 0, 0]
+
+
+def test_append_preserves_special_bit_patterns():
+    cfg = _cfg("bits", 2, 2, 64)
+    case = DeviceCase(cfg, [3, 0], seed=1)
+    pat = torch.tensor([0x8000, 0x0001, 0x7E01, 0x7C00, 0x03FF, 0xFE55, 0xFC00, 0x0000],
+                       dtype=torch.int32).to(torch.int16)
+    case.k_new.view(torch.int16)[0, 0, :8] = pat.cuda()
+    case.v_new.view(torch.int16)[1, 1, 8:16] = pat.cuda()
+    rpart.fd_kv_append(case.cache.desc, case.k_new, case.v_new)
+    torch.cuda.synchronize()
+    assert torch.equal(case.cache.block("K", 0)[:, 3, :].view(torch.int16), case.k_new[0].view(torch.int16))
+    assert torch.equal(case.cache.block("V", 1)[:, 0, :].view(torch.int16), case.v_new[1].view(torch.int16))
+
+
+def test_subnormal_inputs_are_honoured():
+    """fp16 subnormals are exact in fp32 and must not be flushed: with every V a
+    subnormal, the output (their weighted mean) is non-zero."""
+    cfg = _cfg("sub", 1, 1, 128)
+    L = 200
+    case = DeviceCase(cfg, [L], seed=1)
+    case.cache.block("V", 0).view(torch.int16)[:, :L, :] = 0x0200       # 2^-15
+    case.v_new.view(torch.int16)[:] = 0x0200
+    check_step(case)
+    assert torch.all(case.out.view(torch.int16) == 0x0200)
+
+
+def test_invalid_arguments_enqueue_nothing():
+    cfg = _cfg("inval", 2, 2, 128)
+    case = DeviceCase(cfg, [5, 6], seed=1)
+    with pytest.raises(rpart.FdError):
+        rpart.fd_rpart_decode(case.cache.desc, None, case.out, case.ws)
+    with pytest.raises(rpart.FdError):
+        rpart.fd_rpart_decode(case.cache.desc, case.q.view(-1)[1:], case.out, case.ws)   # misaligned
+    with pytest.raises(rpart.FdError):
+        rpart.fd_rpart_decode(case.cache.desc, case.q, case.out, case.ws[1:])            # misaligned
+    bad = rpart.fd_kv_desc.from_buffer_copy(case.cache.desc)
+    bad.d = 96
+    with pytest.raises(rpart.FdError):
+        rpart.fd_kv_append(bad, case.k_new, case.v_new)
+    torch.cuda.synchronize()
+    assert case.cache.seq_lens.cpu().tolist() == [5, 6]
