@@ -1,0 +1,167 @@
+#!/usr/bin/env python3
+"""Throughput of the R-Part decode step on one MI355X.
+
+A step is one pass of the whole hot path over one batch: restore the cached
+lengths, append the new k/v rows, plan the ragged split, stream K/V (split-K
+partial attention), merge.  Inputs are synthetic, seeded, resident in HBM before
+the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2_7b_uniform]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "R-Part decode attention: achieved KV HBM GB/s (% of peak) and sequences/sec"
+HBM_PEAK_GBPS = 8000.0
+
+
+def build_case(cfg, lens, seed, chunk_tokens, growth=8):
+    import torch
+    from paper_2403_11421_amd import workloads as W
+    from paper_2403_11421_amd.kvcache import KVCache
+
+    dev = torch.device("cuda:0")
+    cache = KVCache(cfg.B, cfg.H, cfg.d, [L + growth for L in lens], dev, chunk_tokens)
+    for b, L in enumerate(lens):
+        if L:
+            cache.fill("K", b, W.gen_cache_block(cfg, "K", b, L, seed, dev))
+            cache.fill("V", b, W.gen_cache_block(cfg, "V", b, L, seed, dev))
+    cache.set_lens(lens)
+    vec = {w: W.gen_vectors(cfg, w, seed, dev) for w in ("q", "k_new", "v_new")}
+    return cache, vec
+
+
+def cpu_baseline(cfg, cache, vec, lens_after, n_sample):
+    """Time the fp64 oracle (as it stands) on a sample of this workload's sequences."""
+    import numpy as np
+    import torch
+    from oracle import rpart_oracle as O
+
+    threads = max(1, min(16, os.cpu_count() or 1))
+    n_sample = min(n_sample, cfg.B)
+    step = max(1, cfg.B // n_sample)
+    batch = list(range(0, cfg.B, step))[:n_sample]
+
+    def host(t):
+        return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
+
+    K = [host(cache.block("K", b).permute(1, 0, 2)) for b in batch]
+    V = [host(cache.block("V", b).permute(1, 0, 2)) for b in batch]
+    hl = np.asarray([lens_after[b] for b in batch], dtype=np.int32)
+    q = host(vec["q"][torch.tensor(batch, device=vec["q"].device)])
+    t0 = time.perf_counter()
+    O.rpart_decode(K, V, hl, q, nthreads=threads)
+    dt = time.perf_counter() - t0
+    kv_bytes = cfg.bytes_per_token() * int(hl.sum())
+    return {
+        "value": kv_bytes / dt / 1e9, "unit": "GB/s", "cores": min(threads, len(batch)),
+        "kind": "oracle",
+        "sample": f"{len(batch)} of {cfg.B} sequences (every {step}th), all {cfg.H} heads, "
+                  f"{int(hl.sum())} cached tokens, decode only, {dt:.2f} s wall",
+        "seq_per_s": len(batch) / dt,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="c2_7b_uniform")
+    ap.add_argument("--seed", type=int, default=None)
+    ap.add_argument("--chunk-tokens", type=int, default=0, help="split-K chunk length, 0 = library's choice")
+    ap.add_argument("--cpu-sample", type=int, default=48, help="sequences timed on the CPU oracle (0 = skip)")
+    args = ap.parse_args()
+
+    if args.gpus != 1:
+        print("bench.py: this build runs the R-Part on ONE GPU; sequences are independent, so more "
+              "GPUs would each run this same kernel on their share. Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2403_11421_amd import rpart, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    rpart.load()                                   # fails loudly when the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config]
+    seed = W.DEFAULT_SEED if args.seed is None else args.seed
+    lens = W.seq_lens(cfg, seed)
+    n_tok = W.total_tokens_after_append(lens)
+    kv_bytes = cfg.bytes_per_token() * n_tok       # algorithmic bytes: every cached K and V row once
+
+    cache, vec = build_case(cfg, lens, seed, args.chunk_tokens)
+    out = torch.empty_like(vec["q"])
+    ws = cache.workspace(n_tok)
+    lens0 = cache.seq_lens.clone()
+    desc = cache.desc
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+
+    def step(pair=None):
+        cache.seq_lens.copy_(lens0)                # every step is the quoted config: L cached + 1 appended
+        rpart.fd_kv_append(desc, vec["k_new"], vec["v_new"])
+        rpart.fd_rpart_plan(desc, ws)
+        if pair:
+            pair[0].record()
+        rpart.fd_rpart_partial(desc, vec["q"], out, ws)
+        if pair:
+            pair[1].record()
+        rpart.fd_rpart_merge(desc, out, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    assert rpart.fd_read_status(desc) == 0
+    plan = rpart.fd_plan_info(ws)
+    assert plan["total_tokens"] == n_tok, (plan, n_tok)
+    assert bool(torch.isfinite(out.float()).all())
+
+    ms_step = dt / args.steps * 1e3
+    part_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    value = kv_bytes / (ms_step * 1e-3) / 1e9
+    achieved = kv_bytes / (part_ms * 1e-3) / 1e9
+
+    res = {
+        "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} d={cfg.d} fp16 KV, "
+                               f"{n_tok} cached tokens after append, 1 layer",
+                   "B": cfg.B, "H": cfg.H, "d": cfg.d, "total_tokens": n_tok,
+                   "kv_bytes_per_step": kv_bytes, "seed": seed, "plan": plan},
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "seq_per_s": cfg.B / (ms_step * 1e-3),
+        "seq_per_s_whole_model": cfg.B / (ms_step * 1e-3) / cfg.n_layers,
+        "ns_per_cached_token": ms_step * 1e6 / n_tok,
+        "roofline": {"bound": "hbm", "kernel": "rpart_partial_kernel", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
+                     "avg_kernel_ms": part_ms, "traffic": None},
+    }
+    if args.cpu_sample > 0:
+        res["cpu_baseline"] = cpu_baseline(cfg, cache, vec, [L + 1 for L in lens], args.cpu_sample)
+    print(json.dumps(res))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
