@@ -23,7 +23,6 @@ namespace {
 constexpr int kVersion = 100;          // 0.1.0
 constexpr int kWaves = 4;              // waves per workgroup of the streaming kernel
 constexpr int kThreads = kWaves * 64;
-constexpr int kGranule = 64;           // chunk boundaries are multiples of this many tokens
 constexpr int kPlanThreads = 1024;
 constexpr int kHdrInts = 64;           // 256-byte header
 constexpr float kNegBig = -1.0e30f;    // "no token seen yet" running max (finite: no inf-inf)
@@ -110,7 +109,8 @@ __global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, const int32_t *_
 // ---------------------------------------------------------------------------
 // Planner: one workgroup.  Reads the ragged lengths on the device, picks the
 // chunk length, and writes the work-item table.  Sequence b with L_b tokens is
-// cut into n_b = ceil(L_b / T) chunks of equal length rounded up to the granule.
+// cut into n_b = ceil(L_b / T) chunks of equal length rounded up to the granule
+// (the streaming kernel's workgroup block, so only a sequence's last chunk is ragged).
 // ---------------------------------------------------------------------------
 __device__ inline int block_sum(int v, int *sm)
 {
@@ -133,7 +133,7 @@ __device__ inline int clamp_len(int L, int cap, int *bad)
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
-    int32_t *__restrict__ status, int B, int H, int chunk_req, int grid, int max_items,
+    int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid, int max_items,
     int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
     int4 *__restrict__ items)
 {
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         long long t = units / ((long long)grid * 32);
         T = (int)(t < 128 ? 128 : (t > 1024 ? 1024 : t));
     }
-    T = (T + kGranule - 1) / kGranule * kGranule;
+    T = (T + granule - 1) / granule * granule;
 
     int count;
     for (;;) {
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         nchunk[b] = n;
         if (n > 0) {
             int len = (L + n - 1) / n;
-            len = (len + kGranule - 1) / kGranule * kGranule;   // <= T, so (n-1)*len < L
+            len = (len + granule - 1) / granule * granule;      // <= T, so (n-1)*len < L
             for (int k = 0; k < n; ++k) {
                 const int t0 = k * len;
                 const int t1 = min(L, t0 + len);
@@ -236,6 +236,9 @@ __device__ inline float row_sum(float x)
     return x;
 }
 
+// keeps the instruction scheduler from sinking a tile's prefetch loads down to their uses
+__device__ inline void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ inline half8 ld_stream(const char *p)
@@ -243,37 +246,45 @@ __device__ inline half8 ld_stream(const char *p)
     return __builtin_nontemporal_load(reinterpret_cast<const half8 *>(p));
 }
 
+// One tile = this wave's share of a workgroup block.  A block is kWaves * NL
+// consecutive wave loads (1 KB each) of the K stream and of the V stream; wave w
+// takes loads w, w + kWaves, ...: the workgroup reads the block as one contiguous
+// run with its waves interleaved at 1 KB, and every wave gets the same number of
+// loads whatever the chunk length.
 template <int D, int NL>
 struct Tile {
-    static constexpr int LPR = D / 8;          // lanes per row
-    static constexpr int RPW = 64 / LPR;       // rows (tokens) per wave load
-    static constexpr int TOK = RPW * NL;       // tokens per tile
-    static constexpr int BYTES = TOK * D * 2;  // bytes of K (or V) per tile
+    static constexpr int LPR = D / 8;                    // lanes per row
+    static constexpr int RPW = 64 / LPR;                 // rows (tokens) per wave load
+    static constexpr int STRIDE = kWaves * 1024;         // bytes between a wave's consecutive loads
+    static constexpr int TSTEP = kWaves * RPW;           // tokens between a wave's consecutive loads
+    static constexpr int BLK_TOK = NL * TSTEP;           // tokens per workgroup block
+    static constexpr int BLK_BYTES = NL * STRIDE;        // bytes of K (or V) per workgroup block
     half8 k[NL], v[NL];
 
     __device__ inline void load(const char *kp, const char *vp)
     {
 #pragma unroll
-        for (int j = 0; j < NL; ++j) k[j] = ld_stream(kp + j * 1024);
+        for (int j = 0; j < NL; ++j) k[j] = ld_stream(kp + j * STRIDE);
 #pragma unroll
-        for (int j = 0; j < NL; ++j) v[j] = ld_stream(vp + j * 1024);
+        for (int j = 0; j < NL; ++j) v[j] = ld_stream(vp + j * STRIDE);
     }
 
-    // ragged tail: rows at or beyond `rem` re-read row rem-1 (in bounds) and are masked later
-    __device__ inline void load_tail(const char *kp, const char *vp, int row, int rem)
+    // ragged last block of `rem` tokens: a lane whose token (tok0 + j*TSTEP) is at or beyond
+    // `rem` re-reads token rem-1 (in bounds) and is masked in update<true>
+    __device__ inline void load_tail(const char *kp, const char *vp, int tok0, int rem)
     {
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            const int t = j * RPW + row;
+            const int t = j * TSTEP + tok0;
             const int back = t < rem ? 0 : (t - (rem - 1)) * (D * 2);
-            k[j] = ld_stream(kp + j * 1024 - back);
-            v[j] = ld_stream(vp + j * 1024 - back);
+            k[j] = ld_stream(kp + j * STRIDE - back);
+            v[j] = ld_stream(vp + j * STRIDE - back);
         }
     }
 
     template <bool MASKED>
     __device__ inline void update(const float (&q)[8], float &m, float &l, float (&acc)[8],
-                                  int row, int rem) const
+                                  int tok0, int rem) const
     {
         float s[NL];
 #pragma unroll
@@ -282,7 +293,7 @@ struct Tile {
 #pragma unroll
             for (int i = 0; i < 8; ++i) a = __builtin_fmaf((float)k[j][i], q[i], a);
             a = row_sum<LPR>(a);
-            if (MASKED && j * RPW + row >= rem) a = kNegBig;
+            if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
             s[j] = a;
         }
         float tm = s[0];
@@ -296,7 +307,7 @@ struct Tile {
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             float p = fast_exp2(s[j] - mn);
-            if (MASKED && j * RPW + row >= rem) p = 0.f;
+            if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
             l += p;
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(p, (float)v[j][i], acc[i]);
@@ -338,8 +349,8 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
         const int b = it.x, t0 = it.y, t1 = it.z, nch = it.w;
         const int cap = seq_cap[b];
         const int64_t row0 = seq_off[b] + ((int64_t)h * cap + t0) * D;      // elements
-        const char *kp = k_base + row0 * 2 + lane * 16;
-        const char *vp = v_base + row0 * 2 + lane * 16;
+        const char *kp = k_base + row0 * 2 + tid * 16;     // wave w starts at its 1 KB slot
+        const char *vp = v_base + row0 * 2 + tid * 16;
 
         float qf[8];
         {
@@ -353,27 +364,48 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
         const int ntok = t1 - t0;
-        const int n_full = ntok / T::TOK;
-        const int rem = ntok - n_full * T::TOK;
+        const int n_blk = ntok / T::BLK_TOK;              // full workgroup blocks
+        const int rem = ntok - n_blk * T::BLK_TOK;        // tokens of the ragged last block
 
-        // full tiles w, w+4, ... : ping-pong register buffers, next tile in flight while computing
-        int t = wave;
+        // ping-pong register buffers: the next block's loads are in flight while the current
+        // one is consumed.  The loop body is branch-free so that the wait counters leave
+        // the prefetch outstanding.
+        const char *kt = kp;
+        const char *vt = vp;
         T A, Bf;
-        if (t < n_full) A.load(kp + (int64_t)t * T::BYTES, vp + (int64_t)t * T::BYTES);
-        while (t < n_full) {
-            int tn = t + kWaves;
-            if (tn < n_full) Bf.load(kp + (int64_t)tn * T::BYTES, vp + (int64_t)tn * T::BYTES);
-            A.template update<false>(qf, m, l, acc, row, 0);
-            t = tn;
-            if (t >= n_full) break;
-            tn = t + kWaves;
-            if (tn < n_full) A.load(kp + (int64_t)tn * T::BYTES, vp + (int64_t)tn * T::BYTES);
-            Bf.template update<false>(qf, m, l, acc, row, 0);
-            t = tn;
+        if (n_blk > 0) {
+            A.load(kt, vt);
+            int i = 0;
+            while (i + 2 < n_blk) {
+                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES);
+                sched_fence();
+                A.template update<false>(qf, m, l, acc, 0, 0);
+                sched_fence();
+                A.load(kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES);
+                sched_fence();
+                Bf.template update<false>(qf, m, l, acc, 0, 0);
+                sched_fence();
+                kt += 2 * T::BLK_BYTES;
+                vt += 2 * T::BLK_BYTES;
+                i += 2;
+            }
+            if (i + 1 < n_blk) {
+                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES);
+                sched_fence();
+                A.template update<false>(qf, m, l, acc, 0, 0);
+                sched_fence();
+                Bf.template update<false>(qf, m, l, acc, 0, 0);
+            } else {
+                A.template update<false>(qf, m, l, acc, 0, 0);
+            }
         }
-        if (rem > 0 && wave == (n_full % kWaves)) {
-            A.load_tail(kp + (int64_t)n_full * T::BYTES, vp + (int64_t)n_full * T::BYTES, row, rem);
-            A.template update<true>(qf, m, l, acc, row, rem);
+        if (rem > 0) {
+            const int tok0 = wave * T::RPW + row;
+            if (wave * T::RPW < rem) {                    // this wave has at least one valid row
+                const int64_t o = (int64_t)n_blk * T::BLK_BYTES;
+                A.load_tail(kp + o, vp + o, tok0, rem);
+                A.template update<true>(qf, m, l, acc, tok0, rem);
+            }
         }
 
         // combine the rows of this wave (each 16- or 8-lane row saw different tokens)
@@ -491,26 +523,23 @@ int check_ws(const fd_kv_desc *d, const void *ws, size_t ws_bytes, WsLayout *w)
     return FD_OK;
 }
 
-template <int D>
-const void *partial_fn() { return (const void *)rpart_partial_kernel<D, kTileLoads>; }
+// tokens per workgroup block of the streaming kernel = chunk granule of the planner
+int block_tokens(int d) { return kWaves * kTileLoads * (d == 128 ? 4 : 8); }
 
-// persistent grid: every workgroup that can be resident at once, queried once per process
-int persistent_grid(int d)
+// Persistent grid: one workgroup per compute unit.  Measured on MI355X, 4 waves per CU
+// with 16-32 KB of loads in flight each already saturate HBM, and a second resident
+// workgroup per CU lowers the achieved bandwidth by 1-2 %.
+int persistent_grid()
 {
-    static int grid[2] = {0, 0};
-    const int k = d == 128;
-    if (grid[k] == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
+    static int grid = 0;
+    if (grid == 0) {
+        int dev = 0, cus = 0;
         if (hipGetDevice(&dev) != hipSuccess) return 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             return 0;
-        const void *fn = k ? partial_fn<128>() : partial_fn<64>();
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kThreads, 0) != hipSuccess)
-            return 0;
-        if (per_cu < 1) per_cu = 1;
-        grid[k] = cus * per_cu;
+        grid = cus;
     }
-    return grid[k];
+    return grid;
 }
 
 int launched(void) { return hipGetLastError() == hipSuccess ? FD_OK : FD_EHIP; }
@@ -575,12 +604,12 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     WsLayout w;
     rc = check_ws(desc, workspace, workspace_bytes, &w);
     if (rc != FD_OK) return rc;
-    const int grid = persistent_grid(desc->d);
+    const int grid = persistent_grid();
     if (grid <= 0) return FD_EHIP;
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, grid, (int)w.max_items, (int32_t *)ws,
+                       desc->chunk_tokens, block_tokens(desc->d), grid, (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items));
     return launched();
@@ -596,7 +625,7 @@ int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
     WsLayout w;
     rc = check_ws(desc, workspace, workspace_bytes, &w);
     if (rc != FD_OK) return rc;
-    const int grid = persistent_grid(desc->d);
+    const int grid = persistent_grid();
     if (grid <= 0) return FD_EHIP;
     char *ws = (char *)workspace;
     // scores are kept in the base-2 exponent domain: exp(x) = 2^(x * log2 e)

@@ -13,20 +13,13 @@ import torch
 from . import rpart
 
 
-def _capacity(tokens: int) -> int:
-    """Odd capacity: consecutive heads' streams then never start a power-of-two
-    number of bytes apart, which would pile concurrent streams onto the same
-    HBM channels."""
-    return int(tokens) | 1
-
-
 class KVCache:
     def __init__(self, B: int, H: int, d: int, capacities: Sequence[int], device="cuda",
                  chunk_tokens: int = 0):
         assert len(capacities) == B and d in (64, 128)
         self.B, self.H, self.d = B, H, d
         self.device = torch.device(device)
-        self.caps = [_capacity(c) for c in capacities]
+        self.caps = [max(1, int(c)) for c in capacities]
         offs, o = [], 0
         for c in self.caps:
             offs.append(o)

@@ -41,8 +41,10 @@ def test_edge_lengths_all_chunk_sizes(d, chunk):
     info = rpart.fd_plan_info(case.ws)
     assert info["total_tokens"] == sum(EDGE_LENS) + len(EDGE_LENS)
     if chunk:
-        assert info["chunk_tokens"] == max(64, chunk)
-        assert info["items"] == sum(math.ceil((L + 1) / max(64, chunk)) for L in EDGE_LENS)
+        granule = 128 if d == 128 else 256           # tokens per workgroup block of the streaming kernel
+        T = -(-chunk // granule) * granule
+        assert info["chunk_tokens"] == T
+        assert info["items"] == sum(math.ceil((L + 1) / T) for L in EDGE_LENS)
 
 
 @pytest.mark.parametrize("d", [128, 64])
@@ -123,17 +125,17 @@ def test_chunk_size_independence_and_determinism():
 
 def test_capacity_overflow_sets_status_and_skips():
     cfg = _cfg("full", 3, 2, 128)
-    case = DeviceCase(cfg, [10, 20, 30], seed=1, extra_cap=0)
+    case = DeviceCase(cfg, [10, 20, 30], seed=1, extra_cap=1)   # capacities 11, 21, 31
     case.cache.seq_lens.copy_(case.cache.seq_cap)             # every cache full
-    case.cache.seq_lens[1] = 20                                # ...except sequence 1 (cap 21)
+    case.cache.seq_lens[1] = 20                                # ...except sequence 1
     before = (case.cache.k.clone(), case.cache.v.clone())
     rpart.fd_kv_append(case.cache.desc, case.k_new, case.v_new)
     torch.cuda.synchronize()
     assert rpart.fd_read_status(case.cache.desc, clear=True) == rpart.FD_ST_CAPACITY
     assert rpart.fd_read_status(case.cache.desc) == 0
-    assert case.cache.seq_lens.cpu().tolist() == [case.cache.caps[0], 21, case.cache.caps[2]]
-    k1 = case.cache.block("K", 1)
-    assert torch.equal(k1[:, 20, :], case.k_new[1])
+    assert case.cache.seq_lens.cpu().tolist() == [11, 21, 31]
+    assert torch.equal(case.cache.block("K", 1)[:, 20, :], case.k_new[1])
+    assert torch.equal(case.cache.block("V", 1)[:, 20, :], case.v_new[1])
     for b in (0, 2):
         n = cfg.H * case.cache.caps[b] * cfg.d
         o = case.cache.offs[b]
