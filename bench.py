@@ -79,7 +79,10 @@ def main() -> int:
     ap.add_argument("--config", default="c2_7b_uniform")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--chunk-tokens", type=int, default=0, help="split-K chunk length, 0 = library's choice")
-    ap.add_argument("--cpu-sample", type=int, default=48, help="sequences timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=96, help="sequences timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB before the steps, as the "
+                         "known-size reference dispatch for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -121,6 +124,14 @@ def main() -> int:
             pair[1].record()
         rpart.fd_rpart_merge(desc, out, ws)
 
+    if args.copy_calibration_mib > 0:
+        src = torch.ones(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                             # reads and writes exactly that many bytes
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -157,6 +168,17 @@ def main() -> int:
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
                      "avg_kernel_ms": part_ms, "traffic": None},
     }
+    # the device's pure-read ceiling, timed beside the kernel over the K slab (context for `frac`)
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    nread = rpart.fd_hbm_read_probe(cache.k, sink)
+    e0.record()
+    for _ in range(5):
+        rpart.fd_hbm_read_probe(cache.k, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    res["roofline"]["read_only_ceiling_gbps"] = nread * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
     if args.cpu_sample > 0:
         res["cpu_baseline"] = cpu_baseline(cfg, cache, vec, [L + 1 for L in lens], args.cpu_sample)
     print(json.dumps(res))

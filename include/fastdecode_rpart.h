@@ -146,6 +146,16 @@ int fd_read_status(const fd_kv_desc *desc, int32_t *host_status, int clear, void
  */
 int fd_plan_info(const void *workspace, int32_t info[4], void *stream);
 
+/*
+ * Measurement aid, not part of the R-Part: enqueue a kernel that only reads
+ * `buf` (device, 16-byte aligned) with the same 128-bit streaming loads as the
+ * attention kernel, so a harness can time the device's pure-read ceiling next to
+ * it.  *bytes_read (host) receives the number of bytes the kernel reads, a
+ * multiple of 32 KiB per workgroup not above `bytes`.  `sink` is a device int32
+ * the kernel may write.  FD_EINVAL if `bytes` is too small for one pass.
+ */
+int fd_hbm_read_probe(const void *buf, size_t bytes, int32_t *sink, size_t *bytes_read, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

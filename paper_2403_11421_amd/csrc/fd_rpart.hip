@@ -495,6 +495,30 @@ __global__ __launch_bounds__(256) void rpart_merge_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// Pure-read probe: what a kernel that only streams memory reaches on this device,
+// with the same 128-bit non-temporal loads.  Each workgroup walks a private
+// contiguous region, 8 loads per lane in flight.
+// ---------------------------------------------------------------------------
+typedef unsigned int uint4v __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint4v *__restrict__ p,
+                                                             size_t iters_per_wg,
+                                                             int32_t *__restrict__ sink)
+{
+    constexpr int U = 8;
+    const uint4v *q = p + (size_t)blockIdx.x * iters_per_wg * (256 * U) + threadIdx.x;
+    unsigned acc = 0;
+    for (size_t i = 0; i < iters_per_wg; ++i, q += 256 * U) {
+        uint4v v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(q + u * 256);
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x9E3779B9u) sink[0] = (int32_t)acc;     // keeps the loads alive
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 constexpr int kTileLoads = 8;                          // wave loads of K (and of V) per tile
@@ -702,6 +726,20 @@ int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, cons
     rc = fd_kv_append(desc, k_new, v_new, stream);
     if (rc != FD_OK) return rc;
     return fd_rpart_decode(desc, q, out, workspace, workspace_bytes, stream);
+}
+
+int fd_hbm_read_probe(const void *buf, size_t bytes, int32_t *sink, size_t *bytes_read, void *stream)
+{
+    if (!buf || !sink || !bytes_read || !aligned(buf, 16)) return FD_EINVAL;
+    const int grid = 2 * persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    const size_t per_iter = 256 * 8 * 16;                       // bytes per workgroup iteration
+    const size_t iters = bytes / per_iter / (size_t)grid;
+    *bytes_read = iters * per_iter * (size_t)grid;
+    if (iters == 0) return FD_EINVAL;
+    hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4v *)buf, iters, sink);
+    return launched();
 }
 
 int fd_read_status(const fd_kv_desc *desc, int32_t *host_status, int clear, void *stream)

@@ -75,13 +75,15 @@ def load() -> ctypes.CDLL:
     lib.fd_read_status.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.c_int, _vp]
     lib.fd_plan_info.restype = ctypes.c_int
     lib.fd_plan_info.argtypes = [_vp, ctypes.POINTER(ctypes.c_int32), _vp]
+    lib.fd_hbm_read_probe.restype = ctypes.c_int
+    lib.fd_hbm_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_size_t), _vp]
     _lib = lib
     return lib
 
 
 EXPORTS = ("fd_version", "fd_strerror", "fd_workspace_bytes", "fd_kv_append", "fd_rpart_decode",
            "fd_rpart_plan", "fd_rpart_partial", "fd_rpart_merge", "fd_rpart_step", "fd_kv_reset",
-           "fd_read_status", "fd_plan_info")
+           "fd_read_status", "fd_plan_info", "fd_hbm_read_probe")
 
 
 def version() -> int:
@@ -165,3 +167,12 @@ def fd_plan_info(workspace: torch.Tensor) -> dict:
     info = (ctypes.c_int32 * 4)()
     _check(load().fd_plan_info(workspace.data_ptr(), info, _stream()), "fd_plan_info")
     return {"items": info[0], "chunk_tokens": info[1], "total_tokens": info[2], "grid": info[3]}
+
+
+def fd_hbm_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> int:
+    """Enqueue the pure-read probe over `buf`; returns the bytes it reads."""
+    n = ctypes.c_size_t(0)
+    _check(load().fd_hbm_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(),
+                                    sink.data_ptr(), ctypes.byref(n), _stream()),
+           "fd_hbm_read_probe")
+    return int(n.value)

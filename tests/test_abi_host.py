@@ -1,0 +1,74 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header declares,
+and rejects bad arguments on the host before enqueuing anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2403_11421_amd import rpart
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                      "include", "fastdecode_rpart.h")
+
+
+def _declared():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(fd_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = rpart.load()
+    names = _declared()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(rpart.EXPORTS)
+
+
+def test_version_and_strerror():
+    assert rpart.version() >= 100
+    assert rpart.strerror(rpart.FD_OK) == "ok"
+    for code in (rpart.FD_EINVAL, rpart.FD_EWORKSPACE, rpart.FD_EHIP, -99):
+        assert isinstance(rpart.strerror(code), str) and rpart.strerror(code)
+
+
+def test_workspace_bytes():
+    assert rpart.workspace_bytes(256, 32, 96, 10) == 0          # head_dim must be 64 or 128
+    assert rpart.workspace_bytes(-1, 32, 128, 10) == 0
+    assert rpart.workspace_bytes(1, 0, 128, 10) == 0
+    base = rpart.workspace_bytes(256, 32, 128, 0)
+    per_item = 16 + 32 * 130 * 4
+    assert base >= 256 * per_item and base % 256 == 0
+    more = rpart.workspace_bytes(256, 32, 128, 256 * 2049)
+    assert more - base >= (256 * 2049 // 256) * per_item
+    assert rpart.workspace_bytes(256, 32, 64, 0) < base
+
+
+def test_host_side_argument_checks_need_no_gpu():
+    lib = rpart.load()
+    null = ctypes.POINTER(rpart.fd_kv_desc)()
+    assert lib.fd_kv_append(null, None, None, None) == rpart.FD_EINVAL
+    assert lib.fd_rpart_decode(null, None, None, None, 0, None) == rpart.FD_EINVAL
+    assert lib.fd_rpart_step(null, None, None, None, None, None, 0, None) == rpart.FD_EINVAL
+    assert lib.fd_kv_reset(null, None, 0, None) == rpart.FD_EINVAL
+    assert lib.fd_plan_info(None, None, None) == rpart.FD_EINVAL
+    d = rpart.fd_kv_desc(B=2, H=4, d=96)
+    assert lib.fd_kv_append(ctypes.byref(d), None, None, None) == rpart.FD_EINVAL
+    d = rpart.fd_kv_desc(B=2, H=4, d=128)                      # null cache pointers
+    assert lib.fd_rpart_plan(ctypes.byref(d), None, 0, None) == rpart.FD_EINVAL
+    d = rpart.fd_kv_desc(B=0, H=4, d=128)                      # empty batch: nothing to do
+    assert lib.fd_kv_append(ctypes.byref(d), None, None, None) == rpart.FD_OK
+    assert lib.fd_rpart_decode(ctypes.byref(d), None, None, None, 0, None) == rpart.FD_OK
+    # fake, aligned, never dereferenced on the host
+    d = rpart.fd_kv_desc(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 2, 4, 128, 0)
+    assert lib.fd_rpart_decode(ctypes.byref(d), 0x7000, 0x8000, 0x9000, 16, None) == rpart.FD_EWORKSPACE
+    assert lib.fd_rpart_decode(ctypes.byref(d), 0x7001, 0x8000, 0x9000, 1 << 30, None) == rpart.FD_EINVAL
+    d.chunk_tokens = -5
+    assert lib.fd_rpart_decode(ctypes.byref(d), 0x7000, 0x8000, 0x9000, 1 << 30, None) == rpart.FD_EINVAL
+
+
+def test_binding_raises_fd_error():
+    with pytest.raises(rpart.FdError) as e:
+        rpart._check(rpart.FD_EWORKSPACE, "x")
+    assert e.value.code == rpart.FD_EWORKSPACE and "workspace" in str(e.value)
