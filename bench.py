@@ -171,10 +171,12 @@ def main() -> int:
     # the device's pure-read ceiling, timed beside the kernel over the K slab (context for `frac`)
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    nread = rpart.fd_hbm_read_probe(cache.k, sink)
+    buf = cache.k if cache.k.numel() * 2 >= (1 << 30) else \
+        torch.zeros(1 << 31, dtype=torch.uint8, device="cuda")     # tiny configs: a 2 GiB stand-in
+    nread = rpart.fd_hbm_read_probe(buf, sink)
     e0.record()
     for _ in range(5):
-        rpart.fd_hbm_read_probe(cache.k, sink)
+        rpart.fd_hbm_read_probe(buf, sink)
     e1.record()
     torch.cuda.synchronize()
     res["roofline"]["read_only_ceiling_gbps"] = nread * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9

@@ -24,22 +24,27 @@ constexpr int kVersion = 100;          // 0.1.0
 constexpr int kWaves = 4;              // waves per workgroup of the streaming kernel
 constexpr int kThreads = kWaves * 64;
 constexpr int kPlanThreads = 1024;
+constexpr int kPhases = 4;             // starting points of the workgroups' walks through their rounds
 constexpr int kHdrInts = 64;           // 256-byte header
 constexpr float kNegBig = -1.0e30f;    // "no token seen yet" running max (finite: no inf-inf)
 
 // header words
-enum { HDR_NITEMS = 0, HDR_TICKET = 1, HDR_CHUNK = 2, HDR_TOKENS = 3, HDR_GRID = 4 };
+enum { HDR_NITEMS = 0, HDR_CHUNK = 2, HDR_TOKENS = 3, HDR_GRID = 4 };
 
 struct WsLayout {
     size_t off_item0;     // int32[B]  first item of sequence b
     size_t off_nchunk;    // int32[B]  chunks of sequence b
-    size_t off_items;     // int4[max_items]  {b, t0, t1, n_chunks_of_b}
-    size_t off_part;      // float[max_items][H][d+2]  {acc[d], m, l}
+    size_t off_items;     // int4[max_items]  {b, t0, t1, n_chunks_of_b}, chunks of a sequence adjacent
+    size_t off_order;     // int32[max_items] item indices, longest chunk first (the schedule)
+    size_t off_acc;       // float[max_items][H][d]  unnormalised weighted value sums (512 B records)
+    size_t off_ml;        // float[max_items][H][2]  {running max, sum of exponentials}
     int64_t max_items;
     size_t min_bytes;     // bytes needed for max_items == B
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline size_t ws_per_item(int H, int d) { return 16 + 4 + (size_t)H * (size_t)(d + 2) * 4; }
 
 inline WsLayout ws_layout(int B, int H, int d, size_t ws_bytes)
 {
@@ -50,17 +55,18 @@ inline WsLayout ws_layout(int B, int H, int d, size_t ws_bytes)
     w.off_nchunk = o;
     o = align_up(o + (size_t)B * 4, 256);
     w.off_items = o;
-    size_t per_item = 16 + (size_t)H * (size_t)(d + 2) * 4;
-    size_t slop = 512;                                   // alignment of the partial array
+    const size_t per_item = ws_per_item(H, d);
+    const size_t slop = 4 * 256;                         // alignment of the four arrays
     w.min_bytes = o + slop + (size_t)(B > 0 ? B : 1) * per_item;
-    if (ws_bytes < w.min_bytes) {
-        w.max_items = 0;
-        w.off_part = 0;
-        return w;
-    }
+    w.max_items = 0;
+    w.off_order = w.off_acc = w.off_ml = 0;
+    if (ws_bytes < w.min_bytes) return w;
     w.max_items = (int64_t)((ws_bytes - o - slop) / per_item);
     if (w.max_items > (int64_t)0x3FFFFFFF) w.max_items = 0x3FFFFFFF;
-    w.off_part = align_up(o + (size_t)w.max_items * 16, 256);
+    const size_t n = (size_t)w.max_items;
+    w.off_order = align_up(w.off_items + n * 16, 256);
+    w.off_acc = align_up(w.off_order + n * 4, 256);
+    w.off_ml = align_up(w.off_acc + n * (size_t)H * (size_t)d * 4, 256);
     return w;
 }
 
@@ -108,10 +114,24 @@ __global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, const int32_t *_
 
 // ---------------------------------------------------------------------------
 // Planner: one workgroup.  Reads the ragged lengths on the device, picks the
-// chunk length, and writes the work-item table.  Sequence b with L_b tokens is
-// cut into n_b = ceil(L_b / T) chunks of equal length rounded up to the granule
-// (the streaming kernel's workgroup block, so only a sequence's last chunk is ragged).
+// chunk length, writes the work-item table and a static schedule.
+//
+// Splitting is kept to what load balance needs: every chunk state that has to
+// be written out and merged later costs far more than its bytes (result stores
+// interleaved with the read stream lower the achieved HBM bandwidth by several
+// per cent), so a sequence is cut only when it is longer than 1/16 of a
+// workgroup's share of the step.  Sequence b with L_b tokens is cut into
+// n_b = ceil(L_b / T) chunks of equal length rounded up to the granule.
+//
+// The schedule is static (a shared ticket counter was measured 4-5 % slower: the
+// atomic sits in the in-order return queue in front of the unit's first loads):
+// items are ordered longest first by a counting sort on their length, and the
+// streaming kernel deals (item, head) units to workgroups in snake order, which
+// is the longest-processing-time rule for units that are small against a
+// workgroup's share.
 // ---------------------------------------------------------------------------
+constexpr int kBuckets = 256;
+
 __device__ inline int block_sum(int v, int *sm)
 {
     // sum over the workgroup; result returned to all threads
@@ -131,13 +151,20 @@ __device__ inline int clamp_len(int L, int cap, int *bad)
     return L;
 }
 
+__device__ inline int length_bucket(int len, int T)
+{
+    int k = (int)(((long long)(T - len) * kBuckets) / T);   // longest chunks in bucket 0
+    return k < 0 ? 0 : (k >= kBuckets ? kBuckets - 1 : k);
+}
+
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
     int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid, int max_items,
     int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
-    int4 *__restrict__ items)
+    int4 *__restrict__ items, int32_t *__restrict__ order)
 {
     __shared__ int sm[kPlanThreads];
+    __shared__ int hist[kBuckets];
     const int tid = threadIdx.x;
     const int per = (B + kPlanThreads - 1) / kPlanThreads;   // sequences per thread (contiguous)
     const int b0 = tid * per;
@@ -148,15 +175,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int total = block_sum(mine, sm);
     if (bad) atomicOr(status, FD_ST_BADLEN);
 
-    // chunk length: explicit request, else aim at ~32 work units per resident
-    // workgroup so the tail of the dynamic schedule stays around a percent
     int T;
     if (chunk_req > 0) {
         T = chunk_req;
     } else {
-        const long long units = (long long)total * H;
-        long long t = units / ((long long)grid * 32);
-        T = (int)(t < 128 ? 128 : (t > 1024 ? 1024 : t));
+        const long long share = (long long)total * H / grid;    // token-heads per workgroup
+        long long t = share / 16;
+        T = (int)(t < 128 ? 128 : (t > (1 << 28) ? (1 << 28) : t));
     }
     T = (T + granule - 1) / granule * granule;
 
@@ -178,6 +203,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
         c += (L + T - 1) / T;
     }
+    if (tid < kBuckets) hist[tid] = 0;
     __syncthreads();
     sm[tid] = c;
     __syncthreads();
@@ -187,7 +213,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         sm[tid] += v;
         __syncthreads();
     }
-    int pos = sm[tid] - c;
+    const int first = sm[tid] - c;
+    int pos = first;
     for (int b = b0; b < b1; ++b) {
         const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
         const int n = (L + T - 1) / T;
@@ -199,14 +226,39 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
             for (int k = 0; k < n; ++k) {
                 const int t0 = k * len;
                 const int t1 = min(L, t0 + len);
-                if (pos + k < max_items) items[pos + k] = make_int4(b, t0, t1, n);
+                if (pos + k < max_items) {
+                    items[pos + k] = make_int4(b, t0, t1, n);
+                    atomicAdd(&hist[length_bucket(t1 - t0, T)], 1);
+                }
+            }
+        }
+        pos += n;
+    }
+    __syncthreads();
+    // bucket starts (exclusive scan of 256 counters by one thread), then scatter
+    if (tid == 0) {
+        int run = 0;
+        for (int k = 0; k < kBuckets; ++k) { const int n = hist[k]; hist[k] = run; run += n; }
+    }
+    __syncthreads();
+    pos = first;
+    for (int b = b0; b < b1; ++b) {
+        const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+        const int n = (L + T - 1) / T;
+        if (n > 0) {
+            int len = (L + n - 1) / n;
+            len = (len + granule - 1) / granule * granule;
+            for (int k = 0; k < n; ++k) {
+                const int t0 = k * len;
+                const int t1 = min(L, t0 + len);
+                if (pos + k < max_items)
+                    order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = pos + k;
             }
         }
         pos += n;
     }
     if (tid == 0) {
         hdr[HDR_NITEMS] = count <= max_items ? count : 0;
-        hdr[HDR_TICKET] = grid;          // tickets [0, grid) are taken statically by blockIdx
         hdr[HDR_CHUNK] = T;
         hdr[HDR_TOKENS] = total;
         hdr[HDR_GRID] = grid;
@@ -316,41 +368,79 @@ struct Tile {
     }
 };
 
+// Where a unit of work (one chunk of one head's stream) lives; uniform over the workgroup.
+struct Unit {
+    int64_t row0;            // element offset of the chunk's first row in the K / V slab
+    int ntok;                // tokens in the chunk; 0 = no unit
+    int b, h, item, nch;     // sequence, head, item index, chunks of the sequence
+};
+
 template <int D, int NL>
 __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
     const char *__restrict__ k_base, const char *__restrict__ v_base,
     const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
     const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
-    int32_t *__restrict__ hdr, const int4 *__restrict__ items, float *__restrict__ partials,
+    const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
+    const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
     float qscale)
 {
     using T = Tile<D, NL>;
     constexpr int LPR = T::LPR;
     __shared__ float sm_acc[kWaves][D];
     __shared__ float sm_m[kWaves], sm_l[kWaves];
-    __shared__ int sm_ticket;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int row = lane / LPR;
     const int col = lane % LPR;
-    const int n_tickets = hdr[HDR_NITEMS] * H;
+    const int n_units = hdr[HDR_NITEMS] * H;
+    const int W = gridDim.x, g = blockIdx.x;
 
-    int ticket = blockIdx.x;
-    while (ticket < n_tickets) {
-        // fetch the next ticket early; its latency hides behind this item's streaming
-        int next_ticket = 0;
-        if (tid == 0) next_ticket = atomicAdd(&hdr[HDR_TICKET], 1);
+    // Static snake schedule over units in longest-first order: in round k this workgroup
+    // owns unit k*W + g (even k) or k*W + W-1-g (odd k), which balances the token totals.
+    // The workgroups walk their rounds from kPhases different starting points, so that at
+    // any moment long and short units are in flight together: short units are dominated by
+    // latency, and letting every workgroup reach them at once would leave HBM idle (+3 % on
+    // exponentially distributed lengths).  More phases spread the reads over more of the
+    // cache at once, which costs about 1 % on uniform lengths; four keeps both.
+    const int n_rounds = (int)(((long long)n_units + W - 1) / W);
+    const int k_start = (int)((long long)(g % kPhases) * n_rounds / kPhases);
+    auto fetch = [&](int j) {
+        Unit u;
+        u.ntok = 0;
+        if (j < n_rounds) {
+            int k = k_start + j;
+            if (k >= n_rounds) k -= n_rounds;
+            const long long p = (long long)k * W + ((k & 1) ? W - 1 - g : g);
+            if (p < n_units) {
+                const int sidx = (int)(p / H);
+                const int item = order[sidx];
+                const int4 it = items[item];
+                u.h = (int)(p - (long long)sidx * H);
+                u.b = it.x;
+                u.item = item;
+                u.nch = it.w;
+                u.ntok = it.z - it.y;
+                u.row0 = seq_off[it.x] + ((int64_t)u.h * seq_cap[it.x] + it.y) * D;
+            }
+        }
+        return u;
+    };
 
-        const int item = ticket / H;
-        const int h = ticket - item * H;
-        const int4 it = items[item];
-        const int b = it.x, t0 = it.y, t1 = it.z, nch = it.w;
-        const int cap = seq_cap[b];
-        const int64_t row0 = seq_off[b] + ((int64_t)h * cap + t0) * D;      // elements
-        const char *kp = k_base + row0 * 2 + tid * 16;     // wave w starts at its 1 KB slot
-        const char *vp = v_base + row0 * 2 + tid * 16;
+    // only the last round can be incomplete, so at most one fetched unit is empty
+    int j = 0;
+    Unit cur = fetch(0);
+    if (cur.ntok == 0 && n_rounds > 1) cur = fetch(++j);
+    while (cur.ntok > 0) {
+        // the next unit's descriptor (three dependent scalar loads) is fetched while this
+        // unit streams
+        Unit nxt = fetch(++j);
+        if (nxt.ntok == 0 && j < n_rounds) nxt = fetch(++j);
+
+        const int b = cur.b, h = cur.h;
+        const char *kp = k_base + cur.row0 * 2 + tid * 16;     // wave w starts at its 1 KB slot
+        const char *vp = v_base + cur.row0 * 2 + tid * 16;
 
         float qf[8];
         {
@@ -363,7 +453,7 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
-        const int ntok = t1 - t0;
+        const int ntok = cur.ntok;
         const int n_blk = ntok / T::BLK_TOK;              // full workgroup blocks
         const int rem = ntok - n_blk * T::BLK_TOK;        // tokens of the ragged last block
 
@@ -425,10 +515,11 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
             for (int i = 0; i < 8; ++i) sm_acc[wave][lane * 8 + i] = acc[i];
         }
         if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; }
-        if (tid == 0) sm_ticket = next_ticket;
         __syncthreads();
 
-        // combine the waves; write the final output or this chunk's partial state
+        // combine the waves; write the final output or this chunk's partial state.  Stores
+        // are non-temporal: they are never re-read by this kernel, and plain stores were
+        // measured to cost the read stream about three times as much bandwidth.
         if (tid < D) {
             float M = sm_m[0];
 #pragma unroll
@@ -440,16 +531,19 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
                 L += a * sm_l[w];
                 o += a * sm_acc[w][tid];
             }
-            if (nch == 1) {
-                out[((int64_t)b * H + h) * D + tid] = (_Float16)(o / L);
+            if (cur.nch == 1) {
+                __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
             } else {
-                float *p = partials + ((int64_t)item * H + h) * (D + 2);
-                p[tid] = o;
-                if (tid == 0) { p[D] = M; p[D + 1] = L; }
+                const int64_t rec = (int64_t)cur.item * H + h;
+                __builtin_nontemporal_store(o, &part_acc[rec * D + tid]);
+                if (tid == 0) {
+                    __builtin_nontemporal_store(M, &part_ml[rec * 2]);
+                    __builtin_nontemporal_store(L, &part_ml[rec * 2 + 1]);
+                }
             }
         }
-        ticket = sm_ticket;
-        __syncthreads();               // LDS is reused by the next item
+        __syncthreads();               // LDS is reused by the next unit
+        cur = nxt;
     }
 }
 
@@ -460,7 +554,8 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
 template <int D>
 __global__ __launch_bounds__(256) void rpart_merge_kernel(
     const int32_t *__restrict__ item0, const int32_t *__restrict__ nchunk,
-    const float *__restrict__ partials, _Float16 *__restrict__ out, int B, int H)
+    const float *__restrict__ part_acc, const float *__restrict__ part_ml,
+    _Float16 *__restrict__ out, int B, int H)
 {
     constexpr int PER = D / 64;                       // output elements per lane
     const int lane = threadIdx.x & 63;
@@ -476,19 +571,18 @@ __global__ __launch_bounds__(256) void rpart_merge_kernel(
         for (int i = 0; i < PER; ++i) o[i] = (_Float16)0.f;
         return;
     }
-    const float *p0 = partials + ((int64_t)item0[b] * H + h) * (D + 2);
-    const int64_t stride = (int64_t)H * (D + 2);
+    const int64_t rec0 = (int64_t)item0[b] * H + h;   // chunk c of this (b,h) is record rec0 + c*H
     float M = kNegBig;
-    for (int c = 0; c < n; ++c) M = fmaxf(M, p0[c * stride + D]);
+    for (int c = 0; c < n; ++c) M = fmaxf(M, part_ml[(rec0 + (int64_t)c * H) * 2]);
     float L = 0.f, acc[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) acc[i] = 0.f;
     for (int c = 0; c < n; ++c) {
-        const float *p = p0 + c * stride;
-        const float w = fast_exp2(p[D] - M);
-        L += w * p[D + 1];
+        const int64_t rec = rec0 + (int64_t)c * H;
+        const float w = fast_exp2(part_ml[rec * 2] - M);
+        L += w * part_ml[rec * 2 + 1];
 #pragma unroll
-        for (int i = 0; i < PER; ++i) acc[i] += w * p[lane * PER + i];
+        for (int i = 0; i < PER; ++i) acc[i] += w * part_acc[rec * D + lane * PER + i];
     }
 #pragma unroll
     for (int i = 0; i < PER; ++i) o[i] = (_Float16)(acc[i] / L);
@@ -549,6 +643,8 @@ int check_ws(const fd_kv_desc *d, const void *ws, size_t ws_bytes, WsLayout *w)
 
 // tokens per workgroup block of the streaming kernel = chunk granule of the planner
 int block_tokens(int d) { return kWaves * kTileLoads * (d == 128 ? 4 : 8); }
+// chunk boundaries are multiples of this many tokens (one wave load of rows)
+int chunk_granule(int d) { return d == 128 ? 32 : 64; }
 
 // Persistent grid: one workgroup per compute unit.  Measured on MI355X, 4 waves per CU
 // with 16-32 KB of loads in flight each already saturate HBM, and a second resident
@@ -589,7 +685,7 @@ size_t fd_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t max_total_tok
 {
     if (B < 0 || H <= 0 || (d != 64 && d != 128) || max_total_tokens < 0) return 0;
     WsLayout w = ws_layout(B, H, d, 0);
-    const size_t per_item = 16 + (size_t)H * (size_t)(d + 2) * 4;
+    const size_t per_item = ws_per_item(H, d);
     const size_t extra = (size_t)((max_total_tokens + 255) / 256);
     return align_up(w.min_bytes + extra * per_item, 256);
 }
@@ -633,9 +729,9 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, block_tokens(desc->d), grid, (int)w.max_items, (int32_t *)ws,
+                       desc->chunk_tokens, chunk_granule(desc->d), grid, (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
-                       (int4 *)(ws + w.off_items));
+                       (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
     return launched();
 }
 
@@ -658,14 +754,16 @@ int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
         hipLaunchKernelGGL((rpart_partial_kernel<128, kTileLoads>), dim3(grid), dim3(kThreads), 0,
                            (hipStream_t)stream, (const char *)desc->k_base,
                            (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
-                           (const _Float16 *)q, (_Float16 *)out, desc->H, (int32_t *)ws,
-                           (const int4 *)(ws + w.off_items), (float *)(ws + w.off_part), qscale);
+                           (const _Float16 *)q, (_Float16 *)out, desc->H, (const int32_t *)ws,
+                           (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
+                           (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale);
     else
         hipLaunchKernelGGL((rpart_partial_kernel<64, kTileLoads>), dim3(grid), dim3(kThreads), 0,
                            (hipStream_t)stream, (const char *)desc->k_base,
                            (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
-                           (const _Float16 *)q, (_Float16 *)out, desc->H, (int32_t *)ws,
-                           (const int4 *)(ws + w.off_items), (float *)(ws + w.off_part), qscale);
+                           (const _Float16 *)q, (_Float16 *)out, desc->H, (const int32_t *)ws,
+                           (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
+                           (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale);
     return launched();
 }
 
@@ -685,11 +783,13 @@ int fd_rpart_merge(const fd_kv_desc *desc, void *out,
     if (desc->d == 128)
         hipLaunchKernelGGL(rpart_merge_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream,
                            (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
-                           (const float *)(ws + w.off_part), (_Float16 *)out, desc->B, desc->H);
+                           (const float *)(ws + w.off_acc), (const float *)(ws + w.off_ml),
+                           (_Float16 *)out, desc->B, desc->H);
     else
         hipLaunchKernelGGL(rpart_merge_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream,
                            (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
-                           (const float *)(ws + w.off_part), (_Float16 *)out, desc->B, desc->H);
+                           (const float *)(ws + w.off_acc), (const float *)(ws + w.off_ml),
+                           (_Float16 *)out, desc->B, desc->H);
     return launched();
 }
 

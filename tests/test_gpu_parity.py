@@ -41,7 +41,7 @@ def test_edge_lengths_all_chunk_sizes(d, chunk):
     info = rpart.fd_plan_info(case.ws)
     assert info["total_tokens"] == sum(EDGE_LENS) + len(EDGE_LENS)
     if chunk:
-        granule = 128 if d == 128 else 256           # tokens per workgroup block of the streaming kernel
+        granule = 32 if d == 128 else 64             # chunk boundaries: one wave load of rows
         T = -(-chunk // granule) * granule
         assert info["chunk_tokens"] == T
         assert info["items"] == sum(math.ceil((L + 1) / T) for L in EDGE_LENS)
