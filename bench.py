@@ -22,6 +22,23 @@ if ROOT not in sys.path:
 
 METRIC = "R-Part decode attention: achieved KV HBM GB/s (% of peak) and sequences/sec"
 HBM_PEAK_GBPS = 8000.0
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "rpart_partial_hbm_traffic.json")
+KERNEL_SRC = os.path.join(ROOT, "paper_2403_11421_amd", "csrc", "fd_rpart.hip")
+
+
+def counter_traffic(config_name):
+    """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc, or None
+    when no counters were taken for this config or the kernel source changed since."""
+    import hashlib
+    try:
+        rec = json.load(open(TRAFFIC_JSON))
+        sha = hashlib.sha256(open(KERNEL_SRC, "rb").read()).hexdigest()
+        if rec.get("source_sha256") != sha:
+            return None
+        return rec["configs"][config_name]["traffic_bytes"]
+    except (OSError, KeyError, ValueError):
+        return None
+
 
 
 def build_case(cfg, lens, seed, chunk_tokens, growth=8):
@@ -166,7 +183,8 @@ def main() -> int:
         "ns_per_cached_token": ms_step * 1e6 / n_tok,
         "roofline": {"bound": "hbm", "kernel": "rpart_partial_kernel", "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "avg_kernel_ms": part_ms, "traffic": None},
+                     "avg_kernel_ms": part_ms, "traffic": counter_traffic(cfg.name),
+                     "algorithmic_bytes": kv_bytes},
     }
     # the device's pure-read ceiling, timed beside the kernel over the K slab (context for `frac`)
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
