@@ -144,6 +144,23 @@ __device__ inline int block_sum(int v, int *sm)
     return t;
 }
 
+// exclusive prefix sum over the workgroup's threads (two barriers)
+__device__ inline int block_exclusive_scan(int v, int *sm)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+    for (int off = 1; off < 64; off <<= 1) {
+        const int u = __shfl_up(inc, off);
+        if (lane >= off) inc += u;
+    }
+    __syncthreads();
+    if (lane == 63) sm[wave] = inc;
+    __syncthreads();
+    int base = 0;
+    for (int w = 0; w < wave; ++w) base += sm[w];
+    return base + inc - v;
+}
+
 __device__ inline int clamp_len(int L, int cap, int *bad)
 {
     if (L < 0) { *bad = 1; return 0; }
@@ -204,16 +221,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         c += (L + T - 1) / T;
     }
     if (tid < kBuckets) hist[tid] = 0;
-    __syncthreads();
-    sm[tid] = c;
-    __syncthreads();
-    for (int off = 1; off < kPlanThreads; off <<= 1) {
-        const int v = tid >= off ? sm[tid - off] : 0;
-        __syncthreads();
-        sm[tid] += v;
-        __syncthreads();
-    }
-    const int first = sm[tid] - c;
+    const int first = block_exclusive_scan(c, sm);      // its barriers also publish hist = 0
     int pos = first;
     for (int b = b0; b < b1; ++b) {
         const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
@@ -235,10 +243,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         pos += n;
     }
     __syncthreads();
-    // bucket starts (exclusive scan of 256 counters by one thread), then scatter
-    if (tid == 0) {
-        int run = 0;
-        for (int k = 0; k < kBuckets; ++k) { const int n = hist[k]; hist[k] = run; run += n; }
+    // bucket starts = exclusive scan of the 256 counters, then scatter
+    {
+        const int n = tid < kBuckets ? hist[tid] : 0;
+        const int start = block_exclusive_scan(n, sm);
+        if (tid < kBuckets) hist[tid] = start;
     }
     __syncthreads();
     pos = first;
