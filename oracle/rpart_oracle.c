@@ -29,6 +29,21 @@
  * equal-key mean, permutation and shift invariance, convex bounds, dominance,
  * weights summing to one, a library softmax-attention cross-check, and an
  * exhaustive check of the binary16 decoder.
+ *
+ * Quantised KV-cache (Section 5.2: K_i and V_i are added to the cache after
+ * quantisation; the paper leaves the quantiser to the user).  The quantiser
+ * defined here is the one the library implements: symmetric, one scale per
+ * token and head,
+ *     scale = max_i |x_i| / 127          (IEEE binary32 division)
+ *     code_i = rint(x_i / scale)          (binary32 division, ties to even)
+ * stored as the byte code_i + 128, with scale = 0 (all-zero row) giving code 0.
+ * It is evaluated in binary32 on purpose: a floating-point result decides an
+ * integer, so both sides must take that decision in the same precision.
+ * Attention over a quantised cache is the plain definition above applied to
+ * the dequantised values (code_i - 128) * scale, in double.
+ * Pins (tests/test_oracle_quant_pins.py): error bound scale/2, extreme codes,
+ * exact cases, scaling invariance, idempotence, a numpy re-statement, and
+ * equality with the fp16 path when the dequantised rows are exact in binary16.
  */
 #include <math.h>
 #include <pthread.h>
@@ -175,5 +190,94 @@ int fdo_rpart_decode(int B, int H, int d, const int32_t *seq_lens,
         pthread_create(&th[t], NULL, worker, &jobs[t]);
     for (int t = 0; t < nthreads; ++t)
         pthread_join(th[t], NULL);
+    return 0;
+}
+
+
+/* ------------------------------------------------------------------------- */
+/* Quantised KV-cache (Section 5.2)                                            */
+/* ------------------------------------------------------------------------- */
+
+/* One row of d binary16 values -> d bytes (code + 128) and one binary32 scale. */
+void fdo_quantize_row_i8(const uint16_t *x, int d, uint8_t *codes, float *scale)
+{
+    float amax = 0.0f;
+    for (int i = 0; i < d; ++i) {
+        float v = (float)fdo_half_to_double(x[i]);      /* exact: binary16 is a subset of binary32 */
+        float a = fabsf(v);
+        if (a > amax) amax = a;
+    }
+    float s = amax / 127.0f;
+    *scale = s;
+    for (int i = 0; i < d; ++i) {
+        float v = (float)fdo_half_to_double(x[i]);
+        float c = (s > 0.0f) ? rintf(v / s) : 0.0f;
+        codes[i] = (uint8_t)((int)c + 128);
+    }
+}
+
+/* Append for a quantised cache: Kc[b], Vc[b] are token-major [cap_b][H][d] bytes,
+ * Ks[b], Vs[b] token-major [cap_b][H] binary32 scales.  k_new, v_new: [B][H][d] binary16. */
+void fdo_kvq_append(int B, int H, int d, int32_t *seq_lens,
+                    uint8_t *const *Kc, float *const *Ks, uint8_t *const *Vc, float *const *Vs,
+                    const uint16_t *k_new, const uint16_t *v_new)
+{
+    for (int b = 0; b < B; ++b) {
+        size_t L = (size_t)seq_lens[b];
+        for (int h = 0; h < H; ++h) {
+            size_t src = ((size_t)b * H + h) * d;
+            size_t row = L * H + h;
+            fdo_quantize_row_i8(k_new + src, d, Kc[b] + row * d, Ks[b] + row);
+            fdo_quantize_row_i8(v_new + src, d, Vc[b] + row * d, Vs[b] + row);
+        }
+        seq_lens[b] += 1;
+    }
+}
+
+static double dequant(uint8_t code, float scale) { return (double)((int)code - 128) * (double)scale; }
+
+/* Eq. 2 + Eq. 3 over the dequantised rows of a quantised cache; q stays binary16.
+ * out: [B][H][d] double; lse: [B][H] or NULL.  Single-threaded. */
+int fdo_rpartq_decode(int B, int H, int d, const int32_t *seq_lens,
+                      const uint8_t *const *Kc, const float *const *Ks,
+                      const uint8_t *const *Vc, const float *const *Vs,
+                      const uint16_t *q, double *out, double *lse)
+{
+    if (B < 0 || H <= 0 || d <= 0 || !seq_lens || !q || !out) return -1;
+    double inv = 1.0 / sqrt((double)d);
+    for (int b = 0; b < B; ++b) {
+        int L = seq_lens[b];
+        double *s = (double *)malloc((size_t)(L > 0 ? L : 1) * sizeof(double));
+        for (int h = 0; h < H; ++h) {
+            size_t bh = (size_t)b * H + h;
+            double *o = out + bh * d;
+            for (int i = 0; i < d; ++i) o[i] = 0.0;
+            if (L == 0) {
+                if (lse) lse[bh] = -INFINITY;
+                continue;
+            }
+            double m = -INFINITY;
+            for (int t = 0; t < L; ++t) {
+                size_t row = (size_t)t * H + h;
+                double dot = 0.0;
+                for (int i = 0; i < d; ++i)
+                    dot += fdo_half_to_double(q[bh * d + i]) * dequant(Kc[b][row * d + i], Ks[b][row]);
+                s[t] = dot * inv;
+                if (s[t] > m) m = s[t];
+            }
+            double Z = 0.0;
+            for (int t = 0; t < L; ++t) {
+                s[t] = exp(s[t] - m);
+                Z += s[t];
+            }
+            for (int t = 0; t < L; ++t) {
+                size_t row = (size_t)t * H + h;
+                double a = s[t] / Z;
+                for (int i = 0; i < d; ++i) o[i] += a * dequant(Vc[b][row * d + i], Vs[b][row]);
+            }
+            if (lse) lse[bh] = m + log(Z);
+        }
+        free(s);
+    }
     return 0;
 }

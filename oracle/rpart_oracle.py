@@ -39,6 +39,12 @@ def _load():
         lib.fdo_kv_append.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 5
         lib.fdo_rpart_decode.restype = ctypes.c_int
         lib.fdo_rpart_decode.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 8 + [ctypes.c_int]
+        lib.fdo_quantize_row_i8.restype = None
+        lib.fdo_quantize_row_i8.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        lib.fdo_kvq_append.restype = None
+        lib.fdo_kvq_append.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 7
+        lib.fdo_rpartq_decode.restype = ctypes.c_int
+        lib.fdo_rpartq_decode.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 8
         _lib = lib
     return _lib
 
@@ -104,3 +110,57 @@ def rpart_decode(K: List[np.ndarray], V: List[np.ndarray], seq_lens: np.ndarray,
         weights = [wbuf[woff[b]: woff[b] + H * int(seq_lens[b])].reshape(H, int(seq_lens[b]))
                    for b in range(B)]
     return out, lse, weights
+
+
+# ---------------------------------------------------------------------------
+# quantised KV-cache (Section 5.2): bytes = code + 128, one float32 scale per token and head
+# ---------------------------------------------------------------------------
+def _ptrs(arrs, dtype):
+    for a in arrs:
+        assert a.dtype == dtype and a.flags["C_CONTIGUOUS"]
+    return (ctypes.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+
+
+def quantize_rows_i8(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """x: uint16 [..., d] binary16 patterns -> (codes uint8 [..., d], scales float32 [...])."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    d = x.shape[-1]
+    flat = x.reshape(-1, d)
+    codes = np.empty(flat.shape, dtype=np.uint8)
+    scales = np.empty(flat.shape[0], dtype=np.float32)
+    lib = _load()
+    for r in range(flat.shape[0]):
+        lib.fdo_quantize_row_i8(flat[r].ctypes.data, d, codes[r].ctypes.data,
+                                scales[r:r + 1].ctypes.data)
+    return codes.reshape(x.shape), scales.reshape(x.shape[:-1])
+
+
+def kvq_append(Kc, Ks, Vc, Vs, seq_lens: np.ndarray, k_new: np.ndarray, v_new: np.ndarray) -> None:
+    """In place: quantise k_new[b], v_new[b] into row seq_lens[b]; seq_lens += 1.
+
+    Kc[b], Vc[b]: uint8 [cap_b, H, d]; Ks[b], Vs[b]: float32 [cap_b, H]."""
+    B, H, d = k_new.shape
+    assert seq_lens.dtype == np.int32 and len(Kc) == len(Ks) == len(Vc) == len(Vs) == B
+    for b in range(B):
+        assert Kc[b].shape[1:] == (H, d) and Ks[b].shape[1:] == (H,)
+        assert Kc[b].shape[0] > seq_lens[b], "cache full"
+    k_new = np.ascontiguousarray(k_new, dtype=np.uint16)
+    v_new = np.ascontiguousarray(v_new, dtype=np.uint16)
+    _load().fdo_kvq_append(B, H, d, seq_lens.ctypes.data, _ptrs(Kc, np.uint8), _ptrs(Ks, np.float32),
+                           _ptrs(Vc, np.uint8), _ptrs(Vs, np.float32),
+                           k_new.ctypes.data, v_new.ctypes.data)
+
+
+def rpartq_decode(Kc, Ks, Vc, Vs, seq_lens: np.ndarray, q: np.ndarray):
+    """Attention of q over the dequantised rows [0, seq_lens[b]).  Returns (out, lse) float64."""
+    B, H, d = q.shape
+    assert seq_lens.dtype == np.int32
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    out = np.empty((B, H, d), dtype=np.float64)
+    lse = np.empty((B, H), dtype=np.float64)
+    rc = _load().fdo_rpartq_decode(B, H, d, seq_lens.ctypes.data, _ptrs(Kc, np.uint8),
+                                   _ptrs(Ks, np.float32), _ptrs(Vc, np.uint8), _ptrs(Vs, np.float32),
+                                   q.ctypes.data, out.ctypes.data, lse.ctypes.data)
+    if rc != 0:
+        raise ValueError("fdo_rpartq_decode: invalid arguments")
+    return out, lse
