@@ -41,13 +41,14 @@ def counter_traffic(config_name):
 
 
 
-def build_case(cfg, lens, seed, chunk_tokens, growth=8):
+def build_case(cfg, lens, seed, chunk_tokens, growth=8, kv="fp16"):
     import torch
     from paper_2403_11421_amd import workloads as W
-    from paper_2403_11421_amd.kvcache import KVCache
+    from paper_2403_11421_amd.kvcache import KVCache, KVCacheQ
 
     dev = torch.device("cuda:0")
-    cache = KVCache(cfg.B, cfg.H, cfg.d, [L + growth for L in lens], dev, chunk_tokens)
+    cls = KVCache if kv == "fp16" else KVCacheQ
+    cache = cls(cfg.B, cfg.H, cfg.d, [L + growth for L in lens], dev, chunk_tokens)
     for b, L in enumerate(lens):
         if L:
             cache.fill("K", b, W.gen_cache_block(cfg, "K", b, L, seed, dev))
@@ -97,6 +98,8 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--chunk-tokens", type=int, default=0, help="split-K chunk length, 0 = library's choice")
     ap.add_argument("--cpu-sample", type=int, default=96, help="sequences timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--kv", choices=["fp16", "int8"], default="fp16",
+                    help="KV-cache format: fp16 (the headline path) or the int8 quantised cache")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the steps, as the "
                          "known-size reference dispatch for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
@@ -119,9 +122,16 @@ def main() -> int:
     seed = W.DEFAULT_SEED if args.seed is None else args.seed
     lens = W.seq_lens(cfg, seed)
     n_tok = W.total_tokens_after_append(lens)
-    kv_bytes = cfg.bytes_per_token() * n_tok       # algorithmic bytes: every cached K and V row once
+    # algorithmic bytes: every cached K and V row once (int8: d code bytes + a 4-byte scale per row)
+    bytes_per_token = cfg.bytes_per_token() if args.kv == "fp16" else 2 * cfg.H * (cfg.d + 4)
+    kv_bytes = bytes_per_token * n_tok
+    q8 = args.kv == "int8"
+    f_append = rpart.fd_kvq_append if q8 else rpart.fd_kv_append
+    f_plan = rpart.fd_rpartq_plan if q8 else rpart.fd_rpart_plan
+    f_partial = rpart.fd_rpartq_partial if q8 else rpart.fd_rpart_partial
+    f_merge = rpart.fd_rpartq_merge if q8 else rpart.fd_rpart_merge
 
-    cache, vec = build_case(cfg, lens, seed, args.chunk_tokens)
+    cache, vec = build_case(cfg, lens, seed, args.chunk_tokens, kv=args.kv)
     out = torch.empty_like(vec["q"])
     ws = cache.workspace(n_tok)
     lens0 = cache.seq_lens.clone()
@@ -134,14 +144,14 @@ def main() -> int:
 
     def step(pair=None):
         cache.seq_lens.copy_(lens0)                # every step is the quoted config: L cached + 1 appended
-        rpart.fd_kv_append(desc, vec["k_new"], vec["v_new"])
-        rpart.fd_rpart_plan(desc, ws)
+        f_append(desc, vec["k_new"], vec["v_new"])
+        f_plan(desc, ws)
         if pair:
             pair[0].record()
-        rpart.fd_rpart_partial(desc, vec["q"], out, ws)
+        f_partial(desc, vec["q"], out, ws)
         if pair:
             pair[1].record()
-        rpart.fd_rpart_merge(desc, out, ws)
+        f_merge(desc, out, ws)
 
     if args.copy_calibration_mib > 0:
         src = torch.ones(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda")
@@ -176,7 +186,7 @@ def main() -> int:
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} d={cfg.d} fp16 KV, "
+        "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} d={cfg.d} {args.kv} KV, "
                                f"{n_tok} cached tokens after append, 1 layer",
                    "B": cfg.B, "H": cfg.H, "d": cfg.d, "total_tokens": n_tok,
                    "kv_bytes_per_step": kv_bytes, "seed": seed, "plan": plan},
@@ -184,15 +194,17 @@ def main() -> int:
         "seq_per_s": cfg.B / (ms_step * 1e-3),
         "seq_per_s_whole_model": cfg.B / (ms_step * 1e-3) / cfg.n_layers,
         "ns_per_cached_token": ms_step * 1e6 / n_tok,
-        "roofline": {"bound": "hbm", "kernel": "rpart_partial_kernel", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": "rpartq_partial_kernel" if q8 else "rpart_partial_kernel",
+                     "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "avg_kernel_ms": part_ms, "launches_timed": len(timed), "traffic": counter_traffic(cfg.name),
+                     "avg_kernel_ms": part_ms, "launches_timed": len(timed), "traffic": None if q8 else counter_traffic(cfg.name),
                      "algorithmic_bytes": kv_bytes},
     }
     # the device's pure-read ceiling, timed beside the kernel over the K slab (context for `frac`)
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    buf = cache.k if cache.k.numel() * 2 >= (1 << 30) else \
+    slab = cache.k_codes if q8 else cache.k
+    buf = slab if slab.numel() * slab.element_size() >= (1 << 30) else \
         torch.zeros(1 << 31, dtype=torch.uint8, device="cuda")     # tiny configs: a 2 GiB stand-in
     nread = rpart.fd_hbm_read_probe(buf, sink)
     e0.record()
@@ -202,7 +214,7 @@ def main() -> int:
     torch.cuda.synchronize()
     res["roofline"]["read_only_ceiling_gbps"] = nread * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
-    if args.cpu_sample > 0:
+    if args.cpu_sample > 0 and not q8:
         res["cpu_baseline"] = cpu_baseline(cfg, cache, vec, [L + 1 for L in lens], args.cpu_sample)
     print(json.dumps(res))
     return 0

@@ -146,6 +146,56 @@ int fd_read_status(const fd_kv_desc *desc, int32_t *host_status, int clear, void
  */
 int fd_plan_info(const void *workspace, int32_t info[4], void *stream);
 
+/* ------------------------------------------------------------------------- */
+/* Quantised KV-cache (Section 5.2: K_i and V_i are added to the cache after      */
+/* quantisation; fewer bytes to stream make the memory-bound R-Part faster).      */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * int8 KV-cache of one layer.  The paper leaves the quantiser to the user; the one
+ * implemented is symmetric with one scale per token and head, evaluated in IEEE
+ * binary32 so that the stored bytes are reproducible:
+ *     scale = max_i |x_i| / 127,   code_i = rint(x_i / scale)  (ties to even),
+ * the byte stored is code_i + 128; an all-zero row gets scale 0 and bytes 128.
+ * The query needs no transformation for this scheme.  d must be 128.
+ *
+ * Byte i of the K row of sequence b, head h, token t is
+ *     k_codes[ seq_off[b] + ((int64)h * seq_cap[b] + t) * d + i ]
+ * and its scale is  k_scale[ seq_off[b] / d + (int64)h * seq_cap[b] + t ];
+ * likewise for V.  seq_off[b] must be a multiple of d; blocks must not overlap.
+ */
+typedef struct fd_kvq_desc {
+    void          *k_codes;       /* device, uint8 slab of K codes                              */
+    void          *v_codes;       /* device, uint8 slab of V codes                              */
+    float         *k_scale;       /* device, float32 slab of K scales (one per code row)        */
+    float         *v_scale;       /* device, float32 slab of V scales                           */
+    const int64_t *seq_off;       /* device int64[B]: byte offset of sequence b's code block    */
+    const int32_t *seq_cap;       /* device int32[B]: capacity of sequence b in tokens          */
+    int32_t       *seq_lens;      /* device int32[B]: cached tokens; written by append / reset  */
+    int32_t       *status;        /* device int32[1]: sticky FD_ST_* bits; caller zeroes it     */
+    int32_t        B, H, d;       /* sequences, heads, head dimension (128)                      */
+    int32_t        chunk_tokens;  /* split-K chunk length in tokens; 0 = chosen on the device   */
+} fd_kvq_desc;
+
+/*
+ * Same contracts as the fp16 entry points of the same names without the "q":
+ * fd_kvq_append quantises k_new[b], v_new[b] (device fp16 [B][H][d]) into row
+ * seq_lens[b] and bumps the length (FD_ST_CAPACITY when full); fd_rpartq_decode is
+ * Eq. 2 + Eq. 3 over the dequantised rows (code - 128) * scale with fp32 arithmetic
+ * and an fp16 result; workspace size comes from fd_workspace_bytes(B, H, 128, n).
+ */
+int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new, void *stream);
+int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
+int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_bytes, void *stream);
+int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
+                      void *workspace, size_t workspace_bytes, void *stream);
+int fd_rpartq_merge(const fd_kvq_desc *desc, void *out,
+                    void *workspace, size_t workspace_bytes, void *stream);
+int fd_rpartq_decode(const fd_kvq_desc *desc, const void *q, void *out,
+                     void *workspace, size_t workspace_bytes, void *stream);
+int fd_rpartq_step(const fd_kvq_desc *desc, const void *q, const void *k_new, const void *v_new,
+                   void *out, void *workspace, size_t workspace_bytes, void *stream);
+
 /*
  * Measurement aid, not part of the R-Part: enqueue a kernel that only reads
  * `buf` (device, 16-byte aligned) with the same 128-bit streaming loads as the

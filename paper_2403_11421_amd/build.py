@@ -33,7 +33,7 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = SOURCES + [os.path.join(INCLUDE, "fastdecode_rpart.h")]
+    deps = SOURCES + [os.path.join(_PKG, "csrc", "fd_rpartq.h"), os.path.join(INCLUDE, "fastdecode_rpart.h")]
     return any(os.path.getmtime(p) > t for p in deps)
 
 

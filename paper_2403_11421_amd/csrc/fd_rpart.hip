@@ -882,3 +882,6 @@ int fd_plan_info(const void *workspace, int32_t info[4], void *stream)
 }
 
 } // extern "C"
+
+// quantised KV-cache path (Section 5.2); reuses the planner, merge kernel and helpers above
+#include "fd_rpartq.h"

@@ -1,0 +1,515 @@
+// Quantised KV-cache path of the R-Part (FastDecode Section 5.2: K_i and V_i are added to the
+// cache after quantisation, which divides the bytes the memory-bound attention has to stream).
+// Included at the end of fd_rpart.hip: it reuses that file's planner, merge kernel, schedule
+// and helpers; only the cache format, the append and the streaming kernel differ.
+//
+// Format (the paper leaves the quantiser to the user): symmetric int8, one scale per token and
+// head.  scale = max|x| / 127 and code = rint(x / scale) are evaluated in IEEE binary32 so that
+// the stored bytes are reproducible bit for bit; the byte stored is code + 128.  A row of
+// d = 128 values takes 128 B of codes plus a 4 B scale (1.94 x fewer bytes than fp16).
+// The query needs no transformation for this scheme and stays fp16.
+
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int CTRL>
+__device__ inline float dpp_xmax(float x)
+{
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true);
+    return fmaxf(x, __int_as_float(y));
+}
+
+// ---------------------------------------------------------------------------
+// Quantising append.  One workgroup per sequence; a row (128 fp16) is handled by 16
+// lanes with 8 values each.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void kvq_append_kernel(
+    uint8_t *__restrict__ k_codes, uint8_t *__restrict__ v_codes,
+    float *__restrict__ k_scale, float *__restrict__ v_scale,
+    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
+    int32_t *__restrict__ seq_lens, int32_t *__restrict__ status,
+    const _Float16 *__restrict__ k_new, const _Float16 *__restrict__ v_new, int H)
+{
+    constexpr int D = 128;
+    const int b = blockIdx.x;
+    const int L = seq_lens[b];
+    const int cap = seq_cap[b];
+    if (L < 0 || L >= cap) {
+        if (threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
+        return;
+    }
+    const int sub = threadIdx.x & 15;          // position inside the 16-lane group of a row
+    const int group = threadIdx.x >> 4;        // 16 rows in flight per pass
+    const int64_t off = seq_off[b];
+    for (int r = group; r < 2 * H; r += 16) {
+        const int which = r >= H;
+        const int h = which ? r - H : r;
+        const _Float16 *src = (which ? v_new : k_new) + ((int64_t)b * H + h) * D + sub * 8;
+        const half8 x = *reinterpret_cast<const half8 *>(src);
+        float f[8], amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            f[i] = (float)x[i];
+            amax = fmaxf(amax, fabsf(f[i]));
+        }
+        amax = dpp_xmax<0xB1>(amax);           // max over the 16 lanes of the row
+        amax = dpp_xmax<0x4E>(amax);
+        amax = dpp_xmax<0x141>(amax);
+        amax = dpp_xmax<0x140>(amax);
+        const float scale = __fdiv_rn(amax, 127.0f);
+        unsigned lo = 0, hi = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float c = scale > 0.f ? rintf(__fdiv_rn(f[i], scale)) : 0.f;
+            const unsigned u = (unsigned)((int)c + 128) & 0xFFu;
+            if (i < 4) lo |= u << (8 * i);
+            else       hi |= u << (8 * (i - 4));
+        }
+        const int64_t row = (int64_t)h * cap + L;
+        uint8_t *dst = (which ? v_codes : k_codes) + off + row * D + sub * 8;
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
+        if (sub == 0) (which ? v_scale : k_scale)[off / D + row] = scale;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) seq_lens[b] = L + 1;
+}
+
+// ---------------------------------------------------------------------------
+// Streaming kernel over int8 codes, d = 128.  A row is 128 B = 8 lanes x 16 codes; a wave
+// load covers 8 tokens; a workgroup block is 4 waves x 8 loads = 256 tokens (32 KB of K codes
+// and 32 KB of V codes).  The 64 tokens of a wave's tile map one-to-one onto its 64 lanes for
+// the scales: each lane loads the K and the V scale of "its" token and the values are handed to
+// the lanes that need them with a cross-lane read.
+//
+// Dequantisation is folded into the arithmetic: with u = code + 128,
+//   q . k   = scale_k * (sum_i q_i u_i - 128 * sum_i q_i)
+//   sum p v = sum_t (p_t scale_v,t) u_t - 128 * sum_t (p_t scale_v,t)
+// so each element costs one byte-to-float convert and one FMA.
+// ---------------------------------------------------------------------------
+__device__ inline float byte_f32(unsigned w, int i) { return (float)((w >> (8 * i)) & 0xFFu); }
+
+__device__ inline u32x4 ld_stream_u(const char *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+}
+
+struct TileQ8 {
+    static constexpr int D = 128;
+    static constexpr int NL = 8;
+    static constexpr int LPR = 8;                        // lanes per row
+    static constexpr int RPW = 8;                        // rows (tokens) per wave load
+    static constexpr int EPL = 16;                       // elements per lane
+    static constexpr int STRIDE = kWaves * 1024;         // bytes between a wave's consecutive loads
+    static constexpr int TSTEP = kWaves * RPW;           // tokens between a wave's consecutive loads
+    static constexpr int BLK_TOK = NL * TSTEP;           // 256 tokens per workgroup block
+    static constexpr int BLK_BYTES = NL * STRIDE;        // bytes of K (or V) codes per block
+    u32x4 k[NL], v[NL];
+    float ks, vs;                                        // scales of this lane's own token
+
+    // token (inside a block) whose scales lane `lane` of wave `wave` loads: load lane/8, row lane%8
+    __device__ static inline int own_token(int lane, int wave)
+    {
+        return ((lane >> 3) * kWaves + wave) * RPW + (lane & 7);
+    }
+
+    __device__ inline void load(const char *kp, const char *vp, const float *ksp, const float *vsp)
+    {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) k[j] = ld_stream_u(kp + j * STRIDE);
+        ks = __builtin_nontemporal_load(ksp);
+#pragma unroll
+        for (int j = 0; j < NL; ++j) v[j] = ld_stream_u(vp + j * STRIDE);
+        vs = __builtin_nontemporal_load(vsp);
+    }
+
+    // ragged last block of `rem` >= 1 tokens: lanes whose token is at or beyond `rem` re-read
+    // token rem-1 (in bounds) and are masked in update<true>
+    __device__ inline void load_tail(const char *kp, const char *vp, const float *ksp,
+                                     const float *vsp, int tok0, int own, int rem)
+    {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const int over = j * TSTEP + tok0 - (rem - 1);
+            const int back = over > 0 ? over * D : 0;
+            k[j] = ld_stream_u(kp + (j * STRIDE - back));
+            v[j] = ld_stream_u(vp + (j * STRIDE - back));
+        }
+        const int sback = own > rem - 1 ? own - (rem - 1) : 0;
+        ks = __builtin_nontemporal_load(ksp - sback);
+        vs = __builtin_nontemporal_load(vsp - sback);
+    }
+
+    template <bool MASKED>
+    __device__ inline void update(const float (&q)[EPL], float qsum128, float &m, float &l,
+                                  float &aux, float (&acc)[EPL], int row, int tok0, int rem) const
+    {
+        float s[NL];
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            float a = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a = __builtin_fmaf(byte_f32(k[j][w], i), q[w * 4 + i], a);
+            a = row_sum<LPR>(a);
+            const float sc = __shfl(ks, j * RPW + row);
+            a = (a - qsum128) * sc;
+            if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
+            s[j] = a;
+        }
+        float tm = s[0];
+#pragma unroll
+        for (int j = 1; j < NL; ++j) tm = fmaxf(tm, s[j]);
+        const float mn = fmaxf(m, tm);
+        const float corr = fast_exp2(m - mn);
+        l *= corr;
+        aux *= corr;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] *= corr;
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            float p = fast_exp2(s[j] - mn);
+            if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
+            l += p;
+            const float pv = p * __shfl(vs, j * RPW + row);
+            aux += pv;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc[w * 4 + i] = __builtin_fmaf(pv, byte_f32(v[j][w], i), acc[w * 4 + i]);
+        }
+        m = mn;
+    }
+};
+
+__global__ __launch_bounds__(kThreads) void rpartq_partial_kernel(
+    const char *__restrict__ k_codes, const char *__restrict__ v_codes,
+    const float *__restrict__ k_scale, const float *__restrict__ v_scale,
+    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
+    const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
+    const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
+    const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
+    float qscale)
+{
+    using T = TileQ8;
+    constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL;
+    __shared__ float sm_acc[kWaves][D];
+    __shared__ float sm_m[kWaves], sm_l[kWaves], sm_aux[kWaves];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int row = lane / LPR;
+    const int col = lane % LPR;
+    const int tok0 = wave * T::RPW + row;                  // this lane's token in a block, load 0
+    const int own = T::own_token(lane, wave);              // token whose scales this lane loads
+    const int n_units = hdr[HDR_NITEMS] * H;
+    const int W = gridDim.x, g = blockIdx.x;
+
+    // same static schedule as the fp16 kernel
+    const int n_rounds = (int)(((long long)n_units + W - 1) / W);
+    const int k_start = (int)((long long)(g % kPhases) * n_rounds / kPhases);
+    auto fetch = [&](int j) {
+        Unit u;
+        u.ntok = 0;
+        if (j < n_rounds) {
+            int k = k_start + j;
+            if (k >= n_rounds) k -= n_rounds;
+            const long long p = (long long)k * W + ((k & 1) ? W - 1 - g : g);
+            if (p < n_units) {
+                const int sidx = (int)(p / H);
+                const int item = order[sidx];
+                const int4 it = items[item];
+                u.h = (int)(p - (long long)sidx * H);
+                u.b = it.x;
+                u.item = item;
+                u.nch = it.w;
+                u.ntok = it.z - it.y;
+                u.row0 = seq_off[it.x] / D + (int64_t)u.h * seq_cap[it.x] + it.y;   // row index
+            }
+        }
+        return u;
+    };
+
+    int j = 0;
+    Unit cur = fetch(0);
+    if (cur.ntok == 0 && n_rounds > 1) cur = fetch(++j);
+    while (cur.ntok > 0) {
+        Unit nxt = fetch(++j);
+        if (nxt.ntok == 0 && j < n_rounds) nxt = fetch(++j);
+
+        const int b = cur.b, h = cur.h;
+        const char *kp = k_codes + cur.row0 * D + tid * 16;     // wave w starts at its 1 KB slot
+        const char *vp = v_codes + cur.row0 * D + tid * 16;
+        const float *ksp = k_scale + cur.row0 + own;
+        const float *vsp = v_scale + cur.row0 + own;
+
+        float qf[EPL], qsum = 0.f;
+        {
+            const _Float16 *qp = q + ((int64_t)b * H + h) * D + col * EPL;
+            const half8 q0 = *reinterpret_cast<const half8 *>(qp);
+            const half8 q1 = *reinterpret_cast<const half8 *>(qp + 8);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                qf[i] = (float)q0[i] * qscale;
+                qf[8 + i] = (float)q1[i] * qscale;
+            }
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) qsum += qf[i];
+            qsum = row_sum<LPR>(qsum) * 128.0f;                  // 128 * sum of the whole query
+        }
+
+        float m = kNegBig, l = 0.f, aux = 0.f, acc[EPL];
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+
+        const int ntok = cur.ntok;
+        const int n_blk = ntok / T::BLK_TOK;
+        const int rem = ntok - n_blk * T::BLK_TOK;
+
+        const char *kt = kp;
+        const char *vt = vp;
+        const float *kst = ksp;
+        const float *vst = vsp;
+        T A, Bf;
+        if (n_blk > 0) {
+            A.load(kt, vt, kst, vst);
+            int i = 0;
+            while (i + 2 < n_blk) {
+                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kst + T::BLK_TOK, vst + T::BLK_TOK);
+                sched_fence();
+                A.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                sched_fence();
+                A.load(kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES, kst + 2 * T::BLK_TOK,
+                       vst + 2 * T::BLK_TOK);
+                sched_fence();
+                Bf.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                sched_fence();
+                kt += 2 * T::BLK_BYTES;
+                vt += 2 * T::BLK_BYTES;
+                kst += 2 * T::BLK_TOK;
+                vst += 2 * T::BLK_TOK;
+                i += 2;
+            }
+            if (i + 1 < n_blk) {
+                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kst + T::BLK_TOK, vst + T::BLK_TOK);
+                sched_fence();
+                A.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                sched_fence();
+                Bf.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+            } else {
+                A.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+            }
+        }
+        if (rem > 0 && wave * T::RPW < rem) {              // this wave has at least one valid row
+            const int64_t o = (int64_t)n_blk * T::BLK_BYTES;
+            const int64_t so = (int64_t)n_blk * T::BLK_TOK;
+            A.load_tail(kp + o, vp + o, ksp + so, vsp + so, tok0, own, rem);
+            A.template update<true>(qf, qsum, m, l, aux, acc, row, tok0, rem);
+        }
+
+        // combine the rows of this wave
+#pragma unroll
+        for (int off = LPR; off < 64; off <<= 1) {
+            const float mo = __shfl_xor(m, off);
+            const float lo = __shfl_xor(l, off);
+            const float xo = __shfl_xor(aux, off);
+            const float M = fmaxf(m, mo);
+            const float a = fast_exp2(m - M), c = fast_exp2(mo - M);
+            l = l * a + lo * c;
+            aux = aux * a + xo * c;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], off) * c;
+            m = M;
+        }
+        if (lane < LPR) {
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) sm_acc[wave][lane * EPL + i] = acc[i];
+        }
+        if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; sm_aux[wave] = aux; }
+        __syncthreads();
+
+        if (tid < D) {
+            float M = sm_m[0];
+#pragma unroll
+            for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
+            float L = 0.f, X = 0.f, o = 0.f;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w) {
+                const float a = fast_exp2(sm_m[w] - M);
+                L += a * sm_l[w];
+                X += a * sm_aux[w];
+                o += a * sm_acc[w][tid];
+            }
+            o -= 128.0f * X;                                 // remove the +128 byte offset
+            if (cur.nch == 1) {
+                __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
+            } else {
+                const int64_t rec = (int64_t)cur.item * H + h;
+                __builtin_nontemporal_store(o, &part_acc[rec * D + tid]);
+                if (tid == 0) {
+                    __builtin_nontemporal_store(M, &part_ml[rec * 2]);
+                    __builtin_nontemporal_store(L, &part_ml[rec * 2 + 1]);
+                }
+            }
+        }
+        __syncthreads();               // LDS is reused by the next unit
+        cur = nxt;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+int check_qdesc(const fd_kvq_desc *d)
+{
+    if (!d) return FD_EINVAL;
+    if (d->B < 0 || d->H <= 0 || d->d != 128) return FD_EINVAL;
+    if (d->chunk_tokens < 0) return FD_EINVAL;
+    if (d->B == 0) return FD_OK;
+    if (!d->k_codes || !d->v_codes || !d->k_scale || !d->v_scale || !d->seq_off || !d->seq_cap ||
+        !d->seq_lens || !d->status)
+        return FD_EINVAL;
+    if (!aligned(d->k_codes, 16) || !aligned(d->v_codes, 16) || !aligned(d->k_scale, 4) ||
+        !aligned(d->v_scale, 4) || !aligned(d->seq_off, 8) || !aligned(d->seq_cap, 4) ||
+        !aligned(d->seq_lens, 4) || !aligned(d->status, 4))
+        return FD_EINVAL;
+    return FD_OK;
+}
+
+int check_qws(const fd_kvq_desc *d, const void *ws, size_t ws_bytes, WsLayout *w)
+{
+    if (!ws || !aligned(ws, 256)) return FD_EINVAL;
+    *w = ws_layout(d->B, d->H, d->d, ws_bytes);
+    if (w->max_items < d->B) return FD_EWORKSPACE;
+    return FD_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
+    hipLaunchKernelGGL(kvq_append_kernel, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
+                       (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
+                       desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens, desc->status,
+                       (const _Float16 *)k_new, (const _Float16 *)v_new, desc->H);
+    return launched();
+}
+
+int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (seq_ids && n < 0) return FD_EINVAL;
+    const int count = seq_ids ? n : desc->B;
+    if (count == 0) return FD_OK;
+    hipLaunchKernelGGL(kv_reset_kernel, dim3((count + 255) / 256), dim3(256), 0,
+                       (hipStream_t)stream, desc->seq_lens, seq_ids, count, desc->B);
+    return launched();
+}
+
+int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    WsLayout w;
+    rc = check_qws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    char *ws = (char *)workspace;
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
+                       desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
+                       desc->chunk_tokens, 64, grid, (int)w.max_items, (int32_t *)ws,
+                       (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
+                       (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
+    return launched();
+}
+
+int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
+    WsLayout w;
+    rc = check_qws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    char *ws = (char *)workspace;
+    const float qscale = (float)(1.4426950408889634 / 11.313708498984761);
+    hipLaunchKernelGGL(rpartq_partial_kernel, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream,
+                       (const char *)desc->k_codes, (const char *)desc->v_codes, desc->k_scale,
+                       desc->v_scale, desc->seq_off, desc->seq_cap, (const _Float16 *)q,
+                       (_Float16 *)out, desc->H, (const int32_t *)ws,
+                       (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
+                       (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale);
+    return launched();
+}
+
+int fd_rpartq_merge(const fd_kvq_desc *desc, void *out,
+                    void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!out || !aligned(out, 16)) return FD_EINVAL;
+    WsLayout w;
+    rc = check_qws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    char *ws = (char *)workspace;
+    const int64_t bh = (int64_t)desc->B * desc->H;
+    hipLaunchKernelGGL(rpart_merge_kernel<128>, dim3((unsigned)((bh + 3) / 4)), dim3(256), 0,
+                       (hipStream_t)stream, (const int32_t *)(ws + w.off_item0),
+                       (const int32_t *)(ws + w.off_nchunk), (const float *)(ws + w.off_acc),
+                       (const float *)(ws + w.off_ml), (_Float16 *)out, desc->B, desc->H);
+    return launched();
+}
+
+int fd_rpartq_decode(const fd_kvq_desc *desc, const void *q, void *out,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
+    WsLayout w;
+    rc = check_qws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    rc = fd_rpartq_plan(desc, workspace, workspace_bytes, stream);
+    if (rc != FD_OK) return rc;
+    rc = fd_rpartq_partial(desc, q, out, workspace, workspace_bytes, stream);
+    if (rc != FD_OK) return rc;
+    return fd_rpartq_merge(desc, out, workspace, workspace_bytes, stream);
+}
+
+int fd_rpartq_step(const fd_kvq_desc *desc, const void *q, const void *k_new, const void *v_new,
+                   void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !k_new || !v_new || !aligned(q, 16) || !aligned(out, 16) ||
+        !aligned(k_new, 16) || !aligned(v_new, 16))
+        return FD_EINVAL;
+    WsLayout w;
+    rc = check_qws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    rc = fd_kvq_append(desc, k_new, v_new, stream);
+    if (rc != FD_OK) return rc;
+    return fd_rpartq_decode(desc, q, out, workspace, workspace_bytes, stream);
+}
+
+} // extern "C"

@@ -57,3 +57,75 @@ class KVCache:
     def workspace(self, max_total_tokens: int) -> torch.Tensor:
         n = rpart.workspace_bytes(self.B, self.H, self.d, max_total_tokens)
         return torch.empty(n, dtype=torch.uint8, device=self.device)
+
+
+def quantize_rows_i8(rows: torch.Tensor):
+    """fp16 rows [..., d] -> (uint8 codes [..., d], float32 scales [...]).
+
+    Input preparation for tests and benchmarks (the product path quantises in
+    ``fd_kvq_append``): scale = max|x| / 127 and code = rint(x / scale) in float32,
+    byte = code + 128, all-zero rows get scale 0 and byte 128.  On a GPU torch's division is
+    not correctly rounded, so scales can be 1 ulp off that definition; what is stored is the
+    input either way."""
+    x = rows.float()
+    scale = x.abs().amax(dim=-1) / 127.0
+    safe = torch.where(scale > 0, scale, torch.ones_like(scale))
+    code = torch.where(scale.unsqueeze(-1) > 0, torch.round(x / safe.unsqueeze(-1)),
+                       torch.zeros_like(x))
+    return (code + 128.0).to(torch.uint8), scale
+
+
+class KVCacheQ:
+    """int8 KV-cache of one layer in the layout of ``fd_kvq_desc`` (d = 128)."""
+
+    def __init__(self, B: int, H: int, d: int, capacities: Sequence[int], device="cuda",
+                 chunk_tokens: int = 0):
+        assert len(capacities) == B and d == 128
+        self.B, self.H, self.d = B, H, d
+        self.device = torch.device(device)
+        self.caps = [max(1, int(c)) for c in capacities]
+        offs, o = [], 0
+        for c in self.caps:
+            offs.append(o)
+            o += H * c * d                              # bytes of codes; multiple of d
+            o = (o + 255) // 256 * 256
+        self.offs = offs
+        self.total_bytes = max(o, 256)
+        self.k_codes = torch.full((self.total_bytes,), 128, dtype=torch.uint8, device=self.device)
+        self.v_codes = torch.full((self.total_bytes,), 128, dtype=torch.uint8, device=self.device)
+        self.k_scale = torch.zeros(self.total_bytes // d, dtype=torch.float32, device=self.device)
+        self.v_scale = torch.zeros(self.total_bytes // d, dtype=torch.float32, device=self.device)
+        self.seq_off = torch.tensor(offs, dtype=torch.int64, device=self.device)
+        self.seq_cap = torch.tensor(self.caps, dtype=torch.int32, device=self.device)
+        self.seq_lens = torch.zeros(B, dtype=torch.int32, device=self.device)
+        self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.desc = rpart.fd_kvq_desc(
+            self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_scale.data_ptr(),
+            self.v_scale.data_ptr(), self.seq_off.data_ptr(), self.seq_cap.data_ptr(),
+            self.seq_lens.data_ptr(), self.status.data_ptr(), B, H, d, chunk_tokens)
+
+    def codes(self, which: str, b: int) -> torch.Tensor:
+        """View ``[H, cap_b, d]`` (uint8) of sequence b's K or V codes."""
+        slab = self.k_codes if which == "K" else self.v_codes
+        n = self.H * self.caps[b] * self.d
+        return slab[self.offs[b]: self.offs[b] + n].view(self.H, self.caps[b], self.d)
+
+    def scales(self, which: str, b: int) -> torch.Tensor:
+        """View ``[H, cap_b]`` (float32) of sequence b's K or V scales."""
+        slab = self.k_scale if which == "K" else self.v_scale
+        o = self.offs[b] // self.d
+        return slab[o: o + self.H * self.caps[b]].view(self.H, self.caps[b])
+
+    def fill(self, which: str, b: int, rows: torch.Tensor, t0: int = 0) -> None:
+        """Quantise fp16 ``rows [H, L, d]`` into tokens t0..t0+L-1 of sequence b."""
+        L = rows.shape[1]
+        c, s = quantize_rows_i8(rows)
+        self.codes(which, b)[:, t0:t0 + L, :].copy_(c)
+        self.scales(which, b)[:, t0:t0 + L].copy_(s)
+
+    def set_lens(self, lens: Sequence[int]) -> None:
+        self.seq_lens.copy_(torch.tensor(list(lens), dtype=torch.int32))
+
+    def workspace(self, max_total_tokens: int) -> torch.Tensor:
+        n = rpart.workspace_bytes(self.B, self.H, self.d, max_total_tokens)
+        return torch.empty(n, dtype=torch.uint8, device=self.device)

@@ -29,6 +29,15 @@ class fd_kv_desc(ctypes.Structure):
     ]
 
 
+class fd_kvq_desc(ctypes.Structure):
+    _fields_ = [
+        ("k_codes", _vp), ("v_codes", _vp), ("k_scale", _vp), ("v_scale", _vp),
+        ("seq_off", _vp), ("seq_cap", _vp), ("seq_lens", _vp), ("status", _vp),
+        ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
+        ("chunk_tokens", ctypes.c_int32),
+    ]
+
+
 class FdError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
@@ -75,6 +84,16 @@ def load() -> ctypes.CDLL:
     lib.fd_read_status.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.c_int, _vp]
     lib.fd_plan_info.restype = ctypes.c_int
     lib.fd_plan_info.argtypes = [_vp, ctypes.POINTER(ctypes.c_int32), _vp]
+    Q = ctypes.POINTER(fd_kvq_desc)
+    for name, args in (("fd_kvq_append", [Q, _vp, _vp, _vp]),
+                       ("fd_kvq_reset", [Q, _vp, ctypes.c_int32, _vp]),
+                       ("fd_rpartq_plan", [Q, _vp, ctypes.c_size_t, _vp]),
+                       ("fd_rpartq_partial", [Q, _vp, _vp, _vp, ctypes.c_size_t, _vp]),
+                       ("fd_rpartq_merge", [Q, _vp, _vp, ctypes.c_size_t, _vp]),
+                       ("fd_rpartq_decode", [Q, _vp, _vp, _vp, ctypes.c_size_t, _vp]),
+                       ("fd_rpartq_step", [Q, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp])):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = args
     lib.fd_hbm_read_probe.restype = ctypes.c_int
     lib.fd_hbm_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_size_t), _vp]
     _lib = lib
@@ -83,7 +102,9 @@ def load() -> ctypes.CDLL:
 
 EXPORTS = ("fd_version", "fd_strerror", "fd_workspace_bytes", "fd_kv_append", "fd_rpart_decode",
            "fd_rpart_plan", "fd_rpart_partial", "fd_rpart_merge", "fd_rpart_step", "fd_kv_reset",
-           "fd_read_status", "fd_plan_info", "fd_hbm_read_probe")
+           "fd_read_status", "fd_plan_info", "fd_hbm_read_probe",
+           "fd_kvq_append", "fd_kvq_reset", "fd_rpartq_plan", "fd_rpartq_partial", "fd_rpartq_merge",
+           "fd_rpartq_decode", "fd_rpartq_step")
 
 
 def version() -> int:
@@ -156,9 +177,11 @@ def fd_kv_reset(desc: fd_kv_desc, seq_ids: Optional[torch.Tensor] = None) -> Non
     _check(load().fd_kv_reset(ctypes.byref(desc), _ptr(seq_ids), n, _stream()), "fd_kv_reset")
 
 
-def fd_read_status(desc: fd_kv_desc, clear: bool = False) -> int:
+def fd_read_status(desc, clear: bool = False) -> int:
+    """Sticky device status of an fp16 or a quantised cache (both keep it in `desc.status`)."""
+    probe = fd_kv_desc(status=desc.status)
     v = ctypes.c_int32(0)
-    _check(load().fd_read_status(ctypes.byref(desc), ctypes.byref(v), int(clear), _stream()),
+    _check(load().fd_read_status(ctypes.byref(probe), ctypes.byref(v), int(clear), _stream()),
            "fd_read_status")
     return v.value
 
@@ -176,3 +199,47 @@ def fd_hbm_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> int:
                                     sink.data_ptr(), ctypes.byref(n), _stream()),
            "fd_hbm_read_probe")
     return int(n.value)
+
+
+# ---------------------------------------------------------------------------
+# quantised KV-cache (int8 codes + float32 scales)
+# ---------------------------------------------------------------------------
+def fd_kvq_append(desc: fd_kvq_desc, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
+    _check(load().fd_kvq_append(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), _stream()),
+           "fd_kvq_append")
+
+
+def fd_kvq_reset(desc: fd_kvq_desc, seq_ids: Optional[torch.Tensor] = None) -> None:
+    n = 0 if seq_ids is None else seq_ids.numel()
+    _check(load().fd_kvq_reset(ctypes.byref(desc), _ptr(seq_ids), n, _stream()), "fd_kvq_reset")
+
+
+def fd_rpartq_plan(desc: fd_kvq_desc, workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpartq_plan(ctypes.byref(desc), p, n, _stream()), "fd_rpartq_plan")
+
+
+def fd_rpartq_partial(desc: fd_kvq_desc, q: torch.Tensor, out: torch.Tensor,
+                      workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpartq_partial(ctypes.byref(desc), _ptr(q), _ptr(out), p, n, _stream()),
+           "fd_rpartq_partial")
+
+
+def fd_rpartq_merge(desc: fd_kvq_desc, out: torch.Tensor, workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpartq_merge(ctypes.byref(desc), _ptr(out), p, n, _stream()), "fd_rpartq_merge")
+
+
+def fd_rpartq_decode(desc: fd_kvq_desc, q: torch.Tensor, out: torch.Tensor,
+                     workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpartq_decode(ctypes.byref(desc), _ptr(q), _ptr(out), p, n, _stream()),
+           "fd_rpartq_decode")
+
+
+def fd_rpartq_step(desc: fd_kvq_desc, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                   out: torch.Tensor, workspace: torch.Tensor) -> None:
+    p, n = _ws(workspace)
+    _check(load().fd_rpartq_step(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
+                                 p, n, _stream()), "fd_rpartq_step")
