@@ -89,6 +89,33 @@ def cpu_baseline(cfg, cache, vec, lens_after, n_sample):
     }
 
 
+def schedule_mode(args) -> int:
+    """Per-step R-Part latency of a decode loop under the schedules of Section 4.2 (one layer,
+    Llama-7B head shape): one JSON line per schedule."""
+    from paper_2403_11421_amd import sls_run
+
+    B, S, F = args.sched_B, args.sched_S, args.sched_F
+    n_steps = 2 * S
+    for kind in (["batch", "sls"] if args.schedule == "both" else [args.schedule]):
+        r = sls_run.run_schedule(kind, B, S, F, n_steps)
+        ms, loads = r["ms"], r["loads"]
+        steady = list(range(S, n_steps))                     # after the cold start
+        tok = sum(loads[i] for i in steady)
+        tms = sum(ms[i] for i in steady)
+        srt = sorted(ms[i] for i in steady)
+        print(json.dumps({
+            "metric": "R-Part latency per decode step under a sequence schedule (Section 4.2)",
+            "schedule": kind, "B": B, "S": S, "F": F, "M": r["M"], "H": r["H"], "d": r["d"],
+            "steps": n_steps, "steady_steps": len(steady),
+            "peak_load_tokens": max(loads[i] for i in steady),
+            "mean_load_tokens": tok / len(steady),
+            "peak_ms": srt[-1], "p50_ms": srt[len(srt) // 2], "mean_ms": tms / len(steady),
+            "steady_kv_gbps": 4 * r["H"] * r["d"] * tok / (tms * 1e-3) / 1e9,
+            "tokens_per_s_one_layer": len(steady) * B / (tms * 1e-3),
+            "unit": "ms", "n_gpus": 1, "data": "synthetic", "dtype": "f32"}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -100,6 +127,13 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=96, help="sequences timed on the CPU oracle (0 = skip)")
     ap.add_argument("--kv", choices=["fp16", "int8"], default="fp16",
                     help="KV-cache format: fp16 (the headline path) or the int8 quantised cache")
+    ap.add_argument("--schedule", choices=["none", "batch", "sls", "both"], default="none",
+                    help="instead of the fixed-length step, run a multi-step decode loop under the "
+                         "large-batch or the load-stabilising schedule (Section 4.2) and report the "
+                         "per-step R-Part latency")
+    ap.add_argument("--sched-B", type=int, default=1024)
+    ap.add_argument("--sched-S", type=int, default=1024)
+    ap.add_argument("--sched-F", type=int, default=16)
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB before the steps, as the "
                          "known-size reference dispatch for rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE")
@@ -118,6 +152,8 @@ def main() -> int:
         return 1
     rpart.load()                                   # fails loudly when the HIP library is missing
     torch.cuda.set_device(0)
+    if args.schedule != "none":
+        return schedule_mode(args)
     cfg = W.CONFIGS[args.config]
     seed = W.DEFAULT_SEED if args.seed is None else args.seed
     lens = W.seq_lens(cfg, seed)

@@ -1,0 +1,67 @@
+/*
+ * fastdecode_sched.h -- host-side scheduling arithmetic of FastDecode (arXiv 2403.11421),
+ * Section 4.2: the sequence-level load-stabilising schedule (Eq. 5, Eq. 6, Figure 7) and
+ * the load-control bookkeeping of Algorithm 1.  Pure integer host code in the same shared
+ * library as the GPU kernels; it decides which sequences exist at which length, i.e. the
+ * ragged seq_lens the R-Part kernels see.  Nothing here touches a device.
+ *
+ * Step convention (fixed by Figure 7's worked example): a sequence started at step t has
+ * length s - t + 1 at step s and lives for S steps, s = t .. t+S-1; a step's load is the sum
+ * of the lengths of the sequences alive at that step.
+ *
+ * All functions return negative FD_E* codes (fastdecode_rpart.h) on bad arguments.
+ */
+#ifndef FASTDECODE_SCHED_H
+#define FASTDECODE_SCHED_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Eq. 5: micro-batch size M = B*F/S of the schedule that starts a micro-batch every F
+ * steps and keeps about B sequences in flight.  Requires B, F, S > 0; rounds down, at least 1. */
+int64_t fd_sls_microbatch_size(int64_t B, int64_t F, int64_t S);
+
+/* Eq. 6: peak total length W'max = sum_{k=1..S/F} M*k*F of that schedule (= B(S+F)/2 when F
+ * divides S and S divides B*F).  Computed from the sum, not from the closed form. */
+int64_t fd_sls_peak_load(int64_t M, int64_t F, int64_t S);
+
+/* Per-step total load, loads[0..n_steps), of micro-batches of M sequences started every F
+ * steps from step 0 (Figure 7, lower half).  `loads` is a host array owned by the caller. */
+int fd_sls_step_loads(int64_t M, int64_t F, int64_t S, int64_t n_steps, int64_t *loads);
+
+/* Per-step total load when all B sequences start together and the next batch starts when
+ * they finish (Figure 7, upper half). */
+int fd_batch_step_loads(int64_t B, int64_t S, int64_t n_steps, int64_t *loads);
+
+/*
+ * Algorithm 1 (load control).  The object keeps, for every current micro-batch i, its size
+ * M[i], its ending step E[i] = start + S (exclusive) and W[i], the total load at its last
+ * step E[i]-1, where the load peaks.
+ *   fd_lc_add_microbatch(t, m): records a micro-batch of m sequences started at step t:
+ *       appends (m, t+S, m*S) and adds (E[i]-t)*m to W[i] of every micro-batch that
+ *       existed before the call (the new one's length at their last step).
+ *   fd_lc_earliest_step(t, m): the paper's GetEarliestStep: r = t; for every current
+ *       micro-batch x = floor((W_lim - W[i]) / m), r = max(r, E[i] - x + 1).  Under the step
+ *       convention above this is safe and at most one step later than the exact minimum
+ *       E[i] - x.  Micro-batches whose W[i] already exceeds W_lim give x < 0 and push r
+ *       past their end.
+ *   fd_lc_retire(t): forgets micro-batches with E[i] <= t ("current" means still running).
+ * The handle is host memory owned by the library until fd_lc_destroy.
+ */
+typedef struct fd_load_ctl fd_load_ctl;
+fd_load_ctl *fd_lc_create(int64_t S, int64_t W_lim);
+void fd_lc_destroy(fd_load_ctl *lc);
+int fd_lc_add_microbatch(fd_load_ctl *lc, int64_t t, int64_t m);
+int64_t fd_lc_earliest_step(const fd_load_ctl *lc, int64_t t, int64_t m);
+int64_t fd_lc_retire(fd_load_ctl *lc, int64_t t);
+int64_t fd_lc_count(const fd_load_ctl *lc);
+/* Copies up to `n` entries of (M[i], E[i], W[i]) into the caller's arrays; returns the count. */
+int64_t fd_lc_snapshot(const fd_load_ctl *lc, int64_t n, int64_t *M, int64_t *E, int64_t *W);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTDECODE_SCHED_H */

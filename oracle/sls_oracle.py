@@ -1,0 +1,52 @@
+"""Brute-force reference for the sequence-level load-stabilising schedule (FastDecode Section 4.2).
+
+TEST INFRASTRUCTURE ONLY.  Everything here is a literal simulation: every sequence is an object
+with a start step, and a step's load is the sum of the lengths of the sequences alive at that
+step.  It shares no code with the library's scheduler.
+
+Conventions (fixed by the worked example of Figure 7): a sequence started at step t has length
+s - t + 1 at step s and lives for S steps (s = t .. t+S-1), so its last step carries length S.
+"""
+from __future__ import annotations
+
+from typing import List, Sequence, Tuple
+
+
+def step_loads(starts: Sequence[Tuple[int, int]], S: int, n_steps: int) -> List[int]:
+    """Total cached length per step for micro-batches given as (start step, size)."""
+    loads = [0] * n_steps
+    for t0, m in starts:
+        for _ in range(m):                       # one sequence at a time, on purpose
+            for s in range(max(t0, 0), min(t0 + S, n_steps)):
+                loads[s] += s - t0 + 1
+    return loads
+
+
+def large_batch_starts(B: int, S: int, n_steps: int) -> List[Tuple[int, int]]:
+    """All B sequences start together, the next batch when they finish."""
+    return [(t, B) for t in range(0, n_steps, S)]
+
+
+def sls_starts(M: int, F: int, n_steps: int) -> List[Tuple[int, int]]:
+    """A micro-batch of M sequences every F steps."""
+    return [(t, M) for t in range(0, n_steps, F)]
+
+
+def earliest_start_brute_force(existing: Sequence[Tuple[int, int]], S: int, W_lim: int,
+                               t: int, m: int, horizon: int) -> int:
+    """Smallest start step >= t for a new micro-batch of m sequences such that the load at the
+    last step of every existing micro-batch stays <= W_lim (the quantity Algorithm 1 guards)."""
+    for cand in range(t, horizon):
+        ok = True
+        allmb = list(existing) + [(cand, m)]
+        for t0, _ in existing:
+            last = t0 + S - 1
+            if last < cand:
+                continue
+            load = sum(mm * (last - tt + 1) for tt, mm in allmb if tt <= last < tt + S)
+            if load > W_lim:
+                ok = False
+                break
+        if ok:
+            return cand
+    return horizon

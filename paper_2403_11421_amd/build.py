@@ -7,7 +7,7 @@ import sys
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_PKG)
-SOURCES = [os.path.join(_PKG, "csrc", "fd_rpart.hip")]
+SOURCES = [os.path.join(_PKG, "csrc", "fd_rpart.hip"), os.path.join(_PKG, "csrc", "fd_sched.cpp")]
 INCLUDE = os.path.join(_ROOT, "include")
 LIB = os.path.join(_PKG, "libfd_rpart.so")
 
@@ -33,7 +33,8 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = SOURCES + [os.path.join(_PKG, "csrc", "fd_rpartq.h"), os.path.join(INCLUDE, "fastdecode_rpart.h")]
+    deps = SOURCES + [os.path.join(_PKG, "csrc", "fd_rpartq.h"), os.path.join(INCLUDE, "fastdecode_rpart.h"),
+                      os.path.join(INCLUDE, "fastdecode_sched.h")]
     return any(os.path.getmtime(p) > t for p in deps)
 
 

@@ -1,0 +1,132 @@
+// Host-side scheduling arithmetic of FastDecode Section 4.2 (Eq. 5, Eq. 6, Figure 7,
+// Algorithm 1).  Integer only; see fastdecode_sched.h for the conventions.
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "fastdecode_rpart.h"
+#include "fastdecode_sched.h"
+
+struct fd_load_ctl {
+    int64_t S, W_lim;
+    std::vector<int64_t> M, E, W;
+};
+
+namespace {
+
+// load contributed at step s by m sequences started at step t0 (0 outside their S steps)
+inline int64_t contribution(int64_t m, int64_t t0, int64_t S, int64_t s)
+{
+    const int64_t age = s - t0;
+    return (age >= 0 && age < S) ? m * (age + 1) : 0;
+}
+
+} // namespace
+
+extern "C" {
+
+int64_t fd_sls_microbatch_size(int64_t B, int64_t F, int64_t S)
+{
+    if (B <= 0 || F <= 0 || S <= 0) return FD_EINVAL;
+    return std::max<int64_t>(1, B * F / S);
+}
+
+int64_t fd_sls_peak_load(int64_t M, int64_t F, int64_t S)
+{
+    if (M <= 0 || F <= 0 || S <= 0) return FD_EINVAL;
+    int64_t w = 0;
+    for (int64_t k = 1; k <= S / F; ++k) w += M * k * F;
+    return w;
+}
+
+int fd_sls_step_loads(int64_t M, int64_t F, int64_t S, int64_t n_steps, int64_t *loads)
+{
+    if (M <= 0 || F <= 0 || S <= 0 || n_steps < 0 || (n_steps > 0 && !loads)) return FD_EINVAL;
+    for (int64_t s = 0; s < n_steps; ++s) {
+        // micro-batches alive at step s started at multiples of F in (s - S, s]
+        int64_t w = 0;
+        for (int64_t t0 = s - s % F; t0 >= 0 && t0 > s - S; t0 -= F) w += contribution(M, t0, S, s);
+        loads[s] = w;
+    }
+    return FD_OK;
+}
+
+int fd_batch_step_loads(int64_t B, int64_t S, int64_t n_steps, int64_t *loads)
+{
+    if (B <= 0 || S <= 0 || n_steps < 0 || (n_steps > 0 && !loads)) return FD_EINVAL;
+    for (int64_t s = 0; s < n_steps; ++s) loads[s] = B * (s % S + 1);
+    return FD_OK;
+}
+
+fd_load_ctl *fd_lc_create(int64_t S, int64_t W_lim)
+{
+    if (S <= 0 || W_lim <= 0) return nullptr;
+    fd_load_ctl *lc = new (std::nothrow) fd_load_ctl;
+    if (lc) { lc->S = S; lc->W_lim = W_lim; }
+    return lc;
+}
+
+void fd_lc_destroy(fd_load_ctl *lc) { delete lc; }
+
+int fd_lc_add_microbatch(fd_load_ctl *lc, int64_t t, int64_t m)
+{
+    if (!lc || m <= 0) return FD_EINVAL;
+    // the new micro-batch's length at the last step of every one that already runs
+    int64_t own = m * lc->S;
+    for (size_t i = 0; i < lc->M.size(); ++i) {
+        if (lc->E[i] > t) lc->W[i] += (lc->E[i] - t) * m;
+        // a micro-batch started at this same step is as long as the new one at its last step
+        // (the paper's listing assumes one start per step and has no such term)
+        if (lc->E[i] == t + lc->S) own += lc->M[i] * lc->S;
+    }
+    lc->M.push_back(m);
+    lc->E.push_back(t + lc->S);
+    lc->W.push_back(own);
+    return FD_OK;
+}
+
+int64_t fd_lc_earliest_step(const fd_load_ctl *lc, int64_t t, int64_t m)
+{
+    if (!lc || m <= 0) return FD_EINVAL;
+    int64_t r = t;
+    for (size_t i = 0; i < lc->M.size(); ++i) {
+        if (lc->E[i] <= t) continue;                          // already finished: not current
+        const int64_t margin = lc->W_lim - lc->W[i];
+        // floor division (margin may be negative)
+        int64_t x = margin / m;
+        if (margin % m != 0 && margin < 0) --x;
+        r = std::max(r, lc->E[i] - x + 1);
+    }
+    return r;
+}
+
+int64_t fd_lc_retire(fd_load_ctl *lc, int64_t t)
+{
+    if (!lc) return FD_EINVAL;
+    size_t keep = 0;
+    for (size_t i = 0; i < lc->M.size(); ++i) {
+        if (lc->E[i] > t) {
+            lc->M[keep] = lc->M[i];
+            lc->E[keep] = lc->E[i];
+            lc->W[keep] = lc->W[i];
+            ++keep;
+        }
+    }
+    const int64_t dropped = (int64_t)(lc->M.size() - keep);
+    lc->M.resize(keep);
+    lc->E.resize(keep);
+    lc->W.resize(keep);
+    return dropped;
+}
+
+int64_t fd_lc_count(const fd_load_ctl *lc) { return lc ? (int64_t)lc->M.size() : FD_EINVAL; }
+
+int64_t fd_lc_snapshot(const fd_load_ctl *lc, int64_t n, int64_t *M, int64_t *E, int64_t *W)
+{
+    if (!lc || n < 0 || (n > 0 && (!M || !E || !W))) return FD_EINVAL;
+    const int64_t c = std::min<int64_t>(n, (int64_t)lc->M.size());
+    for (int64_t i = 0; i < c; ++i) { M[i] = lc->M[i]; E[i] = lc->E[i]; W[i] = lc->W[i]; }
+    return c;
+}
+
+} // extern "C"

@@ -1,0 +1,109 @@
+"""ctypes binding over ``include/fastdecode_sched.h`` (FastDecode Section 4.2, host integer logic)."""
+from __future__ import annotations
+
+import ctypes
+from typing import List, Tuple
+
+from . import rpart
+
+_i64 = ctypes.c_int64
+_configured = False
+
+
+def _lib():
+    global _configured
+    lib = rpart.load()
+    if not _configured:
+        P = ctypes.POINTER(_i64)
+        lib.fd_sls_microbatch_size.restype = _i64
+        lib.fd_sls_microbatch_size.argtypes = [_i64] * 3
+        lib.fd_sls_peak_load.restype = _i64
+        lib.fd_sls_peak_load.argtypes = [_i64] * 3
+        lib.fd_sls_step_loads.restype = ctypes.c_int
+        lib.fd_sls_step_loads.argtypes = [_i64] * 4 + [P]
+        lib.fd_batch_step_loads.restype = ctypes.c_int
+        lib.fd_batch_step_loads.argtypes = [_i64] * 3 + [P]
+        lib.fd_lc_create.restype = ctypes.c_void_p
+        lib.fd_lc_create.argtypes = [_i64, _i64]
+        lib.fd_lc_destroy.restype = None
+        lib.fd_lc_destroy.argtypes = [ctypes.c_void_p]
+        lib.fd_lc_add_microbatch.restype = ctypes.c_int
+        lib.fd_lc_add_microbatch.argtypes = [ctypes.c_void_p, _i64, _i64]
+        lib.fd_lc_earliest_step.restype = _i64
+        lib.fd_lc_earliest_step.argtypes = [ctypes.c_void_p, _i64, _i64]
+        lib.fd_lc_retire.restype = _i64
+        lib.fd_lc_retire.argtypes = [ctypes.c_void_p, _i64]
+        lib.fd_lc_count.restype = _i64
+        lib.fd_lc_count.argtypes = [ctypes.c_void_p]
+        lib.fd_lc_snapshot.restype = _i64
+        lib.fd_lc_snapshot.argtypes = [ctypes.c_void_p, _i64, P, P, P]
+        _configured = True
+    return lib
+
+
+EXPORTS = ("fd_sls_microbatch_size", "fd_sls_peak_load", "fd_sls_step_loads", "fd_batch_step_loads",
+           "fd_lc_create", "fd_lc_destroy", "fd_lc_add_microbatch", "fd_lc_earliest_step",
+           "fd_lc_retire", "fd_lc_count", "fd_lc_snapshot")
+
+
+def _ok(v: int, where: str) -> int:
+    if v < 0:
+        raise rpart.FdError(int(v), where)
+    return int(v)
+
+
+def sls_microbatch_size(B: int, F: int, S: int) -> int:
+    return _ok(_lib().fd_sls_microbatch_size(B, F, S), "fd_sls_microbatch_size")
+
+
+def sls_peak_load(M: int, F: int, S: int) -> int:
+    return _ok(_lib().fd_sls_peak_load(M, F, S), "fd_sls_peak_load")
+
+
+def sls_step_loads(M: int, F: int, S: int, n_steps: int) -> List[int]:
+    buf = (_i64 * max(1, n_steps))()
+    _ok(_lib().fd_sls_step_loads(M, F, S, n_steps, buf), "fd_sls_step_loads")
+    return list(buf)[:n_steps]
+
+
+def batch_step_loads(B: int, S: int, n_steps: int) -> List[int]:
+    buf = (_i64 * max(1, n_steps))()
+    _ok(_lib().fd_batch_step_loads(B, S, n_steps, buf), "fd_batch_step_loads")
+    return list(buf)[:n_steps]
+
+
+class LoadControl:
+    """Algorithm 1: bookkeeping of the current micro-batches and the earliest start step."""
+
+    def __init__(self, S: int, W_lim: int):
+        self._h = _lib().fd_lc_create(S, W_lim)
+        if not self._h:
+            raise rpart.FdError(rpart.FD_EINVAL, "fd_lc_create")
+
+    def close(self) -> None:
+        if self._h:
+            _lib().fd_lc_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def add_microbatch(self, t: int, m: int) -> None:
+        _ok(_lib().fd_lc_add_microbatch(self._h, t, m), "fd_lc_add_microbatch")
+
+    def earliest_step(self, t: int, m: int) -> int:
+        lib = _lib()
+        if m <= 0:
+            raise rpart.FdError(rpart.FD_EINVAL, "fd_lc_earliest_step")
+        return int(lib.fd_lc_earliest_step(self._h, t, m))
+
+    def retire(self, t: int) -> int:
+        return _ok(_lib().fd_lc_retire(self._h, t), "fd_lc_retire")
+
+    def __len__(self) -> int:
+        return _ok(_lib().fd_lc_count(self._h), "fd_lc_count")
+
+    def snapshot(self) -> List[Tuple[int, int, int]]:
+        n = len(self)
+        M, E, W = ((_i64 * max(1, n))() for _ in range(3))
+        c = _ok(_lib().fd_lc_snapshot(self._h, n, M, E, W), "fd_lc_snapshot")
+        return [(M[i], E[i], W[i]) for i in range(c)]

@@ -12,9 +12,12 @@ HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))
                       "include", "fastdecode_rpart.h")
 
 
-def _declared():
-    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
-    return sorted(set(re.findall(r"\b(fd_[a-z_]+)\s*\(", text)))
+SCHED_HEADER = os.path.join(os.path.dirname(HEADER), "fastdecode_sched.h")
+
+
+def _declared(path=HEADER):
+    text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(fd_[a-z_0-9]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported():
@@ -24,6 +27,11 @@ def test_every_declared_symbol_is_exported():
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(rpart.EXPORTS)
+    from paper_2403_11421_amd import sched
+    sched_names = _declared(SCHED_HEADER)
+    assert len(sched_names) >= 11 and set(sched_names) == set(sched.EXPORTS)
+    for n in sched_names:
+        assert hasattr(lib, n), n
 
 
 def test_version_and_strerror():
