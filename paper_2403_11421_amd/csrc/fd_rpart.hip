@@ -176,7 +176,8 @@ __device__ inline int length_bucket(int len, int T)
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
-    int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid, int max_items,
+    int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int cus, int wg_per_cu_max,
+    int max_items,
     int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
     int4 *__restrict__ items, int32_t *__restrict__ order)
 {
@@ -191,6 +192,15 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     for (int b = b0; b < b1; ++b) mine += clamp_len(seq_lens[b], seq_cap[b], &bad);
     const int total = block_sum(mine, sm);
     if (bad) atomicOr(status, FD_ST_BADLEN);
+
+    // One workgroup per CU streams long sequences best (a second one costs 1-2 %); when the
+    // sequences are short a unit is a few blocks and its latency is exposed, and a second
+    // workgroup per CU hides it (+6 % at 256 tokens per sequence).  The host launches
+    // wg_per_cu_max per CU; workgroups at or beyond `grid` leave at once.
+    int live = 0;
+    for (int b = b0; b < b1; ++b) live += clamp_len(seq_lens[b], seq_cap[b], &bad) > 0;
+    live = block_sum(live, sm);
+    const int grid = (wg_per_cu_max > 1 && live > 0 && total / live < 512) ? 2 * cus : cus;
 
     int T;
     if (chunk_req > 0) {
@@ -404,7 +414,8 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
     const int row = lane / LPR;
     const int col = lane % LPR;
     const int n_units = hdr[HDR_NITEMS] * H;
-    const int W = gridDim.x, g = blockIdx.x;
+    const int W = hdr[HDR_GRID], g = blockIdx.x;          // active workgroups, chosen by the planner
+    if (g >= W) return;
 
     // Static snake schedule over units in longest-first order: in round k this workgroup
     // owns unit k*W + g (even k) or k*W + W-1-g (odd k), which balances the token totals.
@@ -655,9 +666,8 @@ int block_tokens(int d) { return kWaves * kTileLoads * (d == 128 ? 4 : 8); }
 // chunk boundaries are multiples of this many tokens (one wave load of rows)
 int chunk_granule(int d) { return d == 128 ? 32 : 64; }
 
-// Persistent grid: one workgroup per compute unit.  Measured on MI355X, 4 waves per CU
-// with 16-32 KB of loads in flight each already saturate HBM, and a second resident
-// workgroup per CU lowers the achieved bandwidth by 1-2 %.
+// Compute units of the current device.  The streaming kernels are launched with two
+// workgroups per CU; the planner decides whether the second one takes part.
 int persistent_grid()
 {
     static int grid = 0;
@@ -738,7 +748,7 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, chunk_granule(desc->d), grid, (int)w.max_items, (int32_t *)ws,
+                       desc->chunk_tokens, chunk_granule(desc->d), grid, 2, (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
     return launched();
@@ -760,14 +770,14 @@ int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
     // scores are kept in the base-2 exponent domain: exp(x) = 2^(x * log2 e)
     const float qscale = (float)(1.4426950408889634 / (desc->d == 128 ? 11.313708498984761 : 8.0));
     if (desc->d == 128)
-        hipLaunchKernelGGL((rpart_partial_kernel<128, kTileLoads>), dim3(grid), dim3(kThreads), 0,
+        hipLaunchKernelGGL((rpart_partial_kernel<128, kTileLoads>), dim3(2 * grid), dim3(kThreads), 0,
                            (hipStream_t)stream, (const char *)desc->k_base,
                            (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
                            (const _Float16 *)q, (_Float16 *)out, desc->H, (const int32_t *)ws,
                            (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
                            (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale);
     else
-        hipLaunchKernelGGL((rpart_partial_kernel<64, kTileLoads>), dim3(grid), dim3(kThreads), 0,
+        hipLaunchKernelGGL((rpart_partial_kernel<64, kTileLoads>), dim3(2 * grid), dim3(kThreads), 0,
                            (hipStream_t)stream, (const char *)desc->k_base,
                            (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
                            (const _Float16 *)q, (_Float16 *)out, desc->H, (const int32_t *)ws,

@@ -206,7 +206,8 @@ __global__ __launch_bounds__(kThreads) void rpartq_partial_kernel(
     const int tok0 = wave * T::RPW + row;                  // this lane's token in a block, load 0
     const int own = T::own_token(lane, wave);              // token whose scales this lane loads
     const int n_units = hdr[HDR_NITEMS] * H;
-    const int W = gridDim.x, g = blockIdx.x;
+    const int W = hdr[HDR_GRID], g = blockIdx.x;          // active workgroups, chosen by the planner
+    if (g >= W) return;
 
     // same static schedule as the fp16 kernel
     const int n_rounds = (int)(((long long)n_units + W - 1) / W);
@@ -430,7 +431,8 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, 64, grid, (int)w.max_items, (int32_t *)ws,
+                       desc->chunk_tokens, 64, grid, 1 /* its registers allow one workgroup per CU */,
+                       (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
     return launched();

@@ -122,6 +122,10 @@ CONFIGS: Dict[str, RPartConfig] = {
                                     len_mean=1024, n_layers=40),
     # capacity stress: 2048 sequences of 1024..2048 tokens
     "c5_capacity": RPartConfig("c5_capacity", 2048, 32, 128, "uniform", 1024, 2048),
+    # the workload behind the paper's Table 2 (one block of a 7B model, 256 cached tokens per
+    # sequence: 4.19 MB of KV per sequence, Table 3), at its two batch sizes -- context only
+    "t2_batch1": RPartConfig("t2_batch1", 1, 32, 128, "const", 255, 255),
+    "t2_batch1024": RPartConfig("t2_batch1024", 1024, 32, 128, "const", 255, 255),
 }
 
 

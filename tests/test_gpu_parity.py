@@ -74,6 +74,19 @@ def test_minimal_workspace_forces_long_chunks():
     assert e.value.code == rpart.FD_EWORKSPACE
 
 
+def test_active_workgroups_follow_the_mean_length():
+    """Short sequences get two workgroups per compute unit, long ones one; both give the same
+    answer as the oracle (the fp16 kernel is launched with two per CU either way)."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    cfg = _cfg("grid", 40, 4, 128)
+    short = DeviceCase(cfg, [0] * 8 + [100 + 13 * i for i in range(32)], seed=21)
+    check_step(short)
+    assert rpart.fd_plan_info(short.ws)["grid"] == 2 * cus
+    long_ = DeviceCase(cfg, [0] * 8 + [600 + 13 * i for i in range(32)], seed=22)
+    check_step(long_)
+    assert rpart.fd_plan_info(long_.ws)["grid"] == cus
+
+
 def test_decode_without_append_and_empty_sequences():
     cfg = _cfg("empty", 4, 2, 128)
     case = DeviceCase(cfg, [0, 10, 0, 300], seed=2)
