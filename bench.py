@@ -116,6 +116,86 @@ def schedule_mode(args) -> int:
     return 0
 
 
+def pipeline_mode(args) -> int:
+    """Token step of an N-block model with two mini-batches (Section 4.1's token-level pipeline
+    as the R-worker sees it): blocks A0, B0, A1, B1, ... each append + attend.  Three ways of
+    issuing the same work, one JSON line each:
+      serial   one stream, every block plans for itself (fd_rpart_step)
+      shared   one stream, one plan per mini-batch and token (fd_rpart_layer_step)
+      overlap  as shared, each mini-batch on its own stream
+    Cached lengths grow by one per token step; the bytes are summed exactly."""
+    import torch
+    from paper_2403_11421_amd import rpart, workloads as W
+    from paper_2403_11421_amd.pipeline import RWorker
+
+    cfg = W.CONFIGS[args.config]
+    N, dev = args.layers, torch.device("cuda:0")
+    Bm = cfg.B // 2                                           # the batch split into mini-batches A and B
+    lens = W.seq_lens(cfg)
+    mb_lens = [lens[:Bm], lens[Bm:2 * Bm]]
+    n_tokens = args.warmup + args.steps
+    sub = [W.RPartConfig(f"{cfg.name}_mb{m}", Bm, cfg.H, cfg.d, "const", 0, 0, scale=cfg.scale)
+           for m in range(2)]
+    bpt = cfg.bytes_per_token() if args.kv == "fp16" else 2 * cfg.H * (cfg.d + 4)
+    rw = RWorker(cfg.H, cfg.d, N, [[L + n_tokens + 1 for L in l] for l in mb_lens],
+                 kv=args.kv, n_streams=2, device=dev)
+    for m in range(2):
+        c0 = rw.caches[m][0]
+        for b, L in enumerate(mb_lens[m]):
+            if L:
+                c0.fill("K", b, W.gen_cache_block(cfg, "K", m * Bm + b, L, W.DEFAULT_SEED, dev))
+                c0.fill("V", b, W.gen_cache_block(cfg, "V", m * Bm + b, L, W.DEFAULT_SEED, dev))
+        for c in rw.caches[m][1:]:                         # values do not affect the timing
+            for name in (("k", "v") if args.kv == "fp16" else ("k_codes", "v_codes", "k_scale", "v_scale")):
+                getattr(c, name).copy_(getattr(c0, name))
+    vec = [[{w: W.gen_vectors(sub[m], w, 100 + l, dev) for w in ("q", "k_new", "v_new")}
+            for l in range(N)] for m in range(2)]
+    q = [[vec[m][l]["q"] for l in range(N)] for m in range(2)]
+    kn = [[vec[m][l]["k_new"] for l in range(N)] for m in range(2)]
+    vn = [[vec[m][l]["v_new"] for l in range(N)] for m in range(2)]
+    out = [[torch.empty_like(q[m][l]) for l in range(N)] for m in range(2)]
+    step_fn = rpart.fd_rpartq_step if args.kv == "int8" else rpart.fd_rpart_step
+    for mode in ("serial", "shared", "overlap"):                                 # same caches for all
+        for m in range(2):
+            rw.set_lens(m, mb_lens[m])
+        rw.use_streams(2 if mode == "overlap" else 1)
+
+        def token():
+            if mode == "serial":
+                for l in range(N):
+                    for m in range(2):
+                        step_fn(rw.caches[m][l].desc, q[m][l], kn[m][l], vn[m][l], out[m][l], rw.ws[m])
+            else:
+                rw.token_step(q, kn, vn, out)
+
+        for _ in range(args.warmup):
+            token()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            token()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        assert rw.status() == 0
+        tokens = sum(sum(L + args.warmup + s + 1 for L in l) for l in mb_lens for s in range(args.steps))
+        kv_bytes = bpt * tokens * N
+        ms = dt / args.steps * 1e3
+        value = kv_bytes / dt / 1e9
+        print(json.dumps({
+            "metric": METRIC, "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"{cfg.name} split into two mini-batches of {Bm}, {N} blocks, "
+                                   f"{args.kv} KV, one token step = {2 * N} block steps",
+                       "issue": mode, "layers": N, "kv_bytes_per_step": kv_bytes // args.steps},
+            "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+            "ms_per_block_step": ms / (2 * N),
+            "tokens_per_s": 2 * Bm / (ms * 1e-3) * N / cfg.n_layers,
+            # Section 4.3's R: latency of this R-worker per cached token and block
+            "R_ns_per_cached_token": dt * 1e9 / (tokens * N)}), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,6 +211,10 @@ def main() -> int:
                     help="instead of the fixed-length step, run a multi-step decode loop under the "
                          "large-batch or the load-stabilising schedule (Section 4.2) and report the "
                          "per-step R-Part latency")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="instead of the one-layer step, run token steps of an N-block model with "
+                         "two mini-batches (Section 4.1) and compare three ways of issuing them")
+    ap.add_argument("--layers", type=int, default=8, help="blocks held by --pipeline")
     ap.add_argument("--sched-B", type=int, default=1024)
     ap.add_argument("--sched-S", type=int, default=1024)
     ap.add_argument("--sched-F", type=int, default=16)
@@ -154,6 +238,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.schedule != "none":
         return schedule_mode(args)
+    if args.pipeline:
+        return pipeline_mode(args)
     cfg = W.CONFIGS[args.config]
     seed = W.DEFAULT_SEED if args.seed is None else args.seed
     lens = W.seq_lens(cfg, seed)

@@ -198,6 +198,27 @@ int fd_rpartq_step(const fd_kvq_desc *desc, const void *q, const void *k_new, co
                    void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * One transformer block's share of a token step (Section 4.1: for every block the R-worker
+ * receives Q_i, K_i, V_i of a mini-batch, appends, attends and returns O_i; Section 5.3: the
+ * caches of different blocks are independent).  All blocks of one mini-batch hold the same
+ * sequences at the same lengths, so the ragged plan is the same for each of them:
+ *   replan != 0  append, plan from this layer's lengths, attend      (first block of a step)
+ *   replan == 0  append, attend with the plan already in `workspace` (the other blocks)
+ * `layer` describes this block's cache; every block of the mini-batch must use the same B, H,
+ * d, chunk_tokens, seq_cap values and seq_off values, its own seq_lens array holding the
+ * same lengths as the block that planned, and the same workspace.  If the lengths differ the
+ * result is wrong but every access stays inside the block's slabs.  Two mini-batches with their
+ * own workspaces may run on two streams at once (the token-level pipeline of Section 4.1).
+ * The int8 variant has the same contract.
+ */
+int fd_rpart_layer_step(const fd_kv_desc *layer, const void *q, const void *k_new,
+                        const void *v_new, void *out, void *workspace, size_t workspace_bytes,
+                        int replan, void *stream);
+int fd_rpartq_layer_step(const fd_kvq_desc *layer, const void *q, const void *k_new,
+                         const void *v_new, void *out, void *workspace, size_t workspace_bytes,
+                         int replan, void *stream);
+
+/*
  * Measurement aid, not part of the R-Part: enqueue a kernel that only reads
  * `buf` (device, 16-byte aligned) with the same 128-bit streaming loads as the
  * attention kernel, so a harness can time the device's pure-read ceiling next to

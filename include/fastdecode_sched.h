@@ -61,6 +61,28 @@ int64_t fd_lc_count(const fd_load_ctl *lc);
 /* Copies up to `n` entries of (M[i], E[i], W[i]) into the caller's arrays; returns the count. */
 int64_t fd_lc_snapshot(const fd_load_ctl *lc, int64_t n, int64_t *M, int64_t *E, int64_t *W);
 
+/*
+ * Section 4.3 (workload-balanced hardware selection).  T_B is the measured latency of the
+ * S-Part of one transformer block at batch size B, R the measured R-Part latency of one
+ * R-worker per cached token and block, both in the same time unit; N blocks, sequences of
+ * up to S tokens.  The double-valued functions return NaN on bad arguments.
+ *   fd_model_sequence_latency   Eq. 7, left side: 2 * N * S * T(B), the time to generate one
+ *                               sequence when S-Part and R-Part take equally long.
+ *   fd_model_max_batch          Eq. 7: the largest batch size of a measured table
+ *                               (Bs[i], T[i]), i < n, whose sequence latency is <= L;
+ *                               0 if none qualifies.
+ *   fd_model_sworker_throughput Eq. 8: E(B) = B / T(B).
+ *   fd_model_min_rworkers_memory  Eq. 9: the least P with B*S/2 <= C*P, C = tokens of K and V
+ *                               one R-worker can hold.
+ *   fd_model_num_rworkers       Eq. 11: P = B*S*R / (2*T(B)) = S*R*E(B)/2, not rounded.
+ */
+double fd_model_sequence_latency(int64_t N, int64_t S, double T_B);
+int64_t fd_model_max_batch(int64_t N, int64_t S, double L, const int64_t *Bs, const double *T,
+                           int64_t n);
+double fd_model_sworker_throughput(int64_t B, double T_B);
+int64_t fd_model_min_rworkers_memory(int64_t B, int64_t S, int64_t C);
+double fd_model_num_rworkers(int64_t B, int64_t S, double R, double T_B);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,3 +50,31 @@ def earliest_start_brute_force(existing: Sequence[Tuple[int, int]], S: int, W_li
         if ok:
             return cand
     return horizon
+
+
+# ---------------------------------------------------------------------------
+# Section 4.3, written out with exact rationals
+# ---------------------------------------------------------------------------
+def model_sequence_latency(N, S, T_B):
+    """Eq. 7, left side: S tokens, N blocks per token, an S-Part and an equally long R-Part each."""
+    from fractions import Fraction
+    total = Fraction(0)
+    for _token in range(S):
+        for _block in range(N):
+            total += Fraction(T_B) + Fraction(T_B)
+    return total
+
+
+def model_num_rworkers(B, S, R, T_B):
+    """Eq. 10 solved for P: B sequences of mean length S/2 spread over P workers take
+    (B*S/2/P)*R per block, which is to equal T_B."""
+    from fractions import Fraction
+    return Fraction(B) * Fraction(S) / 2 * Fraction(R) / Fraction(T_B)
+
+
+def model_min_rworkers_memory(B, S, C):
+    """Eq. 9: smallest integer P with B*S/2 <= C*P, by search."""
+    P = 1
+    while 2 * C * P < B * S:
+        P += 1
+    return P

@@ -847,6 +847,30 @@ int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, cons
     return fd_rpart_decode(desc, q, out, workspace, workspace_bytes, stream);
 }
 
+int fd_rpart_layer_step(const fd_kv_desc *layer, const void *q, const void *k_new,
+                        const void *v_new, void *out, void *workspace, size_t workspace_bytes,
+                        int replan, void *stream)
+{
+    int rc = check_desc(layer);
+    if (rc != FD_OK) return rc;
+    if (layer->B == 0) return FD_OK;
+    if (!q || !out || !k_new || !v_new || !aligned(q, 16) || !aligned(out, 16) ||
+        !aligned(k_new, 16) || !aligned(v_new, 16))
+        return FD_EINVAL;
+    WsLayout w;
+    rc = check_ws(layer, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    rc = fd_kv_append(layer, k_new, v_new, stream);
+    if (rc != FD_OK) return rc;
+    if (replan) {
+        rc = fd_rpart_plan(layer, workspace, workspace_bytes, stream);
+        if (rc != FD_OK) return rc;
+    }
+    rc = fd_rpart_partial(layer, q, out, workspace, workspace_bytes, stream);
+    if (rc != FD_OK) return rc;
+    return fd_rpart_merge(layer, out, workspace, workspace_bytes, stream);
+}
+
 int fd_hbm_read_probe(const void *buf, size_t bytes, int32_t *sink, size_t *bytes_read, void *stream)
 {
     if (!buf || !sink || !bytes_read || !aligned(buf, 16)) return FD_EINVAL;

@@ -514,4 +514,28 @@ int fd_rpartq_step(const fd_kvq_desc *desc, const void *q, const void *k_new, co
     return fd_rpartq_decode(desc, q, out, workspace, workspace_bytes, stream);
 }
 
+int fd_rpartq_layer_step(const fd_kvq_desc *layer, const void *q, const void *k_new,
+                         const void *v_new, void *out, void *workspace, size_t workspace_bytes,
+                         int replan, void *stream)
+{
+    int rc = check_qdesc(layer);
+    if (rc != FD_OK) return rc;
+    if (layer->B == 0) return FD_OK;
+    if (!q || !out || !k_new || !v_new || !aligned(q, 16) || !aligned(out, 16) ||
+        !aligned(k_new, 16) || !aligned(v_new, 16))
+        return FD_EINVAL;
+    WsLayout w;
+    rc = check_qws(layer, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    rc = fd_kvq_append(layer, k_new, v_new, stream);
+    if (rc != FD_OK) return rc;
+    if (replan) {
+        rc = fd_rpartq_plan(layer, workspace, workspace_bytes, stream);
+        if (rc != FD_OK) return rc;
+    }
+    rc = fd_rpartq_partial(layer, q, out, workspace, workspace_bytes, stream);
+    if (rc != FD_OK) return rc;
+    return fd_rpartq_merge(layer, out, workspace, workspace_bytes, stream);
+}
+
 } // extern "C"

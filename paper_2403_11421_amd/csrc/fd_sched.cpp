@@ -1,6 +1,7 @@
 // Host-side scheduling arithmetic of FastDecode Section 4.2 (Eq. 5, Eq. 6, Figure 7,
 // Algorithm 1).  Integer only; see fastdecode_sched.h for the conventions.
 #include <algorithm>
+#include <cmath>
 #include <new>
 #include <vector>
 
@@ -127,6 +128,47 @@ int64_t fd_lc_snapshot(const fd_load_ctl *lc, int64_t n, int64_t *M, int64_t *E,
     const int64_t c = std::min<int64_t>(n, (int64_t)lc->M.size());
     for (int64_t i = 0; i < c; ++i) { M[i] = lc->M[i]; E[i] = lc->E[i]; W[i] = lc->W[i]; }
     return c;
+}
+
+// ---------------------------------------------------------------------------
+// Section 4.3: batch size and number of R-workers from two measured quantities
+// ---------------------------------------------------------------------------
+double fd_model_sequence_latency(int64_t N, int64_t S, double T_B)
+{
+    if (N <= 0 || S <= 0 || !(T_B > 0)) return std::nan("");
+    return 2.0 * (double)N * (double)S * T_B;
+}
+
+int64_t fd_model_max_batch(int64_t N, int64_t S, double L, const int64_t *Bs, const double *T,
+                           int64_t n)
+{
+    if (N <= 0 || S <= 0 || !(L > 0) || n < 0 || (n > 0 && (!Bs || !T))) return FD_EINVAL;
+    int64_t best = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (Bs[i] <= 0 || !(T[i] > 0)) return FD_EINVAL;
+        if (fd_model_sequence_latency(N, S, T[i]) <= L) best = std::max(best, Bs[i]);
+    }
+    return best;
+}
+
+double fd_model_sworker_throughput(int64_t B, double T_B)
+{
+    if (B <= 0 || !(T_B > 0)) return std::nan("");
+    return (double)B / T_B;
+}
+
+int64_t fd_model_min_rworkers_memory(int64_t B, int64_t S, int64_t C)
+{
+    if (B <= 0 || S <= 0 || C <= 0) return FD_EINVAL;
+    if (B > INT64_MAX / S) return FD_EINVAL;
+    const int64_t twoC = 2 * C;                      // B*S/2 <= C*P  <=>  P >= B*S / (2C)
+    return (B * S + twoC - 1) / twoC;
+}
+
+double fd_model_num_rworkers(int64_t B, int64_t S, double R, double T_B)
+{
+    if (B <= 0 || S <= 0 || !(R > 0) || !(T_B > 0)) return std::nan("");
+    return (double)B * (double)S * R / (2.0 * T_B);
 }
 
 } // extern "C"

@@ -78,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.fd_rpart_merge.argtypes = [P, _vp, _vp, ctypes.c_size_t, _vp]
     lib.fd_rpart_step.restype = ctypes.c_int
     lib.fd_rpart_step.argtypes = [P, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.fd_rpart_layer_step.restype = ctypes.c_int
+    lib.fd_rpart_layer_step.argtypes = [P, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, ctypes.c_int, _vp]
     lib.fd_kv_reset.restype = ctypes.c_int
     lib.fd_kv_reset.argtypes = [P, _vp, ctypes.c_int32, _vp]
     lib.fd_read_status.restype = ctypes.c_int
@@ -91,7 +93,9 @@ def load() -> ctypes.CDLL:
                        ("fd_rpartq_partial", [Q, _vp, _vp, _vp, ctypes.c_size_t, _vp]),
                        ("fd_rpartq_merge", [Q, _vp, _vp, ctypes.c_size_t, _vp]),
                        ("fd_rpartq_decode", [Q, _vp, _vp, _vp, ctypes.c_size_t, _vp]),
-                       ("fd_rpartq_step", [Q, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp])):
+                       ("fd_rpartq_step", [Q, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]),
+                       ("fd_rpartq_layer_step", [Q, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t,
+                                                 ctypes.c_int, _vp])):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = args
     lib.fd_hbm_read_probe.restype = ctypes.c_int
@@ -104,7 +108,7 @@ EXPORTS = ("fd_version", "fd_strerror", "fd_workspace_bytes", "fd_kv_append", "f
            "fd_rpart_plan", "fd_rpart_partial", "fd_rpart_merge", "fd_rpart_step", "fd_kv_reset",
            "fd_read_status", "fd_plan_info", "fd_hbm_read_probe",
            "fd_kvq_append", "fd_kvq_reset", "fd_rpartq_plan", "fd_rpartq_partial", "fd_rpartq_merge",
-           "fd_rpartq_decode", "fd_rpartq_step")
+           "fd_rpartq_decode", "fd_rpartq_step", "fd_rpart_layer_step", "fd_rpartq_layer_step")
 
 
 def version() -> int:
@@ -243,3 +247,14 @@ def fd_rpartq_step(desc: fd_kvq_desc, q: torch.Tensor, k_new: torch.Tensor, v_ne
     p, n = _ws(workspace)
     _check(load().fd_rpartq_step(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out),
                                  p, n, _stream()), "fd_rpartq_step")
+
+
+def fd_rpart_layer_step(layer, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                        out: torch.Tensor, workspace: torch.Tensor, replan: bool) -> None:
+    """One block's append + attend; `layer` is an fd_kv_desc or an fd_kvq_desc."""
+    p, n = _ws(workspace)
+    quant = isinstance(layer, fd_kvq_desc)
+    f = load().fd_rpartq_layer_step if quant else load().fd_rpart_layer_step
+    _check(f(ctypes.byref(layer), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), p, n,
+             1 if replan else 0, _stream()),
+           "fd_rpartq_layer_step" if quant else "fd_rpart_layer_step")

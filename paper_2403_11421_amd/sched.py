@@ -2,7 +2,7 @@
 from __future__ import annotations
 
 import ctypes
-from typing import List, Tuple
+from typing import List, Sequence, Tuple
 
 from . import rpart
 
@@ -37,13 +37,26 @@ def _lib():
         lib.fd_lc_count.argtypes = [ctypes.c_void_p]
         lib.fd_lc_snapshot.restype = _i64
         lib.fd_lc_snapshot.argtypes = [ctypes.c_void_p, _i64, P, P, P]
+        _f64 = ctypes.c_double
+        lib.fd_model_sequence_latency.restype = _f64
+        lib.fd_model_sequence_latency.argtypes = [_i64, _i64, _f64]
+        lib.fd_model_max_batch.restype = _i64
+        lib.fd_model_max_batch.argtypes = [_i64, _i64, _f64, P, ctypes.POINTER(_f64), _i64]
+        lib.fd_model_sworker_throughput.restype = _f64
+        lib.fd_model_sworker_throughput.argtypes = [_i64, _f64]
+        lib.fd_model_min_rworkers_memory.restype = _i64
+        lib.fd_model_min_rworkers_memory.argtypes = [_i64, _i64, _i64]
+        lib.fd_model_num_rworkers.restype = _f64
+        lib.fd_model_num_rworkers.argtypes = [_i64, _i64, _f64, _f64]
         _configured = True
     return lib
 
 
 EXPORTS = ("fd_sls_microbatch_size", "fd_sls_peak_load", "fd_sls_step_loads", "fd_batch_step_loads",
            "fd_lc_create", "fd_lc_destroy", "fd_lc_add_microbatch", "fd_lc_earliest_step",
-           "fd_lc_retire", "fd_lc_count", "fd_lc_snapshot")
+           "fd_lc_retire", "fd_lc_count", "fd_lc_snapshot",
+           "fd_model_sequence_latency", "fd_model_max_batch", "fd_model_sworker_throughput",
+           "fd_model_min_rworkers_memory", "fd_model_num_rworkers")
 
 
 def _ok(v: int, where: str) -> int:
@@ -107,3 +120,35 @@ class LoadControl:
         M, E, W = ((_i64 * max(1, n))() for _ in range(3))
         c = _ok(_lib().fd_lc_snapshot(self._h, n, M, E, W), "fd_lc_snapshot")
         return [(M[i], E[i], W[i]) for i in range(c)]
+
+
+# ---------------------------------------------------------------------------
+# Section 4.3: batch size and number of R-workers from the measured T(B) and R
+# ---------------------------------------------------------------------------
+def _finite(v: float, where: str) -> float:
+    if v != v:
+        raise rpart.FdError(rpart.FD_EINVAL, where)
+    return float(v)
+
+
+def model_sequence_latency(N: int, S: int, T_B: float) -> float:
+    return _finite(_lib().fd_model_sequence_latency(N, S, T_B), "fd_model_sequence_latency")
+
+
+def model_max_batch(N: int, S: int, L: float, table: Sequence[Tuple[int, float]]) -> int:
+    n = len(table)
+    Bs = (_i64 * max(1, n))(*[b for b, _ in table])
+    T = (ctypes.c_double * max(1, n))(*[t for _, t in table])
+    return _ok(_lib().fd_model_max_batch(N, S, L, Bs, T, n), "fd_model_max_batch")
+
+
+def model_sworker_throughput(B: int, T_B: float) -> float:
+    return _finite(_lib().fd_model_sworker_throughput(B, T_B), "fd_model_sworker_throughput")
+
+
+def model_min_rworkers_memory(B: int, S: int, C: int) -> int:
+    return _ok(_lib().fd_model_min_rworkers_memory(B, S, C), "fd_model_min_rworkers_memory")
+
+
+def model_num_rworkers(B: int, S: int, R: float, T_B: float) -> float:
+    return _finite(_lib().fd_model_num_rworkers(B, S, R, T_B), "fd_model_num_rworkers")

@@ -155,3 +155,62 @@ def test_retire_forgets_finished_microbatches():
         lc.add_microbatch(t, 2)
     assert len(lc) == 3 and lc.retire(4) == 1 and lc.retire(5) == 1 and len(lc) == 1
     assert lc.snapshot()[0][:2] == (2, 9)
+
+
+# ---------------------------------------------------------------------------
+# Section 4.3: Eq. 7 - Eq. 11
+# ---------------------------------------------------------------------------
+def test_oracle_model_pins():
+    """Pins that do not restate the formulas: the half-load premise of Eq. 9 / Eq. 10 against
+    the simulated schedule, and hand-worked numbers."""
+    # in steady state the load-stabilised schedule holds B*(S+1)/2 cached tokens on average:
+    # the "B*S/2" of Eq. 9 and Eq. 10 up to the 1/S the text drops
+    B, S, F = 64, 32, 4
+    M = B * F // S
+    loads = O.step_loads(O.sls_starts(M, F, 40 * S), S, 40 * S)[4 * S:36 * S]
+    mean = sum(loads) / len(loads)
+    assert abs(mean - B * (S + 1) / 2) < 1e-9
+    # with P from Eq. 11 the R-workers take T(B) per block on that mean load (to the same 1/S)
+    R, T_B = 3, 50
+    P = O.model_num_rworkers(B, S, R, T_B)
+    assert abs(float(mean * R / P) / T_B - (S + 1) / S) < 1e-12
+    # hand-worked: 1024 sequences of 1024 tokens, R = 1 ns, T = 1 ms -> 0.524288 workers
+    assert float(O.model_num_rworkers(1024, 1024, 1, 1000000)) == 0.524288
+    assert O.model_sequence_latency(32, 1024, 2) == 2 * 32 * 1024 * 2
+    assert O.model_min_rworkers_memory(1024, 1024, 100000) == 6        # 524288 / 100000 -> 6
+    assert O.model_min_rworkers_memory(8, 4, 16) == 1 and O.model_min_rworkers_memory(8, 4, 15) == 2
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_library_model_matches_oracle(seed):
+    rng = random.Random(seed)
+    for _ in range(50):
+        N, S, B = rng.randint(1, 96), rng.choice([rng.randint(1, 40), rng.randint(1, 4096)]), rng.randint(1, 4096)
+        T_B = rng.randint(1, 10 ** 6) / 64.0                # exact in binary64
+        R = rng.randint(1, 10 ** 4) / 1024.0
+        C = rng.randint(1, 10 ** 6)
+        if S * N <= 4096:              # the oracle's literal loop is only run on small cases
+            assert sched.model_sequence_latency(N, S, T_B) == float(O.model_sequence_latency(N, S, T_B))
+        assert sched.model_sequence_latency(N, S, T_B) == 2.0 * N * S * T_B
+        got = sched.model_num_rworkers(B, S, R, T_B)
+        assert abs(got - float(O.model_num_rworkers(B, S, R, T_B))) <= 1e-12 * got
+        assert sched.model_sworker_throughput(B, T_B) == B / T_B
+        assert sched.model_min_rworkers_memory(B, S, C) == O.model_min_rworkers_memory(B, S, C)
+
+
+def test_model_max_batch_and_bad_arguments():
+    table = [(1, 0.5), (64, 0.6), (256, 1.0), (1024, 3.0)]     # (B, T(B)) in ms
+    N, S = 32, 1024
+    # 2*N*S*T <= L: L = 70 s admits T <= 1.068 ms
+    assert sched.model_max_batch(N, S, 70000.0, table) == 256
+    assert sched.model_max_batch(N, S, 10.0, table) == 0
+    assert sched.model_max_batch(N, S, 1e9, table) == 1024
+    assert sched.model_max_batch(N, S, 2 * N * S * 0.6, table) == 64      # boundary is inclusive
+    for bad in (lambda: sched.model_sequence_latency(0, 1, 1.0),
+                lambda: sched.model_num_rworkers(1, 1, 0.0, 1.0),
+                lambda: sched.model_num_rworkers(1, 1, 1.0, float("nan")),
+                lambda: sched.model_sworker_throughput(0, 1.0),
+                lambda: sched.model_min_rworkers_memory(1, 1, 0),
+                lambda: sched.model_max_batch(1, 1, 1.0, [(0, 1.0)])):
+        with pytest.raises(rpart.FdError):
+            bad()
