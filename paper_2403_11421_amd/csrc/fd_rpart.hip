@@ -130,6 +130,7 @@ __global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, const int32_t *_
 // is the longest-processing-time rule for units that are small against a
 // workgroup's share.
 // ---------------------------------------------------------------------------
+constexpr int kTwoWgBelow = 512;   // fp16 kernel: second workgroup per CU below this mean length
 constexpr int kBuckets = 256;
 
 __device__ inline int block_sum(int v, int *sm)
@@ -176,8 +177,8 @@ __device__ inline int length_bucket(int len, int T)
 
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
-    int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int cus, int wg_per_cu_max,
-    int max_items,
+    int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid_long, int grid_short,
+    int short_below, int hashed, int max_items,
     int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
     int4 *__restrict__ items, int32_t *__restrict__ order)
 {
@@ -195,12 +196,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
 
     // One workgroup per CU streams long sequences best (a second one costs 1-2 %); when the
     // sequences are short a unit is a few blocks and its latency is exposed, and a second
-    // workgroup per CU hides it (+6 % at 256 tokens per sequence).  The host launches
-    // wg_per_cu_max per CU; workgroups at or beyond `grid` leave at once.
+    // workgroup per CU hides it (+6 % at 256 tokens per sequence).  The caller names the number
+    // of workgroups for long and for short sequences and the mean length that separates them;
+    // the host launches the larger number and workgroups at or beyond `grid` leave at once.
     int live = 0;
     for (int b = b0; b < b1; ++b) live += clamp_len(seq_lens[b], seq_cap[b], &bad) > 0;
     live = block_sum(live, sm);
-    const int grid = (wg_per_cu_max > 1 && live > 0 && total / live < 512) ? 2 * cus : cus;
+    const int grid = (live > 0 && total / live < short_below) ? grid_short : grid_long;
 
     int T;
     if (chunk_req > 0) {
@@ -260,21 +262,40 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         if (tid < kBuckets) hist[tid] = start;
     }
     __syncthreads();
-    pos = first;
-    for (int b = b0; b < b1; ++b) {
-        const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
-        const int n = (L + T - 1) / T;
+    // Scatter.  Inside a bucket the order is the arrival order of the atomics.  With `hashed` the
+    // sequences are visited in a scrambled order (a bijection of [0, B)): equal-length sequences
+    // then run side by side in no regular pattern.  A regular one can put the streams that run
+    // in lockstep a constant distance apart, and for some distances (2^a + 2^(a+8) bytes was
+    // seen) they then fight over the same DRAM banks all the way: -10 % on the int8 kernel.
+    int bits = 1;
+    while ((1 << bits) < B) ++bits;
+    const unsigned mask = (1u << bits) - 1u;
+    const int half = (bits + 1) / 2;
+    for (int j = b0; j < b1; ++j) {
+        int b = j;
+        if (hashed) {
+            unsigned x = (unsigned)j;
+            do {                                            // cycle-walk back into [0, B)
+                x = (x * 0x9E3779B1u) & mask;
+                x ^= x >> half;
+                x = (x * 0x85EBCA6Bu) & mask;
+                x ^= x >> half;
+            } while (x >= (unsigned)B);
+            b = (int)x;
+        }
+        const int n = nchunk[b];
+        const int base = item0[b];
         if (n > 0) {
+            const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
             int len = (L + n - 1) / n;
             len = (len + granule - 1) / granule * granule;
             for (int k = 0; k < n; ++k) {
                 const int t0 = k * len;
                 const int t1 = min(L, t0 + len);
-                if (pos + k < max_items)
-                    order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = pos + k;
+                if (base + k < max_items)
+                    order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = base + k;
             }
         }
-        pos += n;
     }
     if (tid == 0) {
         hdr[HDR_NITEMS] = count <= max_items ? count : 0;
@@ -748,7 +769,8 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, chunk_granule(desc->d), grid, 2, (int)w.max_items, (int32_t *)ws,
+                       desc->chunk_tokens, chunk_granule(desc->d), grid, 2 * grid, kTwoWgBelow, 0,
+                       (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
     return launched();

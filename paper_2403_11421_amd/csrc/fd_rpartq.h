@@ -77,10 +77,10 @@ __global__ __launch_bounds__(256) void kvq_append_kernel(
 
 // ---------------------------------------------------------------------------
 // Streaming kernel over int8 codes, d = 128.  A row is 128 B = 8 lanes x 16 codes; a wave
-// load covers 8 tokens; a workgroup block is 4 waves x 8 loads = 256 tokens (32 KB of K codes
-// and 32 KB of V codes).  The 64 tokens of a wave's tile map one-to-one onto its 64 lanes for
-// the scales: each lane loads the K and the V scale of "its" token and the values are handed to
-// the lanes that need them with a cross-lane read.
+// load covers 8 tokens; a workgroup block is 4 waves x NL loads = 32 NL tokens (4 NL KB of K
+// codes and as much of V codes).  The 8 NL tokens of a wave's tile map onto its first 8 NL lanes
+// for the scales: each lane loads the K and the V scale of "its" token (the other lanes repeat
+// them) and the values are handed to the lanes that need them with a cross-lane read.
 //
 // Dequantisation is folded into the arithmetic: with u = code + 128,
 //   q . k   = scale_k * (sum_i q_i u_i - 128 * sum_i q_i)
@@ -94,9 +94,18 @@ __device__ inline u32x4 ld_stream_u(const char *p)
     return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
 }
 
-struct TileQ8 {
+// Tile size and residency, measured on MI355X over the two-block rolling prefetch below: two
+// wave loads per tile and two workgroups per CU (187 VGPRs, two waves per SIMD) stream 6.9 TB/s
+// at 2048 tokens per sequence and 6.1 TB/s at 256; eight loads per tile with one workgroup per
+// CU (the fp16 kernel's shape) reach 6.2 and 3.3: this kernel has 2.5 x the arithmetic per byte,
+// and a second wave per SIMD is what hides it.
+constexpr int kQTileLoads = 2;      // wave loads of K (and of V) per tile
+constexpr int kQWgPerCu = 2;        // workgroups per compute unit
+
+template <int NL_>
+struct TileQ8T {
     static constexpr int D = 128;
-    static constexpr int NL = 8;
+    static constexpr int NL = NL_;
     static constexpr int LPR = 8;                        // lanes per row
     static constexpr int RPW = 8;                        // rows (tokens) per wave load
     static constexpr int EPL = 16;                       // elements per lane
@@ -110,17 +119,18 @@ struct TileQ8 {
     // token (inside a block) whose scales lane `lane` of wave `wave` loads: load lane/8, row lane%8
     __device__ static inline int own_token(int lane, int wave)
     {
-        return ((lane >> 3) * kWaves + wave) * RPW + (lane & 7);
+        return (((lane >> 3) % NL) * kWaves + wave) * RPW + (lane & 7);
     }
 
+    // issue order = consumption order (loads return in order): K scale, K codes, V scale, V codes
     __device__ inline void load(const char *kp, const char *vp, const float *ksp, const float *vsp)
     {
-#pragma unroll
-        for (int j = 0; j < NL; ++j) k[j] = ld_stream_u(kp + j * STRIDE);
         ks = __builtin_nontemporal_load(ksp);
 #pragma unroll
-        for (int j = 0; j < NL; ++j) v[j] = ld_stream_u(vp + j * STRIDE);
+        for (int j = 0; j < NL; ++j) k[j] = ld_stream_u(kp + j * STRIDE);
         vs = __builtin_nontemporal_load(vsp);
+#pragma unroll
+        for (int j = 0; j < NL; ++j) v[j] = ld_stream_u(vp + j * STRIDE);
     }
 
     // ragged last block of `rem` >= 1 tokens: lanes whose token is at or beyond `rem` re-read
@@ -140,11 +150,24 @@ struct TileQ8 {
         vs = __builtin_nontemporal_load(vsp - sback);
     }
 
-    template <bool MASKED>
+    // Consume this tile.  With REFILL every register is reloaded with the same slot of the block
+    // two ahead (kp2, vp2, ksp2, vsp2) as soon as its last use is issued, so that close to two
+    // blocks of loads per wave stay in flight during the arithmetic as well.
+    template <bool MASKED, bool REFILL>
     __device__ inline void update(const float (&q)[EPL], float qsum128, float &m, float &l,
-                                  float &aux, float (&acc)[EPL], int row, int tok0, int rem) const
+                                  float &aux, float (&acc)[EPL], int row, int tok0, int rem,
+                                  const char *kp2 = nullptr, const char *vp2 = nullptr,
+                                  const float *ksp2 = nullptr, const float *vsp2 = nullptr)
     {
+        // hand every row its tokens' K scales first: after that the register is free to refill
         float s[NL];
+#pragma unroll
+        for (int j = 0; j < NL; ++j) s[j] = __shfl(ks, j * RPW + row);
+        if (REFILL) {
+            sched_fence();
+            ks = __builtin_nontemporal_load(ksp2);
+            sched_fence();
+        }
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             float a = 0.f;
@@ -152,9 +175,13 @@ struct TileQ8 {
             for (int w = 0; w < 4; ++w)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) a = __builtin_fmaf(byte_f32(k[j][w], i), q[w * 4 + i], a);
+            if (REFILL) {
+                sched_fence();
+                k[j] = ld_stream_u(kp2 + j * STRIDE);
+                sched_fence();
+            }
             a = row_sum<LPR>(a);
-            const float sc = __shfl(ks, j * RPW + row);
-            a = (a - qsum128) * sc;
+            a = (a - qsum128) * s[j];
             if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
             s[j] = a;
         }
@@ -167,24 +194,42 @@ struct TileQ8 {
         aux *= corr;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) acc[i] *= corr;
+        // weights times V scales, then the V scale register is free as well
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             float p = fast_exp2(s[j] - mn);
             if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
             l += p;
-            const float pv = p * __shfl(vs, j * RPW + row);
-            aux += pv;
+            s[j] = p * __shfl(vs, j * RPW + row);
+            aux += s[j];
+        }
+        if (REFILL) {
+            sched_fence();
+            vs = __builtin_nontemporal_load(vsp2);
+            sched_fence();
+        }
+#pragma unroll
+        for (int j = 0; j < NL; ++j) {
+            const float pv = s[j];
 #pragma unroll
             for (int w = 0; w < 4; ++w)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     acc[w * 4 + i] = __builtin_fmaf(pv, byte_f32(v[j][w], i), acc[w * 4 + i]);
+            if (REFILL) {
+                sched_fence();
+                v[j] = ld_stream_u(vp2 + j * STRIDE);
+                sched_fence();
+            }
         }
         m = mn;
     }
 };
 
-__global__ __launch_bounds__(kThreads) void rpartq_partial_kernel(
+using TileQ8 = TileQ8T<kQTileLoads>;
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kQWgPerCu, kQWgPerCu)))
+void rpartq_partial_kernel(
     const char *__restrict__ k_codes, const char *__restrict__ v_codes,
     const float *__restrict__ k_scale, const float *__restrict__ v_scale,
     const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
@@ -276,39 +321,49 @@ __global__ __launch_bounds__(kThreads) void rpartq_partial_kernel(
         const float *vst = vsp;
         T A, Bf;
         if (n_blk > 0) {
-            A.load(kt, vt, kst, vst);
-            int i = 0;
-            while (i + 2 < n_blk) {
+            int left = n_blk;                              // A holds block n_blk-left, Bf the one after
+            if (n_blk >= 4) {
+                // both loads are issued unconditionally on the way into the loop: its wait
+                // counts can then leave a whole block outstanding behind the one in use
+                A.load(kt, vt, kst, vst);
                 Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kst + T::BLK_TOK, vst + T::BLK_TOK);
                 sched_fence();
-                A.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
-                sched_fence();
-                A.load(kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES, kst + 2 * T::BLK_TOK,
-                       vst + 2 * T::BLK_TOK);
-                sched_fence();
-                Bf.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
-                sched_fence();
-                kt += 2 * T::BLK_BYTES;
-                vt += 2 * T::BLK_BYTES;
-                kst += 2 * T::BLK_TOK;
-                vst += 2 * T::BLK_TOK;
-                i += 2;
-            }
-            if (i + 1 < n_blk) {
-                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kst + T::BLK_TOK, vst + T::BLK_TOK);
-                sched_fence();
-                A.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
-                sched_fence();
-                Bf.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                do {
+                    A.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
+                                                   kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES,
+                                                   kst + 2 * T::BLK_TOK, vst + 2 * T::BLK_TOK);
+                    Bf.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
+                                                    kt + 3 * T::BLK_BYTES, vt + 3 * T::BLK_BYTES,
+                                                    kst + 3 * T::BLK_TOK, vst + 3 * T::BLK_TOK);
+                    kt += 2 * T::BLK_BYTES;
+                    vt += 2 * T::BLK_BYTES;
+                    kst += 2 * T::BLK_TOK;
+                    vst += 2 * T::BLK_TOK;
+                    left -= 2;
+                } while (left > 3);
             } else {
-                A.template update<false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                A.load(kt, vt, kst, vst);
+                if (n_blk > 1) Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kst + T::BLK_TOK, vst + T::BLK_TOK);
+                sched_fence();
+            }
+            if (left == 3) {
+                A.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
+                                               kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES,
+                                               kst + 2 * T::BLK_TOK, vst + 2 * T::BLK_TOK);
+                Bf.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                A.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+            } else if (left == 2) {
+                A.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                Bf.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+            } else {
+                A.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
             }
         }
         if (rem > 0 && wave * T::RPW < rem) {              // this wave has at least one valid row
             const int64_t o = (int64_t)n_blk * T::BLK_BYTES;
             const int64_t so = (int64_t)n_blk * T::BLK_TOK;
             A.load_tail(kp + o, vp + o, ksp + so, vsp + so, tok0, own, rem);
-            A.template update<true>(qf, qsum, m, l, aux, acc, row, tok0, rem);
+            A.template update<true, false>(qf, qsum, m, l, aux, acc, row, tok0, rem);
         }
 
         // combine the rows of this wave
@@ -431,7 +486,7 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, 64, grid, 1 /* its registers allow one workgroup per CU */,
+                       desc->chunk_tokens, 64, kQWgPerCu * grid, kQWgPerCu * grid, 0, 1,
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
@@ -452,7 +507,7 @@ int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
     if (grid <= 0) return FD_EHIP;
     char *ws = (char *)workspace;
     const float qscale = (float)(1.4426950408889634 / 11.313708498984761);
-    hipLaunchKernelGGL(rpartq_partial_kernel, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(rpartq_partial_kernel, dim3(kQWgPerCu * grid), dim3(kThreads), 0, (hipStream_t)stream,
                        (const char *)desc->k_codes, (const char *)desc->v_codes, desc->k_scale,
                        desc->v_scale, desc->seq_off, desc->seq_cap, (const _Float16 *)q,
                        (_Float16 *)out, desc->H, (const int32_t *)ws,
