@@ -41,19 +41,28 @@ def counter_traffic(config_name):
 
 
 
-def build_case(cfg, lens, seed, chunk_tokens, growth=8, kv="fp16"):
+def build_case(cfg, lens, seed, chunk_tokens, growth=8, kv="fp16", window=0, sinks=0):
+    """window > 0: a windowed cache of sinks + window rows per sequence that has already seen
+    lens[b] tokens (its rows hold that many, or all of them when the history is longer)."""
     import torch
     from paper_2403_11421_amd import workloads as W
     from paper_2403_11421_amd.kvcache import KVCache, KVCacheQ
 
     dev = torch.device("cuda:0")
     cls = KVCache if kv == "fp16" else KVCacheQ
-    cache = cls(cfg.B, cfg.H, cfg.d, [L + growth for L in lens], dev, chunk_tokens)
-    for b, L in enumerate(lens):
+    if window > 0:
+        cache = cls(cfg.B, cfg.H, cfg.d, [sinks + window] * cfg.B, dev, chunk_tokens, n_sink=sinks)
+        held = [min(L, sinks + window) for L in lens]
+    else:
+        cache = cls(cfg.B, cfg.H, cfg.d, [L + growth for L in lens], dev, chunk_tokens)
+        held = lens
+    for b, L in enumerate(held):
         if L:
             cache.fill("K", b, W.gen_cache_block(cfg, "K", b, L, seed, dev))
             cache.fill("V", b, W.gen_cache_block(cfg, "V", b, L, seed, dev))
-    cache.set_lens(lens)
+    cache.set_lens(held)
+    if window > 0:
+        cache.seq_seen.copy_(torch.tensor(list(lens), dtype=torch.int32))
     vec = {w: W.gen_vectors(cfg, w, seed, dev) for w in ("q", "k_new", "v_new")}
     return cache, vec
 
@@ -211,6 +220,10 @@ def main() -> int:
                     help="instead of the fixed-length step, run a multi-step decode loop under the "
                          "large-batch or the load-stabilising schedule (Section 4.2) and report the "
                          "per-step R-Part latency")
+    ap.add_argument("--window", type=int, default=0,
+                    help="window attention: every sequence keeps --sinks first tokens and its last "
+                         "WINDOW tokens in a bounded cache (0 = attend to everything)")
+    ap.add_argument("--sinks", type=int, default=4)
     ap.add_argument("--pipeline", action="store_true",
                     help="instead of the one-layer step, run token steps of an N-block model with "
                          "two mini-batches (Section 4.1) and compare three ways of issuing them")
@@ -244,6 +257,8 @@ def main() -> int:
     seed = W.DEFAULT_SEED if args.seed is None else args.seed
     lens = W.seq_lens(cfg, seed)
     n_tok = W.total_tokens_after_append(lens)
+    if args.window > 0:                            # rows attended after the append: the bounded buffer's
+        n_tok = sum(min(L + 1, args.sinks + args.window) for L in lens)
     # algorithmic bytes: every cached K and V row once (int8: d code bytes + a 4-byte scale per row)
     bytes_per_token = cfg.bytes_per_token() if args.kv == "fp16" else 2 * cfg.H * (cfg.d + 4)
     kv_bytes = bytes_per_token * n_tok
@@ -253,10 +268,12 @@ def main() -> int:
     f_partial = rpart.fd_rpartq_partial if q8 else rpart.fd_rpart_partial
     f_merge = rpart.fd_rpartq_merge if q8 else rpart.fd_rpart_merge
 
-    cache, vec = build_case(cfg, lens, seed, args.chunk_tokens, kv=args.kv)
+    cache, vec = build_case(cfg, lens, seed, args.chunk_tokens, kv=args.kv, window=args.window,
+                            sinks=args.sinks)
     out = torch.empty_like(vec["q"])
     ws = cache.workspace(n_tok)
     lens0 = cache.seq_lens.clone()
+    seen0 = cache.seq_seen.clone() if args.window > 0 else None
     desc = cache.desc
 
     # HIP events around the dominant kernel on every 4th timed step: each record costs a ~5 us
@@ -266,6 +283,8 @@ def main() -> int:
 
     def step(pair=None):
         cache.seq_lens.copy_(lens0)                # every step is the quoted config: L cached + 1 appended
+        if seen0 is not None:
+            cache.seq_seen.copy_(seen0)
         f_append(desc, vec["k_new"], vec["v_new"])
         f_plan(desc, ws)
         if pair:
@@ -309,7 +328,9 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: B={cfg.B} H={cfg.H} d={cfg.d} {args.kv} KV, "
-                               f"{n_tok} cached tokens after append, 1 layer",
+                               f"{n_tok} cached tokens after append, 1 layer"
+                               + (f", window attention: {args.sinks} sink + last {args.window} tokens"
+                                  if args.window > 0 else ""),
                    "B": cfg.B, "H": cfg.H, "d": cfg.d, "total_tokens": n_tok,
                    "kv_bytes_per_step": kv_bytes, "seed": seed, "plan": plan},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
@@ -336,7 +357,7 @@ def main() -> int:
     torch.cuda.synchronize()
     res["roofline"]["read_only_ceiling_gbps"] = nread * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
-    if args.cpu_sample > 0 and not q8:
+    if args.cpu_sample > 0 and not q8 and args.window == 0:
         res["cpu_baseline"] = cpu_baseline(cfg, cache, vec, [L + 1 for L in lens], args.cpu_sample)
     print(json.dumps(res))
     return 0

@@ -41,6 +41,10 @@ extern "C" {
 
 #define FD_ST_CAPACITY 1    /* append skipped for a sequence whose cache is full                 */
 #define FD_ST_BADLEN   2    /* a seq_lens entry was outside [0, seq_cap]; it was clamped         */
+#define FD_ST_WINDOW   4    /* windowed cache: n_sink leaves no window row, or seq_seen and
+                               seq_lens of a sequence disagree; its append was skipped           */
+
+#define FD_SLOT_FREE  (-1)  /* value of seq_lens[b] for a slot that holds no sequence            */
 
 /*
  * KV-cache of one layer for B sequences (the paper prescribes no layout; this
@@ -62,7 +66,27 @@ typedef struct fd_kv_desc {
     int32_t        H;             /* attention heads (multi-head: one K/V head per query head)  */
     int32_t        d;             /* head dimension, 64 or 128                                   */
     int32_t        chunk_tokens;  /* split-K chunk length in tokens; 0 = chosen on the device   */
+    int32_t       *seq_seen;      /* device int32[B] or NULL: see "windowed cache" below        */
+    int32_t        n_sink;        /* windowed cache: leading tokens that are never replaced     */
 } fd_kv_desc;
+
+/*
+ * Free slots.  seq_lens[b] == FD_SLOT_FREE marks a slot without a sequence
+ * (Section 4.1: the cache of a sequence is dropped when its generation ends, and
+ * the slot's block is reused by a later sequence without reallocation): append
+ * leaves it alone, decode treats it as empty (out[b] = 0).  fd_kv_release frees
+ * slots, fd_kv_reset starts a new sequence (length 0) in them.
+ *
+ * Windowed cache (window attention with sink tokens: the variation of attention
+ * that the paper's Related Work names as reducing the tokens a new token interacts
+ * with).  With seq_seen != NULL, sequence b attends to its first n_sink tokens and to
+ * its last seq_cap[b] - n_sink tokens only, and its block is a bounded buffer:
+ * seq_seen[b] counts the tokens appended so far; token p is stored in row p while
+ * p < seq_cap[b], afterwards in row n_sink + (p - n_sink) mod (seq_cap[b] - n_sink),
+ * replacing the oldest token that is not a sink; seq_lens[b] = min(seq_seen[b],
+ * seq_cap[b]).  Attention does not depend on the order of the rows, so the decode
+ * entry points need nothing else.  Requires n_sink < seq_cap[b].
+ */
 
 /* Library version (major*10000 + minor*100 + patch). */
 int fd_version(void);
@@ -82,7 +106,9 @@ size_t fd_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t max_total_tok
  * Append (Section 4.1): for every b, copy the d*H fp16 of k_new[b] and v_new[b]
  * bit-for-bit into row seq_lens[b] of the sequence's K and V blocks, then
  * seq_lens[b] += 1.  A sequence with seq_lens[b] >= seq_cap[b] is left
- * untouched and FD_ST_CAPACITY is set in *desc->status.
+ * untouched and FD_ST_CAPACITY is set in *desc->status.  Free slots are skipped.
+ * With a windowed cache the row is the one described above, seq_seen[b] += 1 and
+ * the length saturates at seq_cap[b]; there is no capacity error.
  *   k_new, v_new: device fp16 [B][H][d], 16-byte aligned.
  */
 int fd_kv_append(const fd_kv_desc *desc, const void *k_new, const void *v_new, void *stream);
@@ -126,11 +152,14 @@ int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, cons
 
 /*
  * Drop cached sequences (Section 4.1: a worker may drop a sequence's cache when
- * its generation ends): seq_lens[seq_ids[j]] = 0 for j < n.  seq_ids is a device
+ * its generation ends): seq_lens[seq_ids[j]] = 0 (and seq_seen, if present) for
+ * j < n, i.e. the slot now holds a new, empty sequence.  seq_ids is a device
  * int32[n]; NULL means all B sequences (n is then ignored).  Ids outside [0,B)
  * are ignored.  The cache rows themselves are not cleared.
+ * fd_kv_release does the same but marks the slots FD_SLOT_FREE.
  */
 int fd_kv_reset(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
+int fd_kv_release(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
 
 /*
  * Copy the sticky status word to the host.  SYNCHRONISES `stream`.
@@ -176,6 +205,8 @@ typedef struct fd_kvq_desc {
     int32_t       *status;        /* device int32[1]: sticky FD_ST_* bits; caller zeroes it     */
     int32_t        B, H, d;       /* sequences, heads, head dimension (128)                      */
     int32_t        chunk_tokens;  /* split-K chunk length in tokens; 0 = chosen on the device   */
+    int32_t       *seq_seen;      /* device int32[B] or NULL: windowed cache, as in fd_kv_desc  */
+    int32_t        n_sink;        /* windowed cache: leading tokens that are never replaced     */
 } fd_kvq_desc;
 
 /*
@@ -187,6 +218,7 @@ typedef struct fd_kvq_desc {
  */
 int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new, void *stream);
 int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
+int fd_kvq_release(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
 int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_bytes, void *stream);
 int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
                       void *workspace, size_t workspace_bytes, void *stream);

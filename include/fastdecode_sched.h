@@ -62,6 +62,22 @@ int64_t fd_lc_count(const fd_load_ctl *lc);
 int64_t fd_lc_snapshot(const fd_load_ctl *lc, int64_t n, int64_t *M, int64_t *E, int64_t *W);
 
 /*
+ * Slot bookkeeping for an R-worker with room for B sequences (Section 4.1: the cache of a
+ * sequence is dropped when its generation ends; its slot and block are handed to the next
+ * sequence).  A host-side free list; the device side of a slot is fd_kv_release / fd_kv_reset.
+ *   fd_slots_acquire  a free slot id (the most recently released one first; 0, 1, 2, ... while
+ *                     none has been released), or
+ *                     FD_SLOT_FREE (-1) when all B are taken.
+ *   fd_slots_release  returns slot `id`; FD_EINVAL if it is out of range or already free.
+ */
+typedef struct fd_slots fd_slots;
+fd_slots *fd_slots_create(int32_t B);
+void fd_slots_destroy(fd_slots *s);
+int32_t fd_slots_acquire(fd_slots *s);
+int fd_slots_release(fd_slots *s, int32_t id);
+int32_t fd_slots_in_use(const fd_slots *s);
+
+/*
  * Section 4.3 (workload-balanced hardware selection).  T_B is the measured latency of the
  * S-Part of one transformer block at batch size B, R the measured R-Part latency of one
  * R-worker per cached token and block, both in the same time unit; N blocks, sequences of

@@ -74,19 +74,46 @@ inline WsLayout ws_layout(int B, int H, int d, size_t ws_bytes)
 // Append (Section 4.1).  One workgroup per sequence: 2*H rows of d fp16 are
 // copied as raw 128-bit words, then one thread bumps the length.
 // ---------------------------------------------------------------------------
+// Row that the new token of sequence b goes to, and the sequence's length afterwards; -1 if
+// the append is skipped (free slot, full plain cache, inconsistent window state).  Uniform
+// over the workgroup; thread 0 reports errors.
+__device__ inline int append_row(const int32_t *seq_lens, const int32_t *seq_cap,
+                                 const int32_t *seq_seen, int n_sink, int32_t *status, int b,
+                                 int *new_len)
+{
+    const int L = seq_lens[b];
+    const int cap = seq_cap[b];
+    if (L == FD_SLOT_FREE) return -1;
+    if (!seq_seen) {
+        if (L < 0 || L >= cap) {
+            if (threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
+            return -1;
+        }
+        *new_len = L + 1;
+        return L;
+    }
+    // windowed cache: a bounded buffer of n_sink fixed rows and a ring of cap - n_sink rows
+    const int p = seq_seen[b];
+    if (n_sink < 0 || n_sink >= cap || p < 0 || L != (p < cap ? p : cap)) {
+        if (threadIdx.x == 0) atomicOr(status, FD_ST_WINDOW);
+        return -1;
+    }
+    *new_len = p + 1 < cap ? p + 1 : cap;
+    return p < cap ? p : n_sink + (p - n_sink) % (cap - n_sink);
+}
+
 __global__ __launch_bounds__(256) void kv_append_kernel(
     uint4 *__restrict__ k_base, uint4 *__restrict__ v_base,
     const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
     int32_t *__restrict__ seq_lens, int32_t *__restrict__ status,
-    const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new, int H, int d)
+    const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new, int H, int d,
+    int32_t *__restrict__ seq_seen, int n_sink)
 {
     const int b = blockIdx.x;
-    const int L = seq_lens[b];
     const int cap = seq_cap[b];
-    if (L < 0 || L >= cap) {
-        if (threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
-        return;
-    }
+    int new_len = 0;
+    const int L = append_row(seq_lens, seq_cap, seq_seen, n_sink, status, b, &new_len);
+    if (L < 0) return;
     const int vpr = d / 8;                               // 16-byte words per row
     const int n = H * vpr;
     const int64_t blk = seq_off[b] / 8;                  // block offset in 16-byte words
@@ -100,16 +127,23 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
         else       k_base[dst] = k_new[src0 + y];
     }
     __syncthreads();
-    if (threadIdx.x == 0) seq_lens[b] = L + 1;
+    if (threadIdx.x == 0) {
+        seq_lens[b] = new_len;
+        if (seq_seen) seq_seen[b] += 1;
+    }
 }
 
-__global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, const int32_t *__restrict__ ids,
-                                int n, int B)
+// value = 0 starts an empty sequence in the slot, FD_SLOT_FREE marks the slot free
+__global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, int32_t *__restrict__ seq_seen,
+                                const int32_t *__restrict__ ids, int n, int B, int value)
 {
     const int j = blockIdx.x * blockDim.x + threadIdx.x;
     if (j >= n) return;
     const int b = ids ? ids[j] : j;
-    if (b >= 0 && b < B) seq_lens[b] = 0;
+    if (b >= 0 && b < B) {
+        seq_lens[b] = value;
+        if (seq_seen) seq_seen[b] = 0;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -164,6 +198,7 @@ __device__ inline int block_exclusive_scan(int v, int *sm)
 
 __device__ inline int clamp_len(int L, int cap, int *bad)
 {
+    if (L == FD_SLOT_FREE) return 0;                     // a free slot counts as empty
     if (L < 0) { *bad = 1; return 0; }
     if (L > cap) { *bad = 1; return cap > 0 ? cap : 0; }
     return L;
@@ -671,6 +706,7 @@ int check_desc(const fd_kv_desc *d)
     if (!aligned(d->k_base, 16) || !aligned(d->v_base, 16) || !aligned(d->seq_off, 8) ||
         !aligned(d->seq_cap, 4) || !aligned(d->seq_lens, 4) || !aligned(d->status, 4))
         return FD_EINVAL;
+    if (d->seq_seen && (!aligned(d->seq_seen, 4) || d->n_sink < 0)) return FD_EINVAL;
     return FD_OK;
 }
 
@@ -739,11 +775,12 @@ int fd_kv_append(const fd_kv_desc *desc, const void *k_new, const void *v_new, v
     hipLaunchKernelGGL(kv_append_kernel, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
                        (uint4 *)desc->k_base, (uint4 *)desc->v_base, desc->seq_off, desc->seq_cap,
                        desc->seq_lens, desc->status, (const uint4 *)k_new, (const uint4 *)v_new,
-                       desc->H, desc->d);
+                       desc->H, desc->d, desc->seq_seen, desc->n_sink);
     return launched();
 }
 
-int fd_kv_reset(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void *stream)
+static int reset_slots(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, int value,
+                       void *stream)
 {
     int rc = check_desc(desc);
     if (rc != FD_OK) return rc;
@@ -752,8 +789,19 @@ int fd_kv_reset(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void 
     const int count = seq_ids ? n : desc->B;
     if (count == 0) return FD_OK;
     hipLaunchKernelGGL(kv_reset_kernel, dim3((count + 255) / 256), dim3(256), 0,
-                       (hipStream_t)stream, desc->seq_lens, seq_ids, count, desc->B);
+                       (hipStream_t)stream, desc->seq_lens, desc->seq_seen, seq_ids, count,
+                       desc->B, value);
     return launched();
+}
+
+int fd_kv_reset(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void *stream)
+{
+    return reset_slots(desc, seq_ids, n, 0, stream);
+}
+
+int fd_kv_release(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void *stream)
+{
+    return reset_slots(desc, seq_ids, n, FD_SLOT_FREE, stream);
 }
 
 int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_bytes, void *stream)

@@ -29,16 +29,15 @@ __global__ __launch_bounds__(256) void kvq_append_kernel(
     float *__restrict__ k_scale, float *__restrict__ v_scale,
     const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
     int32_t *__restrict__ seq_lens, int32_t *__restrict__ status,
-    const _Float16 *__restrict__ k_new, const _Float16 *__restrict__ v_new, int H)
+    const _Float16 *__restrict__ k_new, const _Float16 *__restrict__ v_new, int H,
+    int32_t *__restrict__ seq_seen, int n_sink)
 {
     constexpr int D = 128;
     const int b = blockIdx.x;
-    const int L = seq_lens[b];
     const int cap = seq_cap[b];
-    if (L < 0 || L >= cap) {
-        if (threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
-        return;
-    }
+    int new_len = 0;
+    const int L = append_row(seq_lens, seq_cap, seq_seen, n_sink, status, b, &new_len);
+    if (L < 0) return;
     const int sub = threadIdx.x & 15;          // position inside the 16-lane group of a row
     const int group = threadIdx.x >> 4;        // 16 rows in flight per pass
     const int64_t off = seq_off[b];
@@ -72,7 +71,10 @@ __global__ __launch_bounds__(256) void kvq_append_kernel(
         if (sub == 0) (which ? v_scale : k_scale)[off / D + row] = scale;
     }
     __syncthreads();
-    if (threadIdx.x == 0) seq_lens[b] = L + 1;
+    if (threadIdx.x == 0) {
+        seq_lens[b] = new_len;
+        if (seq_seen) seq_seen[b] += 1;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -432,6 +434,7 @@ int check_qdesc(const fd_kvq_desc *d)
         !aligned(d->v_scale, 4) || !aligned(d->seq_off, 8) || !aligned(d->seq_cap, 4) ||
         !aligned(d->seq_lens, 4) || !aligned(d->status, 4))
         return FD_EINVAL;
+    if (d->seq_seen && (!aligned(d->seq_seen, 4) || d->n_sink < 0)) return FD_EINVAL;
     return FD_OK;
 }
 
@@ -456,11 +459,13 @@ int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new,
     hipLaunchKernelGGL(kvq_append_kernel, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
                        (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
                        desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens, desc->status,
-                       (const _Float16 *)k_new, (const _Float16 *)v_new, desc->H);
+                       (const _Float16 *)k_new, (const _Float16 *)v_new, desc->H, desc->seq_seen,
+                       desc->n_sink);
     return launched();
 }
 
-int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream)
+static int reset_qslots(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, int value,
+                        void *stream)
 {
     int rc = check_qdesc(desc);
     if (rc != FD_OK) return rc;
@@ -469,8 +474,19 @@ int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, voi
     const int count = seq_ids ? n : desc->B;
     if (count == 0) return FD_OK;
     hipLaunchKernelGGL(kv_reset_kernel, dim3((count + 255) / 256), dim3(256), 0,
-                       (hipStream_t)stream, desc->seq_lens, seq_ids, count, desc->B);
+                       (hipStream_t)stream, desc->seq_lens, desc->seq_seen, seq_ids, count,
+                       desc->B, value);
     return launched();
+}
+
+int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream)
+{
+    return reset_qslots(desc, seq_ids, n, 0, stream);
+}
+
+int fd_kvq_release(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream)
+{
+    return reset_qslots(desc, seq_ids, n, FD_SLOT_FREE, stream);
 }
 
 int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_bytes, void *stream)

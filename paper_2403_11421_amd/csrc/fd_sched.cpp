@@ -131,6 +131,50 @@ int64_t fd_lc_snapshot(const fd_load_ctl *lc, int64_t n, int64_t *M, int64_t *E,
 }
 
 // ---------------------------------------------------------------------------
+// Slot free list (Section 4.1: dropped sequences hand their slot to later ones)
+// ---------------------------------------------------------------------------
+struct fd_slots {
+    std::vector<int32_t> free_ids;      // stack of free slots; back() is handed out next
+    std::vector<char> taken;
+};
+
+fd_slots *fd_slots_create(int32_t B)
+{
+    if (B <= 0) return nullptr;
+    fd_slots *s = new (std::nothrow) fd_slots;
+    if (!s) return nullptr;
+    s->taken.assign((size_t)B, 0);
+    s->free_ids.resize((size_t)B);
+    for (int32_t i = 0; i < B; ++i) s->free_ids[(size_t)i] = B - 1 - i;    // slot 0 first
+    return s;
+}
+
+void fd_slots_destroy(fd_slots *s) { delete s; }
+
+int32_t fd_slots_acquire(fd_slots *s)
+{
+    if (!s) return FD_EINVAL;
+    if (s->free_ids.empty()) return FD_SLOT_FREE;
+    const int32_t id = s->free_ids.back();
+    s->free_ids.pop_back();
+    s->taken[(size_t)id] = 1;
+    return id;
+}
+
+int fd_slots_release(fd_slots *s, int32_t id)
+{
+    if (!s || id < 0 || (size_t)id >= s->taken.size() || !s->taken[(size_t)id]) return FD_EINVAL;
+    s->taken[(size_t)id] = 0;
+    s->free_ids.push_back(id);
+    return FD_OK;
+}
+
+int32_t fd_slots_in_use(const fd_slots *s)
+{
+    return s ? (int32_t)(s->taken.size() - s->free_ids.size()) : FD_EINVAL;
+}
+
+// ---------------------------------------------------------------------------
 // Section 4.3: batch size and number of R-workers from two measured quantities
 // ---------------------------------------------------------------------------
 double fd_model_sequence_latency(int64_t N, int64_t S, double T_B)

@@ -6,7 +6,7 @@ Sequence b owns a ``[H][cap_b][d]`` block at element offset ``seq_off[b]``.
 """
 from __future__ import annotations
 
-from typing import Sequence
+from typing import Optional, Sequence
 
 import torch
 
@@ -15,7 +15,9 @@ from . import rpart
 
 class KVCache:
     def __init__(self, B: int, H: int, d: int, capacities: Sequence[int], device="cuda",
-                 chunk_tokens: int = 0):
+                 chunk_tokens: int = 0, n_sink: Optional[int] = None):
+        """n_sink = None: plain cache.  n_sink >= 0: windowed cache, sequence b keeps its first
+        n_sink tokens and its last capacities[b] - n_sink tokens."""
         assert len(capacities) == B and d in (64, 128)
         self.B, self.H, self.d = B, H, d
         self.device = torch.device(device)
@@ -33,9 +35,11 @@ class KVCache:
         self.seq_cap = torch.tensor(self.caps, dtype=torch.int32, device=self.device)
         self.seq_lens = torch.zeros(B, dtype=torch.int32, device=self.device)
         self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.seq_seen = None if n_sink is None else torch.zeros(B, dtype=torch.int32, device=self.device)
         self.desc = rpart.fd_kv_desc(
             self.k.data_ptr(), self.v.data_ptr(), self.seq_off.data_ptr(), self.seq_cap.data_ptr(),
-            self.seq_lens.data_ptr(), self.status.data_ptr(), B, H, d, chunk_tokens)
+            self.seq_lens.data_ptr(), self.status.data_ptr(), B, H, d, chunk_tokens,
+            None if n_sink is None else self.seq_seen.data_ptr(), 0 if n_sink is None else n_sink)
 
     def set_chunk_tokens(self, t: int) -> None:
         self.desc.chunk_tokens = int(t)
@@ -52,7 +56,13 @@ class KVCache:
         self.block(which, b)[:, t0:t0 + L, :].copy_(rows)
 
     def set_lens(self, lens: Sequence[int]) -> None:
-        self.seq_lens.copy_(torch.tensor(list(lens), dtype=torch.int32))
+        """Cached tokens per sequence; a windowed cache is told the tokens seen so far, which
+        must not exceed the capacity here (rows 0..L-1 hold tokens 0..L-1)."""
+        t = torch.tensor(list(lens), dtype=torch.int32)
+        self.seq_lens.copy_(t)
+        if self.seq_seen is not None:
+            assert all(L <= c for L, c in zip(lens, self.caps))
+            self.seq_seen.copy_(t)
 
     def workspace(self, max_total_tokens: int) -> torch.Tensor:
         n = rpart.workspace_bytes(self.B, self.H, self.d, max_total_tokens)
@@ -79,7 +89,7 @@ class KVCacheQ:
     """int8 KV-cache of one layer in the layout of ``fd_kvq_desc`` (d = 128)."""
 
     def __init__(self, B: int, H: int, d: int, capacities: Sequence[int], device="cuda",
-                 chunk_tokens: int = 0):
+                 chunk_tokens: int = 0, n_sink: Optional[int] = None):
         assert len(capacities) == B and d == 128
         self.B, self.H, self.d = B, H, d
         self.device = torch.device(device)
@@ -99,10 +109,12 @@ class KVCacheQ:
         self.seq_cap = torch.tensor(self.caps, dtype=torch.int32, device=self.device)
         self.seq_lens = torch.zeros(B, dtype=torch.int32, device=self.device)
         self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
+        self.seq_seen = None if n_sink is None else torch.zeros(B, dtype=torch.int32, device=self.device)
         self.desc = rpart.fd_kvq_desc(
             self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_scale.data_ptr(),
             self.v_scale.data_ptr(), self.seq_off.data_ptr(), self.seq_cap.data_ptr(),
-            self.seq_lens.data_ptr(), self.status.data_ptr(), B, H, d, chunk_tokens)
+            self.seq_lens.data_ptr(), self.status.data_ptr(), B, H, d, chunk_tokens,
+            None if n_sink is None else self.seq_seen.data_ptr(), 0 if n_sink is None else n_sink)
 
     def codes(self, which: str, b: int) -> torch.Tensor:
         """View ``[H, cap_b, d]`` (uint8) of sequence b's K or V codes."""
@@ -124,7 +136,13 @@ class KVCacheQ:
         self.scales(which, b)[:, t0:t0 + L].copy_(s)
 
     def set_lens(self, lens: Sequence[int]) -> None:
-        self.seq_lens.copy_(torch.tensor(list(lens), dtype=torch.int32))
+        """Cached tokens per sequence; a windowed cache is told the tokens seen so far, which
+        must not exceed the capacity here (rows 0..L-1 hold tokens 0..L-1)."""
+        t = torch.tensor(list(lens), dtype=torch.int32)
+        self.seq_lens.copy_(t)
+        if self.seq_seen is not None:
+            assert all(L <= c for L, c in zip(lens, self.caps))
+            self.seq_seen.copy_(t)
 
     def workspace(self, max_total_tokens: int) -> torch.Tensor:
         n = rpart.workspace_bytes(self.B, self.H, self.d, max_total_tokens)

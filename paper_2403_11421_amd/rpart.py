@@ -15,7 +15,8 @@ import torch
 from . import build as _build
 
 FD_OK, FD_EINVAL, FD_EWORKSPACE, FD_EHIP = 0, -1, -2, -3
-FD_ST_CAPACITY, FD_ST_BADLEN = 1, 2
+FD_ST_CAPACITY, FD_ST_BADLEN, FD_ST_WINDOW = 1, 2, 4
+FD_SLOT_FREE = -1
 
 _vp = ctypes.c_void_p
 
@@ -26,6 +27,7 @@ class fd_kv_desc(ctypes.Structure):
         ("seq_lens", _vp), ("status", _vp),
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
         ("chunk_tokens", ctypes.c_int32),
+        ("seq_seen", _vp), ("n_sink", ctypes.c_int32),
     ]
 
 
@@ -35,6 +37,7 @@ class fd_kvq_desc(ctypes.Structure):
         ("seq_off", _vp), ("seq_cap", _vp), ("seq_lens", _vp), ("status", _vp),
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
         ("chunk_tokens", ctypes.c_int32),
+        ("seq_seen", _vp), ("n_sink", ctypes.c_int32),
     ]
 
 
@@ -82,6 +85,8 @@ def load() -> ctypes.CDLL:
     lib.fd_rpart_layer_step.argtypes = [P, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, ctypes.c_int, _vp]
     lib.fd_kv_reset.restype = ctypes.c_int
     lib.fd_kv_reset.argtypes = [P, _vp, ctypes.c_int32, _vp]
+    lib.fd_kv_release.restype = ctypes.c_int
+    lib.fd_kv_release.argtypes = [P, _vp, ctypes.c_int32, _vp]
     lib.fd_read_status.restype = ctypes.c_int
     lib.fd_read_status.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.c_int, _vp]
     lib.fd_plan_info.restype = ctypes.c_int
@@ -89,6 +94,7 @@ def load() -> ctypes.CDLL:
     Q = ctypes.POINTER(fd_kvq_desc)
     for name, args in (("fd_kvq_append", [Q, _vp, _vp, _vp]),
                        ("fd_kvq_reset", [Q, _vp, ctypes.c_int32, _vp]),
+                       ("fd_kvq_release", [Q, _vp, ctypes.c_int32, _vp]),
                        ("fd_rpartq_plan", [Q, _vp, ctypes.c_size_t, _vp]),
                        ("fd_rpartq_partial", [Q, _vp, _vp, _vp, ctypes.c_size_t, _vp]),
                        ("fd_rpartq_merge", [Q, _vp, _vp, ctypes.c_size_t, _vp]),
@@ -108,7 +114,8 @@ EXPORTS = ("fd_version", "fd_strerror", "fd_workspace_bytes", "fd_kv_append", "f
            "fd_rpart_plan", "fd_rpart_partial", "fd_rpart_merge", "fd_rpart_step", "fd_kv_reset",
            "fd_read_status", "fd_plan_info", "fd_hbm_read_probe",
            "fd_kvq_append", "fd_kvq_reset", "fd_rpartq_plan", "fd_rpartq_partial", "fd_rpartq_merge",
-           "fd_rpartq_decode", "fd_rpartq_step", "fd_rpart_layer_step", "fd_rpartq_layer_step")
+           "fd_rpartq_decode", "fd_rpartq_step", "fd_rpart_layer_step", "fd_rpartq_layer_step",
+           "fd_kv_release", "fd_kvq_release")
 
 
 def version() -> int:
@@ -179,6 +186,15 @@ def fd_rpart_step(desc: fd_kv_desc, q: torch.Tensor, k_new: torch.Tensor, v_new:
 def fd_kv_reset(desc: fd_kv_desc, seq_ids: Optional[torch.Tensor] = None) -> None:
     n = 0 if seq_ids is None else seq_ids.numel()
     _check(load().fd_kv_reset(ctypes.byref(desc), _ptr(seq_ids), n, _stream()), "fd_kv_reset")
+
+
+def fd_kv_release(desc, seq_ids: Optional[torch.Tensor] = None) -> None:
+    """Mark slots free (seq_lens = FD_SLOT_FREE); `desc` is an fd_kv_desc or an fd_kvq_desc."""
+    n = 0 if seq_ids is None else seq_ids.numel()
+    quant = isinstance(desc, fd_kvq_desc)
+    f = load().fd_kvq_release if quant else load().fd_kv_release
+    _check(f(ctypes.byref(desc), _ptr(seq_ids), n, _stream()),
+           "fd_kvq_release" if quant else "fd_kv_release")
 
 
 def fd_read_status(desc, clear: bool = False) -> int:

@@ -37,6 +37,16 @@ def _lib():
         lib.fd_lc_count.argtypes = [ctypes.c_void_p]
         lib.fd_lc_snapshot.restype = _i64
         lib.fd_lc_snapshot.argtypes = [ctypes.c_void_p, _i64, P, P, P]
+        lib.fd_slots_create.restype = ctypes.c_void_p
+        lib.fd_slots_create.argtypes = [ctypes.c_int32]
+        lib.fd_slots_destroy.restype = None
+        lib.fd_slots_destroy.argtypes = [ctypes.c_void_p]
+        lib.fd_slots_acquire.restype = ctypes.c_int32
+        lib.fd_slots_acquire.argtypes = [ctypes.c_void_p]
+        lib.fd_slots_release.restype = ctypes.c_int
+        lib.fd_slots_release.argtypes = [ctypes.c_void_p, ctypes.c_int32]
+        lib.fd_slots_in_use.restype = ctypes.c_int32
+        lib.fd_slots_in_use.argtypes = [ctypes.c_void_p]
         _f64 = ctypes.c_double
         lib.fd_model_sequence_latency.restype = _f64
         lib.fd_model_sequence_latency.argtypes = [_i64, _i64, _f64]
@@ -56,7 +66,9 @@ EXPORTS = ("fd_sls_microbatch_size", "fd_sls_peak_load", "fd_sls_step_loads", "f
            "fd_lc_create", "fd_lc_destroy", "fd_lc_add_microbatch", "fd_lc_earliest_step",
            "fd_lc_retire", "fd_lc_count", "fd_lc_snapshot",
            "fd_model_sequence_latency", "fd_model_max_batch", "fd_model_sworker_throughput",
-           "fd_model_min_rworkers_memory", "fd_model_num_rworkers")
+           "fd_model_min_rworkers_memory", "fd_model_num_rworkers",
+           "fd_slots_create", "fd_slots_destroy", "fd_slots_acquire", "fd_slots_release",
+           "fd_slots_in_use")
 
 
 def _ok(v: int, where: str) -> int:
@@ -152,3 +164,31 @@ def model_min_rworkers_memory(B: int, S: int, C: int) -> int:
 
 def model_num_rworkers(B: int, S: int, R: float, T_B: float) -> float:
     return _finite(_lib().fd_model_num_rworkers(B, S, R, T_B), "fd_model_num_rworkers")
+
+
+class Slots:
+    """Free list of the B sequence slots of an R-worker (Section 4.1: dropped sequences hand
+    their slot to later ones)."""
+
+    def __init__(self, B: int):
+        self._h = _lib().fd_slots_create(B)
+        if not self._h:
+            raise rpart.FdError(rpart.FD_EINVAL, "fd_slots_create")
+
+    def close(self) -> None:
+        if self._h:
+            _lib().fd_slots_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()
+
+    def acquire(self) -> int:
+        """A free slot id, or -1 when every slot is taken."""
+        return int(_lib().fd_slots_acquire(self._h))
+
+    def release(self, slot: int) -> None:
+        _ok(_lib().fd_slots_release(self._h, slot), "fd_slots_release")
+
+    def in_use(self) -> int:
+        return _ok(_lib().fd_slots_in_use(self._h), "fd_slots_in_use")

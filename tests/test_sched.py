@@ -214,3 +214,42 @@ def test_model_max_batch_and_bad_arguments():
                 lambda: sched.model_max_batch(1, 1, 1.0, [(0, 1.0)])):
         with pytest.raises(rpart.FdError):
             bad()
+
+
+# ---------------------------------------------------------------------------
+# slot free list
+# ---------------------------------------------------------------------------
+def test_slots_hand_out_every_slot_once_and_reuse_released_ones():
+    s = sched.Slots(5)
+    got = [s.acquire() for _ in range(5)]
+    assert got == [0, 1, 2, 3, 4] and s.in_use() == 5
+    assert s.acquire() == -1                                  # all taken
+    s.release(3)
+    s.release(1)
+    assert s.in_use() == 3
+    assert s.acquire() == 1 and s.acquire() == 3              # most recently released first
+    with pytest.raises(rpart.FdError):
+        s.release(7)
+    s.release(0)
+    with pytest.raises(rpart.FdError):
+        s.release(0)                                          # already free
+    s.close()
+    with pytest.raises(rpart.FdError):
+        sched.Slots(0)
+
+
+def test_slots_random_walk_never_duplicates():
+    rng = random.Random(3)
+    B = 17
+    s = sched.Slots(B)
+    held = set()
+    for _ in range(2000):
+        if held and (len(held) == B or rng.random() < 0.5):
+            x = rng.choice(sorted(held))
+            s.release(x)
+            held.remove(x)
+        else:
+            x = s.acquire()
+            assert 0 <= x < B and x not in held
+            held.add(x)
+        assert s.in_use() == len(held)
