@@ -281,3 +281,107 @@ int fdo_rpartq_decode(int B, int H, int d, const int32_t *seq_lens,
     }
     return 0;
 }
+
+
+/* ------------------------------------------------------------------------- */
+/* 4-bit quantised KV-cache (Section 5.2: with 4-bit integers the memory access */
+/* size is a quarter of fp16's)                                                 */
+/* ------------------------------------------------------------------------- */
+
+/* One row of d binary16 values (d even) -> d/2 bytes, one binary32 scale and one binary32
+ * zero point.  Asymmetric, per row: zero = min x, scale = (max x - min x) / 15,
+ * code = rint((x - zero) / scale) in 0..15, all evaluated in binary32; a constant row has
+ * scale 0 and codes 0.  Element 2j sits in the low nibble of byte j, element 2j+1 in the high. */
+void fdo_quantize_row_u4(const uint16_t *x, int d, uint8_t *packed, float *scale, float *zero)
+{
+    float mn = (float)fdo_half_to_double(x[0]), mx = mn;
+    for (int i = 1; i < d; ++i) {
+        float v = (float)fdo_half_to_double(x[i]);
+        if (v < mn) mn = v;
+        if (v > mx) mx = v;
+    }
+    float s = (mx - mn) / 15.0f;
+    *scale = s;
+    *zero = mn;
+    for (int j = 0; j < d / 2; ++j) {
+        int c[2];
+        for (int e = 0; e < 2; ++e) {
+            float v = (float)fdo_half_to_double(x[2 * j + e]);
+            float r = (s > 0.0f) ? rintf((v - mn) / s) : 0.0f;
+            c[e] = (int)r;
+            if (c[e] < 0) c[e] = 0;
+            if (c[e] > 15) c[e] = 15;
+        }
+        packed[j] = (uint8_t)(c[0] | (c[1] << 4));
+    }
+}
+
+/* Append for a 4-bit cache: Kc[b], Vc[b] token-major [cap_b][H][d/2] bytes; Ksz[b], Vsz[b]
+ * token-major [cap_b][H][2] binary32 (scale, zero). */
+void fdo_kvq4_append(int B, int H, int d, int32_t *seq_lens,
+                     uint8_t *const *Kc, float *const *Ksz, uint8_t *const *Vc, float *const *Vsz,
+                     const uint16_t *k_new, const uint16_t *v_new)
+{
+    for (int b = 0; b < B; ++b) {
+        size_t L = (size_t)seq_lens[b];
+        for (int h = 0; h < H; ++h) {
+            size_t src = ((size_t)b * H + h) * d;
+            size_t row = L * H + h;
+            fdo_quantize_row_u4(k_new + src, d, Kc[b] + row * (d / 2), Ksz[b] + row * 2, Ksz[b] + row * 2 + 1);
+            fdo_quantize_row_u4(v_new + src, d, Vc[b] + row * (d / 2), Vsz[b] + row * 2, Vsz[b] + row * 2 + 1);
+        }
+        seq_lens[b] += 1;
+    }
+}
+
+static double dequant4(const uint8_t *row, int i, const float *sz)
+{
+    int c = (i & 1) ? (row[i / 2] >> 4) : (row[i / 2] & 15);
+    return (double)c * (double)sz[0] + (double)sz[1];
+}
+
+/* Eq. 2 + Eq. 3 over the dequantised rows (code * scale + zero, in double) of a 4-bit cache. */
+int fdo_rpartq4_decode(int B, int H, int d, const int32_t *seq_lens,
+                       const uint8_t *const *Kc, const float *const *Ksz,
+                       const uint8_t *const *Vc, const float *const *Vsz,
+                       const uint16_t *q, double *out, double *lse)
+{
+    if (B < 0 || H <= 0 || d <= 0 || (d & 1) || !seq_lens || !q || !out) return -1;
+    double inv = 1.0 / sqrt((double)d);
+    size_t rb = (size_t)d / 2;
+    for (int b = 0; b < B; ++b) {
+        int L = seq_lens[b];
+        double *s = (double *)malloc((size_t)(L > 0 ? L : 1) * sizeof(double));
+        for (int h = 0; h < H; ++h) {
+            size_t bh = (size_t)b * H + h;
+            double *o = out + bh * d;
+            for (int i = 0; i < d; ++i) o[i] = 0.0;
+            if (L <= 0) {
+                if (lse) lse[bh] = -INFINITY;
+                continue;
+            }
+            double m = -INFINITY;
+            for (int t = 0; t < L; ++t) {
+                size_t row = (size_t)t * H + h;
+                double dot = 0.0;
+                for (int i = 0; i < d; ++i)
+                    dot += fdo_half_to_double(q[bh * d + i]) * dequant4(Kc[b] + row * rb, i, Ksz[b] + row * 2);
+                s[t] = dot * inv;
+                if (s[t] > m) m = s[t];
+            }
+            double Z = 0.0;
+            for (int t = 0; t < L; ++t) {
+                s[t] = exp(s[t] - m);
+                Z += s[t];
+            }
+            for (int t = 0; t < L; ++t) {
+                size_t row = (size_t)t * H + h;
+                double a = s[t] / Z;
+                for (int i = 0; i < d; ++i) o[i] += a * dequant4(Vc[b] + row * rb, i, Vsz[b] + row * 2);
+            }
+            if (lse) lse[bh] = m + log(Z);
+        }
+        free(s);
+    }
+    return 0;
+}

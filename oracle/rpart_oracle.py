@@ -45,6 +45,12 @@ def _load():
         lib.fdo_kvq_append.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 7
         lib.fdo_rpartq_decode.restype = ctypes.c_int
         lib.fdo_rpartq_decode.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 8
+        lib.fdo_quantize_row_u4.restype = None
+        lib.fdo_quantize_row_u4.argtypes = [ctypes.c_void_p, ctypes.c_int] + [ctypes.c_void_p] * 3
+        lib.fdo_kvq4_append.restype = None
+        lib.fdo_kvq4_append.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 7
+        lib.fdo_rpartq4_decode.restype = ctypes.c_int
+        lib.fdo_rpartq4_decode.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 8
         _lib = lib
     return _lib
 
@@ -163,4 +169,59 @@ def rpartq_decode(Kc, Ks, Vc, Vs, seq_lens: np.ndarray, q: np.ndarray):
                                    q.ctypes.data, out.ctypes.data, lse.ctypes.data)
     if rc != 0:
         raise ValueError("fdo_rpartq_decode: invalid arguments")
+    return out, lse
+
+
+# ---------------------------------------------------------------------------
+# 4-bit cache: packed codes (two per byte) and a (scale, zero) pair per token and head
+# ---------------------------------------------------------------------------
+def quantize_rows_u4(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """x: uint16 [..., d] binary16 patterns -> (packed uint8 [..., d/2], float32 [..., 2] = scale, zero)."""
+    x = np.ascontiguousarray(x, dtype=np.uint16)
+    d = x.shape[-1]
+    assert d % 2 == 0
+    flat = x.reshape(-1, d)
+    packed = np.empty((flat.shape[0], d // 2), dtype=np.uint8)
+    sz = np.empty((flat.shape[0], 2), dtype=np.float32)
+    lib = _load()
+    for r in range(flat.shape[0]):
+        lib.fdo_quantize_row_u4(flat[r].ctypes.data, d, packed[r].ctypes.data,
+                                sz[r, 0:1].ctypes.data, sz[r, 1:2].ctypes.data)
+    return packed.reshape(x.shape[:-1] + (d // 2,)), sz.reshape(x.shape[:-1] + (2,))
+
+
+def unpack_u4(packed: np.ndarray) -> np.ndarray:
+    """uint8 [..., d/2] -> codes uint8 [..., d] (element 2j = low nibble of byte j)."""
+    out = np.empty(packed.shape[:-1] + (packed.shape[-1] * 2,), dtype=np.uint8)
+    out[..., 0::2] = packed & 15
+    out[..., 1::2] = packed >> 4
+    return out
+
+
+def kvq4_append(Kc, Ksz, Vc, Vsz, seq_lens: np.ndarray, k_new: np.ndarray, v_new: np.ndarray) -> None:
+    """In place.  Kc[b], Vc[b]: uint8 [cap_b, H, d/2]; Ksz[b], Vsz[b]: float32 [cap_b, H, 2]."""
+    B, H, d = k_new.shape
+    assert seq_lens.dtype == np.int32 and len(Kc) == len(Ksz) == len(Vc) == len(Vsz) == B
+    for b in range(B):
+        assert Kc[b].shape[1:] == (H, d // 2) and Ksz[b].shape[1:] == (H, 2)
+        assert Kc[b].shape[0] > seq_lens[b], "cache full"
+    k_new = np.ascontiguousarray(k_new, dtype=np.uint16)
+    v_new = np.ascontiguousarray(v_new, dtype=np.uint16)
+    _load().fdo_kvq4_append(B, H, d, seq_lens.ctypes.data, _ptrs(Kc, np.uint8), _ptrs(Ksz, np.float32),
+                            _ptrs(Vc, np.uint8), _ptrs(Vsz, np.float32),
+                            k_new.ctypes.data, v_new.ctypes.data)
+
+
+def rpartq4_decode(Kc, Ksz, Vc, Vsz, seq_lens: np.ndarray, q: np.ndarray):
+    """Attention of q over the dequantised rows (code * scale + zero).  Returns (out, lse) float64."""
+    B, H, d = q.shape
+    assert seq_lens.dtype == np.int32
+    q = np.ascontiguousarray(q, dtype=np.uint16)
+    out = np.empty((B, H, d), dtype=np.float64)
+    lse = np.empty((B, H), dtype=np.float64)
+    rc = _load().fdo_rpartq4_decode(B, H, d, seq_lens.ctypes.data, _ptrs(Kc, np.uint8),
+                                    _ptrs(Ksz, np.float32), _ptrs(Vc, np.uint8), _ptrs(Vsz, np.float32),
+                                    q.ctypes.data, out.ctypes.data, lse.ctypes.data)
+    if rc != 0:
+        raise ValueError("fdo_rpartq4_decode: invalid arguments")
     return out, lse
