@@ -41,6 +41,14 @@ def counter_traffic(config_name):
 
 
 
+def kv_bytes_per_token(cfg, kv):
+    """Algorithmic bytes per cached token: K row + V row over all heads (quantised rows: the code
+    bytes plus the row's float32 parameters, one scale for 8 bit, scale and zero for 4 bit)."""
+    if kv == "fp16":
+        return cfg.bytes_per_token()
+    return 2 * cfg.H * (cfg.d + 4) if kv == "int8" else 2 * cfg.H * (cfg.d // 2 + 8)
+
+
 def build_case(cfg, lens, seed, chunk_tokens, growth=8, kv="fp16", window=0, sinks=0):
     """window > 0: a windowed cache of sinks + window rows per sequence that has already seen
     lens[b] tokens (its rows hold that many, or all of them when the history is longer)."""
@@ -49,12 +57,13 @@ def build_case(cfg, lens, seed, chunk_tokens, growth=8, kv="fp16", window=0, sin
     from paper_2403_11421_amd.kvcache import KVCache, KVCacheQ
 
     dev = torch.device("cuda:0")
+    kw = {} if kv == "fp16" else {"bits": 4 if kv == "int4" else 8}
     cls = KVCache if kv == "fp16" else KVCacheQ
     if window > 0:
-        cache = cls(cfg.B, cfg.H, cfg.d, [sinks + window] * cfg.B, dev, chunk_tokens, n_sink=sinks)
+        cache = cls(cfg.B, cfg.H, cfg.d, [sinks + window] * cfg.B, dev, chunk_tokens, n_sink=sinks, **kw)
         held = [min(L, sinks + window) for L in lens]
     else:
-        cache = cls(cfg.B, cfg.H, cfg.d, [L + growth for L in lens], dev, chunk_tokens)
+        cache = cls(cfg.B, cfg.H, cfg.d, [L + growth for L in lens], dev, chunk_tokens, **kw)
         held = lens
     for b, L in enumerate(held):
         if L:
@@ -145,7 +154,7 @@ def pipeline_mode(args) -> int:
     n_tokens = args.warmup + args.steps
     sub = [W.RPartConfig(f"{cfg.name}_mb{m}", Bm, cfg.H, cfg.d, "const", 0, 0, scale=cfg.scale)
            for m in range(2)]
-    bpt = cfg.bytes_per_token() if args.kv == "fp16" else 2 * cfg.H * (cfg.d + 4)
+    bpt = kv_bytes_per_token(cfg, args.kv)
     rw = RWorker(cfg.H, cfg.d, N, [[L + n_tokens + 1 for L in l] for l in mb_lens],
                  kv=args.kv, n_streams=2, device=dev)
     for m in range(2):
@@ -163,7 +172,7 @@ def pipeline_mode(args) -> int:
     kn = [[vec[m][l]["k_new"] for l in range(N)] for m in range(2)]
     vn = [[vec[m][l]["v_new"] for l in range(N)] for m in range(2)]
     out = [[torch.empty_like(q[m][l]) for l in range(N)] for m in range(2)]
-    step_fn = rpart.fd_rpartq_step if args.kv == "int8" else rpart.fd_rpart_step
+    step_fn = rpart.fd_rpart_step if args.kv == "fp16" else rpart.fd_rpartq_step
     for mode in ("serial", "shared", "overlap"):                                 # same caches for all
         for m in range(2):
             rw.set_lens(m, mb_lens[m])
@@ -214,8 +223,8 @@ def main() -> int:
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--chunk-tokens", type=int, default=0, help="split-K chunk length, 0 = library's choice")
     ap.add_argument("--cpu-sample", type=int, default=96, help="sequences timed on the CPU oracle (0 = skip)")
-    ap.add_argument("--kv", choices=["fp16", "int8"], default="fp16",
-                    help="KV-cache format: fp16 (the headline path) or the int8 quantised cache")
+    ap.add_argument("--kv", choices=["fp16", "int8", "int4"], default="fp16",
+                    help="KV-cache format: fp16 (the headline path) or a quantised cache (Section 5.2)")
     ap.add_argument("--schedule", choices=["none", "batch", "sls", "both"], default="none",
                     help="instead of the fixed-length step, run a multi-step decode loop under the "
                          "large-batch or the load-stabilising schedule (Section 4.2) and report the "
@@ -260,9 +269,9 @@ def main() -> int:
     if args.window > 0:                            # rows attended after the append: the bounded buffer's
         n_tok = sum(min(L + 1, args.sinks + args.window) for L in lens)
     # algorithmic bytes: every cached K and V row once (int8: d code bytes + a 4-byte scale per row)
-    bytes_per_token = cfg.bytes_per_token() if args.kv == "fp16" else 2 * cfg.H * (cfg.d + 4)
+    bytes_per_token = kv_bytes_per_token(cfg, args.kv)
     kv_bytes = bytes_per_token * n_tok
-    q8 = args.kv == "int8"
+    q8 = args.kv != "fp16"
     f_append = rpart.fd_kvq_append if q8 else rpart.fd_kv_append
     f_plan = rpart.fd_rpartq_plan if q8 else rpart.fd_rpart_plan
     f_partial = rpart.fd_rpartq_partial if q8 else rpart.fd_rpart_partial

@@ -182,23 +182,32 @@ int fd_plan_info(const void *workspace, int32_t info[4], void *stream);
 /* ------------------------------------------------------------------------- */
 
 /*
- * int8 KV-cache of one layer.  The paper leaves the quantiser to the user; the one
- * implemented is symmetric with one scale per token and head, evaluated in IEEE
- * binary32 so that the stored bytes are reproducible:
- *     scale = max_i |x_i| / 127,   code_i = rint(x_i / scale)  (ties to even),
- * the byte stored is code_i + 128; an all-zero row gets scale 0 and bytes 128.
- * The query needs no transformation for this scheme.  d must be 128.
+ * Quantised KV-cache of one layer, 8 or 4 bits per element.  The paper leaves the
+ * quantiser to the user; the ones implemented keep one set of parameters per token
+ * and head and are evaluated in IEEE binary32 so that the stored bytes are
+ * reproducible:
+ *   bits = 8 (or 0): symmetric.  scale = max_i |x_i| / 127, code_i = rint(x_i / scale)
+ *       (ties to even), the byte stored is code_i + 128; value = (byte - 128) * scale;
+ *       an all-zero row gets scale 0 and bytes 128.  One float per row in k_scale.
+ *   bits = 4: asymmetric.  zero = min_i x_i, scale = (max_i x_i - zero) / 15,
+ *       code_i = rint((x_i - zero) / scale) in 0..15, element 2j in the low nibble of
+ *       byte j, element 2j+1 in the high one; value = code * scale + zero; a constant
+ *       row gets scale 0 and codes 0.  Two floats (scale, zero) per row in k_scale.
+ * The query needs no transformation for these schemes.  d must be 128.
  *
- * Byte i of the K row of sequence b, head h, token t is
- *     k_codes[ seq_off[b] + ((int64)h * seq_cap[b] + t) * d + i ]
- * and its scale is  k_scale[ seq_off[b] / d + (int64)h * seq_cap[b] + t ];
- * likewise for V.  seq_off[b] must be a multiple of d; blocks must not overlap.
+ * With rb = d * bits / 8 bytes of codes per row, byte i of the K row of sequence b,
+ * head h, token t is
+ *     k_codes[ seq_off[b] + ((int64)h * seq_cap[b] + t) * rb + i ]
+ * and its parameters start at float index
+ *     (seq_off[b] / rb + (int64)h * seq_cap[b] + t) * (bits == 4 ? 2 : 1)   of k_scale;
+ * likewise for V.  seq_off[b] must be a multiple of 128; blocks must not overlap.
+ * k_scale and v_scale must be 8-byte aligned.
  */
 typedef struct fd_kvq_desc {
-    void          *k_codes;       /* device, uint8 slab of K codes                              */
-    void          *v_codes;       /* device, uint8 slab of V codes                              */
-    float         *k_scale;       /* device, float32 slab of K scales (one per code row)        */
-    float         *v_scale;       /* device, float32 slab of V scales                           */
+    void          *k_codes;       /* device, byte slab of K codes                               */
+    void          *v_codes;       /* device, byte slab of V codes                               */
+    float         *k_scale;       /* device, float32 slab of K row parameters (see above)       */
+    float         *v_scale;       /* device, float32 slab of V row parameters                   */
     const int64_t *seq_off;       /* device int64[B]: byte offset of sequence b's code block    */
     const int32_t *seq_cap;       /* device int32[B]: capacity of sequence b in tokens          */
     int32_t       *seq_lens;      /* device int32[B]: cached tokens; written by append / reset  */
@@ -207,14 +216,14 @@ typedef struct fd_kvq_desc {
     int32_t        chunk_tokens;  /* split-K chunk length in tokens; 0 = chosen on the device   */
     int32_t       *seq_seen;      /* device int32[B] or NULL: windowed cache, as in fd_kv_desc  */
     int32_t        n_sink;        /* windowed cache: leading tokens that are never replaced     */
+    int32_t        bits;          /* 8 (or 0) or 4                                              */
 } fd_kvq_desc;
 
 /*
  * Same contracts as the fp16 entry points of the same names without the "q":
  * fd_kvq_append quantises k_new[b], v_new[b] (device fp16 [B][H][d]) into row
  * seq_lens[b] and bumps the length (FD_ST_CAPACITY when full); fd_rpartq_decode is
- * Eq. 2 + Eq. 3 over the dequantised rows (code - 128) * scale with fp32 arithmetic
- * and an fp16 result; workspace size comes from fd_workspace_bytes(B, H, 128, n).
+ * Eq. 2 + Eq. 3 over the dequantised rows with fp32 arithmetic and an fp16 result; workspace size comes from fd_workspace_bytes(B, H, 128, n).
  */
 int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new, void *stream);
 int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);

@@ -358,7 +358,7 @@ __device__ inline float row_sum(float x)
 {
     x = dpp_xadd<0xB1>(x);                  // quad_perm [1,0,3,2]
     x = dpp_xadd<0x4E>(x);                  // quad_perm [2,3,0,1]
-    x = dpp_xadd<0x141>(x);                 // row_half_mirror: other quad of the 8
+    if (LPR >= 8) x = dpp_xadd<0x141>(x);   // row_half_mirror: other quad of the 8
     if (LPR == 16) x = dpp_xadd<0x140>(x);  // row_mirror: other half of the 16
     return x;
 }

@@ -1,17 +1,23 @@
 // Quantised KV-cache path of the R-Part (FastDecode Section 5.2: K_i and V_i are added to the
-// cache after quantisation, which divides the bytes the memory-bound attention has to stream).
+// cache after quantisation, which divides the bytes the memory-bound attention has to stream;
+// with 4-bit integers the memory access size is a quarter of fp16's).
 // Included at the end of fd_rpart.hip: it reuses that file's planner, merge kernel, schedule
 // and helpers; only the cache format, the append and the streaming kernel differ.
 //
-// Format (the paper leaves the quantiser to the user): symmetric int8, one scale per token and
-// head.  scale = max|x| / 127 and code = rint(x / scale) are evaluated in IEEE binary32 so that
-// the stored bytes are reproducible bit for bit; the byte stored is code + 128.  A row of
-// d = 128 values takes 128 B of codes plus a 4 B scale (1.94 x fewer bytes than fp16).
-// The query needs no transformation for this scheme and stays fp16.
+// Formats (the paper leaves the quantiser to the user), one set of parameters per token and
+// head, everything evaluated in IEEE binary32 so that the stored bytes are reproducible:
+//   8 bit: symmetric.  scale = max|x| / 127, code = rint(x / scale), byte = code + 128;
+//          value = (byte - 128) * scale.  A row of d = 128 values: 128 B + a 4 B scale.
+//   4 bit: asymmetric. zero = min x, scale = (max x - min x) / 15,
+//          code = rint((x - zero) / scale) in 0..15, element 2j in the low nibble of byte j;
+//          value = code * scale + zero.  A row: 64 B + an 8 B (scale, zero) pair.
+// The query needs no transformation for these schemes and stays fp16.
 
 namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 template <int CTRL>
 __device__ inline float dpp_xmax(float x)
@@ -20,19 +26,42 @@ __device__ inline float dpp_xmax(float x)
     return fmaxf(x, __int_as_float(y));
 }
 
+template <int CTRL>
+__device__ inline float dpp_xmin(float x)
+{
+    const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true);
+    return fminf(x, __int_as_float(y));
+}
+
+// geometry of a quantised row of 128 elements
+template <int BITS>
+struct QFmt {
+    static_assert(BITS == 8 || BITS == 4, "8- or 4-bit codes");
+    static constexpr int D = 128;
+    static constexpr int RB = D * BITS / 8;              // bytes of codes per row
+    static constexpr int MW = BITS == 8 ? 1 : 2;         // floats of parameters per row
+    static constexpr int LB = RB / 8;                    // bytes of a row one lane loads (8 lanes per row)
+    static constexpr int NW = LB / 4;                    // 32-bit words per lane load
+};
+template <int BITS> struct CodeVec;
+template <> struct CodeVec<8> { typedef u32x4 type; };
+template <> struct CodeVec<4> { typedef u32x2 type; };
+
 // ---------------------------------------------------------------------------
 // Quantising append.  One workgroup per sequence; a row (128 fp16) is handled by 16
 // lanes with 8 values each.
 // ---------------------------------------------------------------------------
+template <int BITS>
 __global__ __launch_bounds__(256) void kvq_append_kernel(
     uint8_t *__restrict__ k_codes, uint8_t *__restrict__ v_codes,
-    float *__restrict__ k_scale, float *__restrict__ v_scale,
+    float *__restrict__ k_meta, float *__restrict__ v_meta,
     const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
     int32_t *__restrict__ seq_lens, int32_t *__restrict__ status,
     const _Float16 *__restrict__ k_new, const _Float16 *__restrict__ v_new, int H,
     int32_t *__restrict__ seq_seen, int n_sink)
 {
-    constexpr int D = 128;
+    using F = QFmt<BITS>;
+    constexpr int D = F::D;
     const int b = blockIdx.x;
     const int cap = seq_cap[b];
     int new_len = 0;
@@ -46,29 +75,56 @@ __global__ __launch_bounds__(256) void kvq_append_kernel(
         const int h = which ? r - H : r;
         const _Float16 *src = (which ? v_new : k_new) + ((int64_t)b * H + h) * D + sub * 8;
         const half8 x = *reinterpret_cast<const half8 *>(src);
-        float f[8], amax = 0.f;
+        float f[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            f[i] = (float)x[i];
-            amax = fmaxf(amax, fabsf(f[i]));
-        }
-        amax = dpp_xmax<0xB1>(amax);           // max over the 16 lanes of the row
-        amax = dpp_xmax<0x4E>(amax);
-        amax = dpp_xmax<0x141>(amax);
-        amax = dpp_xmax<0x140>(amax);
-        const float scale = __fdiv_rn(amax, 127.0f);
-        unsigned lo = 0, hi = 0;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float c = scale > 0.f ? rintf(__fdiv_rn(f[i], scale)) : 0.f;
-            const unsigned u = (unsigned)((int)c + 128) & 0xFFu;
-            if (i < 4) lo |= u << (8 * i);
-            else       hi |= u << (8 * (i - 4));
-        }
+        for (int i = 0; i < 8; ++i) f[i] = (float)x[i];
         const int64_t row = (int64_t)h * cap + L;
-        uint8_t *dst = (which ? v_codes : k_codes) + off + row * D + sub * 8;
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
-        if (sub == 0) (which ? v_scale : k_scale)[off / D + row] = scale;
+        uint8_t *dst = (which ? v_codes : k_codes) + off + row * F::RB + sub * (F::RB / 16);   // 8 codes
+        float *meta = (which ? v_meta : k_meta) + (off / F::RB + row) * F::MW;
+        if (BITS == 8) {
+            float amax = 0.f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+            amax = dpp_xmax<0xB1>(amax);           // max over the 16 lanes of the row
+            amax = dpp_xmax<0x4E>(amax);
+            amax = dpp_xmax<0x141>(amax);
+            amax = dpp_xmax<0x140>(amax);
+            const float scale = __fdiv_rn(amax, 127.0f);
+            unsigned lo = 0, hi = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float c = scale > 0.f ? rintf(__fdiv_rn(f[i], scale)) : 0.f;
+                const unsigned u = (unsigned)((int)c + 128) & 0xFFu;
+                if (i < 4) lo |= u << (8 * i);
+                else       hi |= u << (8 * (i - 4));
+            }
+            *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
+            if (sub == 0) meta[0] = scale;
+        } else {
+            float mn = f[0], mx = f[0];
+#pragma unroll
+            for (int i = 1; i < 8; ++i) {
+                mn = fminf(mn, f[i]);
+                mx = fmaxf(mx, f[i]);
+            }
+            mn = dpp_xmin<0xB1>(mn);  mx = dpp_xmax<0xB1>(mx);
+            mn = dpp_xmin<0x4E>(mn);  mx = dpp_xmax<0x4E>(mx);
+            mn = dpp_xmin<0x141>(mn); mx = dpp_xmax<0x141>(mx);
+            mn = dpp_xmin<0x140>(mn); mx = dpp_xmax<0x140>(mx);
+            const float scale = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
+            unsigned w = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float c = scale > 0.f ? rintf(__fdiv_rn(__fsub_rn(f[i], mn), scale)) : 0.f;
+                c = fminf(fmaxf(c, 0.f), 15.f);
+                w |= (unsigned)(int)c << (4 * i);
+            }
+            *reinterpret_cast<unsigned *>(dst) = w;
+            if (sub == 0) {
+                meta[0] = scale;
+                meta[1] = mn;
+            }
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -78,112 +134,184 @@ __global__ __launch_bounds__(256) void kvq_append_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Streaming kernel over int8 codes, d = 128.  A row is 128 B = 8 lanes x 16 codes; a wave
-// load covers 8 tokens; a workgroup block is 4 waves x NL loads = 32 NL tokens (4 NL KB of K
-// codes and as much of V codes).  The 8 NL tokens of a wave's tile map onto its first 8 NL lanes
-// for the scales: each lane loads the K and the V scale of "its" token (the other lanes repeat
+// Streaming kernel over codes, d = 128.  A row is 8 lanes x 16 elements (16 B of 8-bit or 8 B
+// of 4-bit codes per lane), a wave load covers 8 tokens (1 KB or 512 B); a workgroup block is
+// 4 waves x NL loads = 32 NL tokens.  The 8 NL tokens of a wave's tile map onto its first 8 NL
+// lanes for the row parameters: each lane loads those of "its" token (the other lanes repeat
 // them) and the values are handed to the lanes that need them with a cross-lane read.
 //
-// Dequantisation is folded into the arithmetic: with u = code + 128,
-//   q . k   = scale_k * (sum_i q_i u_i - 128 * sum_i q_i)
-//   sum p v = sum_t (p_t scale_v,t) u_t - 128 * sum_t (p_t scale_v,t)
-// so each element costs one byte-to-float convert and one FMA.
+// Dequantisation is folded into the arithmetic.  With value = u * scale + zero (8 bit: u is
+// the stored byte and zero = -128 * scale):
+//   q . k   = scale_k * sum_i q_i u_i + zero_k * sum_i q_i
+//   sum p v = sum_t (p_t scale_v,t) u_t  +  sum_t p_t zero_v,t   (the same for every element)
+// so an element costs one convert and one FMA (4 bit: plus a quarter of a mask/shift).
 // ---------------------------------------------------------------------------
 __device__ inline float byte_f32(unsigned w, int i) { return (float)((w >> (8 * i)) & 0xFFu); }
 
-__device__ inline u32x4 ld_stream_u(const char *p)
+template <typename V>
+__device__ inline V ld_stream_u(const char *p)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
+    return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
 }
 
-// Tile size and residency, measured on MI355X over the two-block rolling prefetch below: two
-// wave loads per tile and two workgroups per CU (187 VGPRs, two waves per SIMD) stream 6.9 TB/s
-// at 2048 tokens per sequence and 6.1 TB/s at 256; eight loads per tile with one workgroup per
-// CU (the fp16 kernel's shape) reach 6.2 and 3.3: this kernel has 2.5 x the arithmetic per byte,
-// and a second wave per SIMD is what hides it.
-constexpr int kQTileLoads = 2;      // wave loads of K (and of V) per tile
+// Tile size and residency, measured on MI355X over the two-block rolling prefetch below (8-bit
+// codes): two wave loads per tile and two workgroups per CU (187 VGPRs, two waves per SIMD)
+// stream 6.9 TB/s at 2048 tokens per sequence and 6.1 TB/s at 256; eight loads per tile with one
+// workgroup per CU (the fp16 kernel's shape) reach 6.2 and 3.3: this kernel has 2.5 x the
+// arithmetic per byte, and a second wave per SIMD is what hides it.
+// The 4-bit kernel takes twice the loads of half the size, so as many bytes are in flight.
+template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }   // wave loads per tile
 constexpr int kQWgPerCu = 2;        // workgroups per compute unit
 
-template <int NL_>
-struct TileQ8T {
-    static constexpr int D = 128;
+template <int BITS, int NL_>
+struct TileQ {
+    using F = QFmt<BITS>;
+    static constexpr int D = F::D;
     static constexpr int NL = NL_;
+    static constexpr int RB = F::RB;
+    static constexpr int MW = F::MW;
+    static constexpr int LB = F::LB;
+    static constexpr int NW = F::NW;
     static constexpr int LPR = 8;                        // lanes per row
     static constexpr int RPW = 8;                        // rows (tokens) per wave load
-    static constexpr int EPL = 16;                       // elements per lane
-    static constexpr int STRIDE = kWaves * 1024;         // bytes between a wave's consecutive loads
+    static constexpr int EPL = D / LPR;                  // elements per lane
+    static constexpr int STRIDE = kWaves * 64 * LB;      // bytes between a wave's consecutive loads
     static constexpr int TSTEP = kWaves * RPW;           // tokens between a wave's consecutive loads
-    static constexpr int BLK_TOK = NL * TSTEP;           // 256 tokens per workgroup block
+    static constexpr int BLK_TOK = NL * TSTEP;           // tokens per workgroup block
     static constexpr int BLK_BYTES = NL * STRIDE;        // bytes of K (or V) codes per block
-    u32x4 k[NL], v[NL];
-    float ks, vs;                                        // scales of this lane's own token
+    static_assert(NL * RPW <= 64, "one lane per token of the tile for the row parameters");
+    typedef typename CodeVec<BITS>::type CV;
+    CV k[NL], v[NL];
+    float ks, kz, vs, vz;                                // parameters of this lane's own token
 
-    // token (inside a block) whose scales lane `lane` of wave `wave` loads: load lane/8, row lane%8
+    // token (inside a block) whose parameters lane `lane` of wave `wave` loads
     __device__ static inline int own_token(int lane, int wave)
     {
-        return (((lane >> 3) % NL) * kWaves + wave) * RPW + (lane & 7);
+        return (((lane / RPW) % NL) * kWaves + wave) * RPW + (lane % RPW);
     }
 
-    // issue order = consumption order (loads return in order): K scale, K codes, V scale, V codes
-    __device__ inline void load(const char *kp, const char *vp, const float *ksp, const float *vsp)
+    __device__ inline void load_kmeta(const float *p)
     {
-        ks = __builtin_nontemporal_load(ksp);
+        if (BITS == 8) {
+            ks = __builtin_nontemporal_load(p);
+        } else {
+            const f32x2 t = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(p));
+            ks = t[0];
+            kz = t[1];
+        }
+    }
+    __device__ inline void load_vmeta(const float *p)
+    {
+        if (BITS == 8) {
+            vs = __builtin_nontemporal_load(p);
+        } else {
+            const f32x2 t = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(p));
+            vs = t[0];
+            vz = t[1];
+        }
+    }
+
+    // issue order = consumption order (loads return in order): K parameters, K codes,
+    // V parameters, V codes
+    __device__ inline void load(const char *kp, const char *vp, const float *kmp, const float *vmp)
+    {
+        load_kmeta(kmp);
 #pragma unroll
-        for (int j = 0; j < NL; ++j) k[j] = ld_stream_u(kp + j * STRIDE);
-        vs = __builtin_nontemporal_load(vsp);
+        for (int j = 0; j < NL; ++j) k[j] = ld_stream_u<CV>(kp + j * STRIDE);
+        load_vmeta(vmp);
 #pragma unroll
-        for (int j = 0; j < NL; ++j) v[j] = ld_stream_u(vp + j * STRIDE);
+        for (int j = 0; j < NL; ++j) v[j] = ld_stream_u<CV>(vp + j * STRIDE);
     }
 
     // ragged last block of `rem` >= 1 tokens: lanes whose token is at or beyond `rem` re-read
-    // token rem-1 (in bounds) and are masked in update<true>
-    __device__ inline void load_tail(const char *kp, const char *vp, const float *ksp,
-                                     const float *vsp, int tok0, int own, int rem)
+    // token rem-1 (in bounds) and are masked in update<true, ...>
+    __device__ inline void load_tail(const char *kp, const char *vp, const float *kmp,
+                                     const float *vmp, int tok0, int own, int rem)
     {
+        const int sback = own > rem - 1 ? own - (rem - 1) : 0;
+        load_kmeta(kmp - sback * MW);
+        load_vmeta(vmp - sback * MW);
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             const int over = j * TSTEP + tok0 - (rem - 1);
-            const int back = over > 0 ? over * D : 0;
-            k[j] = ld_stream_u(kp + (j * STRIDE - back));
-            v[j] = ld_stream_u(vp + (j * STRIDE - back));
+            const int back = over > 0 ? over * RB : 0;
+            k[j] = ld_stream_u<CV>(kp + (j * STRIDE - back));
+            v[j] = ld_stream_u<CV>(vp + (j * STRIDE - back));
         }
-        const int sback = own > rem - 1 ? own - (rem - 1) : 0;
-        ks = __builtin_nontemporal_load(ksp - sback);
-        vs = __builtin_nontemporal_load(vsp - sback);
+    }
+
+    // sum_e q[e] * u_e over this lane's 16 elements
+    __device__ static inline float dot_codes(const CV &c, const float (&q)[EPL])
+    {
+        float a = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            if (BITS == 8) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a = __builtin_fmaf(byte_f32(c[w], i), q[w * 4 + i], a);
+            } else {
+                const unsigned lo = c[w] & 0x0F0F0F0Fu, hi = (c[w] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    a = __builtin_fmaf(byte_f32(lo, i), q[w * 8 + 2 * i], a);
+                    a = __builtin_fmaf(byte_f32(hi, i), q[w * 8 + 2 * i + 1], a);
+                }
+            }
+        }
+        return a;
+    }
+
+    // acc[e] += pv * u_e
+    __device__ static inline void axpy_codes(const CV &c, float pv, float (&acc)[EPL])
+    {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            if (BITS == 8) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    acc[w * 4 + i] = __builtin_fmaf(pv, byte_f32(c[w], i), acc[w * 4 + i]);
+            } else {
+                const unsigned lo = c[w] & 0x0F0F0F0Fu, hi = (c[w] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[w * 8 + 2 * i] = __builtin_fmaf(pv, byte_f32(lo, i), acc[w * 8 + 2 * i]);
+                    acc[w * 8 + 2 * i + 1] = __builtin_fmaf(pv, byte_f32(hi, i), acc[w * 8 + 2 * i + 1]);
+                }
+            }
+        }
     }
 
     // Consume this tile.  With REFILL every register is reloaded with the same slot of the block
-    // two ahead (kp2, vp2, ksp2, vsp2) as soon as its last use is issued, so that close to two
+    // two ahead (kp2, vp2, kmp2, vmp2) as soon as its last use is issued, so that close to two
     // blocks of loads per wave stay in flight during the arithmetic as well.
     template <bool MASKED, bool REFILL>
-    __device__ inline void update(const float (&q)[EPL], float qsum128, float &m, float &l,
+    __device__ inline void update(const float (&q)[EPL], float qsum, float &m, float &l,
                                   float &aux, float (&acc)[EPL], int row, int tok0, int rem,
                                   const char *kp2 = nullptr, const char *vp2 = nullptr,
-                                  const float *ksp2 = nullptr, const float *vsp2 = nullptr)
+                                  const float *kmp2 = nullptr, const float *vmp2 = nullptr)
     {
-        // hand every row its tokens' K scales first: after that the register is free to refill
-        float s[NL];
+        // hand every row its tokens' K parameters first: after that the registers are free to refill
+        float s[NL], z[NL];
 #pragma unroll
-        for (int j = 0; j < NL; ++j) s[j] = __shfl(ks, j * RPW + row);
+        for (int j = 0; j < NL; ++j) {
+            s[j] = __shfl(ks, j * RPW + row);
+            z[j] = BITS == 8 ? -128.0f * s[j] : __shfl(kz, j * RPW + row);
+        }
         if (REFILL) {
             sched_fence();
-            ks = __builtin_nontemporal_load(ksp2);
+            load_kmeta(kmp2);
             sched_fence();
         }
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            float a = 0.f;
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) a = __builtin_fmaf(byte_f32(k[j][w], i), q[w * 4 + i], a);
+            float a = dot_codes(k[j], q);
             if (REFILL) {
                 sched_fence();
-                k[j] = ld_stream_u(kp2 + j * STRIDE);
+                k[j] = ld_stream_u<CV>(kp2 + j * STRIDE);
                 sched_fence();
             }
             a = row_sum<LPR>(a);
-            a = (a - qsum128) * s[j];
+            a = __builtin_fmaf(a, s[j], z[j] * qsum);
             if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
             s[j] = a;
         }
@@ -196,31 +324,27 @@ struct TileQ8T {
         aux *= corr;
 #pragma unroll
         for (int i = 0; i < EPL; ++i) acc[i] *= corr;
-        // weights times V scales, then the V scale register is free as well
+        // weights times V scales; the weighted zero points go to aux; then the V parameter
+        // registers are free as well
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             float p = fast_exp2(s[j] - mn);
             if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
             l += p;
             s[j] = p * __shfl(vs, j * RPW + row);
-            aux += s[j];
+            aux += BITS == 8 ? -128.0f * s[j] : p * __shfl(vz, j * RPW + row);
         }
         if (REFILL) {
             sched_fence();
-            vs = __builtin_nontemporal_load(vsp2);
+            load_vmeta(vmp2);
             sched_fence();
         }
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            const float pv = s[j];
-#pragma unroll
-            for (int w = 0; w < 4; ++w)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    acc[w * 4 + i] = __builtin_fmaf(pv, byte_f32(v[j][w], i), acc[w * 4 + i]);
+            axpy_codes(v[j], s[j], acc);
             if (REFILL) {
                 sched_fence();
-                v[j] = ld_stream_u(vp2 + j * STRIDE);
+                v[j] = ld_stream_u<CV>(vp2 + j * STRIDE);
                 sched_fence();
             }
         }
@@ -228,20 +352,19 @@ struct TileQ8T {
     }
 };
 
-using TileQ8 = TileQ8T<kQTileLoads>;
-
+template <int BITS>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kQWgPerCu, kQWgPerCu)))
 void rpartq_partial_kernel(
     const char *__restrict__ k_codes, const char *__restrict__ v_codes,
-    const float *__restrict__ k_scale, const float *__restrict__ v_scale,
+    const float *__restrict__ k_meta, const float *__restrict__ v_meta,
     const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
     const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
     const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
     const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
     float qscale)
 {
-    using T = TileQ8;
-    constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL;
+    using T = TileQ<BITS, q_tile_loads<BITS>()>;
+    constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL, RB = T::RB, MW = T::MW, LB = T::LB;
     __shared__ float sm_acc[kWaves][D];
     __shared__ float sm_m[kWaves], sm_l[kWaves], sm_aux[kWaves];
 
@@ -251,7 +374,7 @@ void rpartq_partial_kernel(
     const int row = lane / LPR;
     const int col = lane % LPR;
     const int tok0 = wave * T::RPW + row;                  // this lane's token in a block, load 0
-    const int own = T::own_token(lane, wave);              // token whose scales this lane loads
+    const int own = T::own_token(lane, wave);              // token whose parameters this lane loads
     const int n_units = hdr[HDR_NITEMS] * H;
     const int W = hdr[HDR_GRID], g = blockIdx.x;          // active workgroups, chosen by the planner
     if (g >= W) return;
@@ -275,7 +398,7 @@ void rpartq_partial_kernel(
                 u.item = item;
                 u.nch = it.w;
                 u.ntok = it.z - it.y;
-                u.row0 = seq_off[it.x] / D + (int64_t)u.h * seq_cap[it.x] + it.y;   // row index
+                u.row0 = seq_off[it.x] / RB + (int64_t)u.h * seq_cap[it.x] + it.y;   // row index
             }
         }
         return u;
@@ -289,24 +412,23 @@ void rpartq_partial_kernel(
         if (nxt.ntok == 0 && j < n_rounds) nxt = fetch(++j);
 
         const int b = cur.b, h = cur.h;
-        const char *kp = k_codes + cur.row0 * D + tid * 16;     // wave w starts at its 1 KB slot
-        const char *vp = v_codes + cur.row0 * D + tid * 16;
-        const float *ksp = k_scale + cur.row0 + own;
-        const float *vsp = v_scale + cur.row0 + own;
+        const char *kp = k_codes + cur.row0 * RB + tid * LB;    // wave w starts at its own slot
+        const char *vp = v_codes + cur.row0 * RB + tid * LB;
+        const float *kmp = k_meta + (cur.row0 + own) * MW;
+        const float *vmp = v_meta + (cur.row0 + own) * MW;
 
         float qf[EPL], qsum = 0.f;
         {
             const _Float16 *qp = q + ((int64_t)b * H + h) * D + col * EPL;
-            const half8 q0 = *reinterpret_cast<const half8 *>(qp);
-            const half8 q1 = *reinterpret_cast<const half8 *>(qp + 8);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                qf[i] = (float)q0[i] * qscale;
-                qf[8 + i] = (float)q1[i] * qscale;
+            for (int c8 = 0; c8 < EPL / 8; ++c8) {
+                const half8 qh = *reinterpret_cast<const half8 *>(qp + 8 * c8);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) qf[8 * c8 + i] = (float)qh[i] * qscale;
             }
 #pragma unroll
             for (int i = 0; i < EPL; ++i) qsum += qf[i];
-            qsum = row_sum<LPR>(qsum) * 128.0f;                  // 128 * sum of the whole query
+            qsum = row_sum<LPR>(qsum);                           // sum of the whole query
         }
 
         float m = kNegBig, l = 0.f, aux = 0.f, acc[EPL];
@@ -319,39 +441,40 @@ void rpartq_partial_kernel(
 
         const char *kt = kp;
         const char *vt = vp;
-        const float *kst = ksp;
-        const float *vst = vsp;
+        const float *kmt = kmp;
+        const float *vmt = vmp;
+        constexpr int MSTEP = T::BLK_TOK * MW;                  // floats of parameters per block
         T A, Bf;
         if (n_blk > 0) {
             int left = n_blk;                              // A holds block n_blk-left, Bf the one after
             if (n_blk >= 4) {
                 // both loads are issued unconditionally on the way into the loop: its wait
                 // counts can then leave a whole block outstanding behind the one in use
-                A.load(kt, vt, kst, vst);
-                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kst + T::BLK_TOK, vst + T::BLK_TOK);
+                A.load(kt, vt, kmt, vmt);
+                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kmt + MSTEP, vmt + MSTEP);
                 sched_fence();
                 do {
                     A.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
                                                    kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES,
-                                                   kst + 2 * T::BLK_TOK, vst + 2 * T::BLK_TOK);
+                                                   kmt + 2 * MSTEP, vmt + 2 * MSTEP);
                     Bf.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
                                                     kt + 3 * T::BLK_BYTES, vt + 3 * T::BLK_BYTES,
-                                                    kst + 3 * T::BLK_TOK, vst + 3 * T::BLK_TOK);
+                                                    kmt + 3 * MSTEP, vmt + 3 * MSTEP);
                     kt += 2 * T::BLK_BYTES;
                     vt += 2 * T::BLK_BYTES;
-                    kst += 2 * T::BLK_TOK;
-                    vst += 2 * T::BLK_TOK;
+                    kmt += 2 * MSTEP;
+                    vmt += 2 * MSTEP;
                     left -= 2;
                 } while (left > 3);
             } else {
-                A.load(kt, vt, kst, vst);
-                if (n_blk > 1) Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kst + T::BLK_TOK, vst + T::BLK_TOK);
+                A.load(kt, vt, kmt, vmt);
+                if (n_blk > 1) Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kmt + MSTEP, vmt + MSTEP);
                 sched_fence();
             }
             if (left == 3) {
                 A.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
                                                kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES,
-                                               kst + 2 * T::BLK_TOK, vst + 2 * T::BLK_TOK);
+                                               kmt + 2 * MSTEP, vmt + 2 * MSTEP);
                 Bf.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
                 A.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
             } else if (left == 2) {
@@ -363,8 +486,8 @@ void rpartq_partial_kernel(
         }
         if (rem > 0 && wave * T::RPW < rem) {              // this wave has at least one valid row
             const int64_t o = (int64_t)n_blk * T::BLK_BYTES;
-            const int64_t so = (int64_t)n_blk * T::BLK_TOK;
-            A.load_tail(kp + o, vp + o, ksp + so, vsp + so, tok0, own, rem);
+            const int64_t so = (int64_t)n_blk * MSTEP;
+            A.load_tail(kp + o, vp + o, kmp + so, vmp + so, tok0, own, rem);
             A.template update<true, false>(qf, qsum, m, l, aux, acc, row, tok0, rem);
         }
 
@@ -401,7 +524,7 @@ void rpartq_partial_kernel(
                 X += a * sm_aux[w];
                 o += a * sm_acc[w][tid];
             }
-            o -= 128.0f * X;                                 // remove the +128 byte offset
+            o += X;                                          // the weighted zero points
             if (cur.nch == 1) {
                 __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
             } else {
@@ -426,12 +549,13 @@ int check_qdesc(const fd_kvq_desc *d)
     if (!d) return FD_EINVAL;
     if (d->B < 0 || d->H <= 0 || d->d != 128) return FD_EINVAL;
     if (d->chunk_tokens < 0) return FD_EINVAL;
+    if (d->bits != 0 && d->bits != 8 && d->bits != 4) return FD_EINVAL;
     if (d->B == 0) return FD_OK;
     if (!d->k_codes || !d->v_codes || !d->k_scale || !d->v_scale || !d->seq_off || !d->seq_cap ||
         !d->seq_lens || !d->status)
         return FD_EINVAL;
-    if (!aligned(d->k_codes, 16) || !aligned(d->v_codes, 16) || !aligned(d->k_scale, 4) ||
-        !aligned(d->v_scale, 4) || !aligned(d->seq_off, 8) || !aligned(d->seq_cap, 4) ||
+    if (!aligned(d->k_codes, 16) || !aligned(d->v_codes, 16) || !aligned(d->k_scale, 8) ||
+        !aligned(d->v_scale, 8) || !aligned(d->seq_off, 8) || !aligned(d->seq_cap, 4) ||
         !aligned(d->seq_lens, 4) || !aligned(d->status, 4))
         return FD_EINVAL;
     if (d->seq_seen && (!aligned(d->seq_seen, 4) || d->n_sink < 0)) return FD_EINVAL;
@@ -456,11 +580,18 @@ int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new,
     if (rc != FD_OK) return rc;
     if (desc->B == 0) return FD_OK;
     if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
-    hipLaunchKernelGGL(kvq_append_kernel, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
-                       (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
-                       desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens, desc->status,
-                       (const _Float16 *)k_new, (const _Float16 *)v_new, desc->H, desc->seq_seen,
-                       desc->n_sink);
+    if (desc->bits == 4)
+        hipLaunchKernelGGL(kvq_append_kernel<4>, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
+                           (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
+                           desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens,
+                           desc->status, (const _Float16 *)k_new, (const _Float16 *)v_new, desc->H,
+                           desc->seq_seen, desc->n_sink);
+    else
+        hipLaunchKernelGGL(kvq_append_kernel<8>, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
+                           (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
+                           desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens,
+                           desc->status, (const _Float16 *)k_new, (const _Float16 *)v_new, desc->H,
+                           desc->seq_seen, desc->n_sink);
     return launched();
 }
 
@@ -523,12 +654,22 @@ int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
     if (grid <= 0) return FD_EHIP;
     char *ws = (char *)workspace;
     const float qscale = (float)(1.4426950408889634 / 11.313708498984761);
-    hipLaunchKernelGGL(rpartq_partial_kernel, dim3(kQWgPerCu * grid), dim3(kThreads), 0, (hipStream_t)stream,
-                       (const char *)desc->k_codes, (const char *)desc->v_codes, desc->k_scale,
-                       desc->v_scale, desc->seq_off, desc->seq_cap, (const _Float16 *)q,
-                       (_Float16 *)out, desc->H, (const int32_t *)ws,
-                       (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
-                       (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale);
+    if (desc->bits == 4)
+        hipLaunchKernelGGL(rpartq_partial_kernel<4>, dim3(kQWgPerCu * grid), dim3(kThreads), 0,
+                           (hipStream_t)stream, (const char *)desc->k_codes,
+                           (const char *)desc->v_codes, desc->k_scale, desc->v_scale, desc->seq_off,
+                           desc->seq_cap, (const _Float16 *)q, (_Float16 *)out, desc->H,
+                           (const int32_t *)ws, (const int4 *)(ws + w.off_items),
+                           (const int32_t *)(ws + w.off_order), (float *)(ws + w.off_acc),
+                           (float *)(ws + w.off_ml), qscale);
+    else
+        hipLaunchKernelGGL(rpartq_partial_kernel<8>, dim3(kQWgPerCu * grid), dim3(kThreads), 0,
+                           (hipStream_t)stream, (const char *)desc->k_codes,
+                           (const char *)desc->v_codes, desc->k_scale, desc->v_scale, desc->seq_off,
+                           desc->seq_cap, (const _Float16 *)q, (_Float16 *)out, desc->H,
+                           (const int32_t *)ws, (const int4 *)(ws + w.off_items),
+                           (const int32_t *)(ws + w.off_order), (float *)(ws + w.off_acc),
+                           (float *)(ws + w.off_ml), qscale);
     return launched();
 }
 

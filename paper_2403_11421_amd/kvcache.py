@@ -85,26 +85,47 @@ def quantize_rows_i8(rows: torch.Tensor):
     return (code + 128.0).to(torch.uint8), scale
 
 
+def quantize_rows_u4(rows: torch.Tensor):
+    """fp16 rows [..., d] -> (packed uint8 [..., d/2], float32 [..., 2] = scale, zero).
+
+    Input preparation for tests and benchmarks, as `quantize_rows_i8`: zero = min, scale =
+    (max - min) / 15, code = rint((x - zero) / scale) clamped to 0..15, element 2j in the low
+    nibble of byte j."""
+    x = rows.float()
+    mn = x.amin(dim=-1)
+    scale = (x.amax(dim=-1) - mn) / 15.0
+    safe = torch.where(scale > 0, scale, torch.ones_like(scale))
+    code = torch.where(scale.unsqueeze(-1) > 0,
+                       torch.round((x - mn.unsqueeze(-1)) / safe.unsqueeze(-1)), torch.zeros_like(x))
+    code = code.clamp_(0, 15).to(torch.uint8)
+    packed = code[..., 0::2] | (code[..., 1::2] << 4)
+    return packed, torch.stack([scale, mn], dim=-1)
+
+
 class KVCacheQ:
-    """int8 KV-cache of one layer in the layout of ``fd_kvq_desc`` (d = 128)."""
+    """Quantised KV-cache of one layer in the layout of ``fd_kvq_desc`` (d = 128, 8 or 4 bits)."""
 
     def __init__(self, B: int, H: int, d: int, capacities: Sequence[int], device="cuda",
-                 chunk_tokens: int = 0, n_sink: Optional[int] = None):
-        assert len(capacities) == B and d == 128
-        self.B, self.H, self.d = B, H, d
+                 chunk_tokens: int = 0, n_sink: Optional[int] = None, bits: int = 8):
+        assert len(capacities) == B and d == 128 and bits in (8, 4)
+        self.B, self.H, self.d, self.bits = B, H, d, bits
+        self.rb = d * bits // 8                         # bytes of codes per row
+        self.mw = 1 if bits == 8 else 2                 # floats of parameters per row
         self.device = torch.device(device)
         self.caps = [max(1, int(c)) for c in capacities]
         offs, o = [], 0
         for c in self.caps:
             offs.append(o)
-            o += H * c * d                              # bytes of codes; multiple of d
+            o += H * c * self.rb                        # bytes of codes
             o = (o + 255) // 256 * 256
         self.offs = offs
         self.total_bytes = max(o, 256)
-        self.k_codes = torch.full((self.total_bytes,), 128, dtype=torch.uint8, device=self.device)
-        self.v_codes = torch.full((self.total_bytes,), 128, dtype=torch.uint8, device=self.device)
-        self.k_scale = torch.zeros(self.total_bytes // d, dtype=torch.float32, device=self.device)
-        self.v_scale = torch.zeros(self.total_bytes // d, dtype=torch.float32, device=self.device)
+        fill = 128 if bits == 8 else 0
+        self.k_codes = torch.full((self.total_bytes,), fill, dtype=torch.uint8, device=self.device)
+        self.v_codes = torch.full((self.total_bytes,), fill, dtype=torch.uint8, device=self.device)
+        n_meta = self.total_bytes // self.rb * self.mw
+        self.k_scale = torch.zeros(n_meta, dtype=torch.float32, device=self.device)
+        self.v_scale = torch.zeros(n_meta, dtype=torch.float32, device=self.device)
         self.seq_off = torch.tensor(offs, dtype=torch.int64, device=self.device)
         self.seq_cap = torch.tensor(self.caps, dtype=torch.int32, device=self.device)
         self.seq_lens = torch.zeros(B, dtype=torch.int32, device=self.device)
@@ -114,24 +135,26 @@ class KVCacheQ:
             self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_scale.data_ptr(),
             self.v_scale.data_ptr(), self.seq_off.data_ptr(), self.seq_cap.data_ptr(),
             self.seq_lens.data_ptr(), self.status.data_ptr(), B, H, d, chunk_tokens,
-            None if n_sink is None else self.seq_seen.data_ptr(), 0 if n_sink is None else n_sink)
+            None if n_sink is None else self.seq_seen.data_ptr(), 0 if n_sink is None else n_sink,
+            bits)
 
     def codes(self, which: str, b: int) -> torch.Tensor:
-        """View ``[H, cap_b, d]`` (uint8) of sequence b's K or V codes."""
+        """View ``[H, cap_b, rb]`` (uint8) of sequence b's K or V code bytes."""
         slab = self.k_codes if which == "K" else self.v_codes
-        n = self.H * self.caps[b] * self.d
-        return slab[self.offs[b]: self.offs[b] + n].view(self.H, self.caps[b], self.d)
+        n = self.H * self.caps[b] * self.rb
+        return slab[self.offs[b]: self.offs[b] + n].view(self.H, self.caps[b], self.rb)
 
     def scales(self, which: str, b: int) -> torch.Tensor:
-        """View ``[H, cap_b]`` (float32) of sequence b's K or V scales."""
+        """View ``[H, cap_b]`` (8 bit: scale) or ``[H, cap_b, 2]`` (4 bit: scale, zero), float32."""
         slab = self.k_scale if which == "K" else self.v_scale
-        o = self.offs[b] // self.d
-        return slab[o: o + self.H * self.caps[b]].view(self.H, self.caps[b])
+        o = self.offs[b] // self.rb * self.mw
+        v = slab[o: o + self.H * self.caps[b] * self.mw]
+        return v.view(self.H, self.caps[b]) if self.mw == 1 else v.view(self.H, self.caps[b], 2)
 
     def fill(self, which: str, b: int, rows: torch.Tensor, t0: int = 0) -> None:
         """Quantise fp16 ``rows [H, L, d]`` into tokens t0..t0+L-1 of sequence b."""
         L = rows.shape[1]
-        c, s = quantize_rows_i8(rows)
+        c, s = quantize_rows_i8(rows) if self.bits == 8 else quantize_rows_u4(rows)
         self.codes(which, b)[:, t0:t0 + L, :].copy_(c)
         self.scales(which, b)[:, t0:t0 + L].copy_(s)
 

@@ -25,13 +25,17 @@ class RWorker:
     def __init__(self, H: int, d: int, n_layers: int, capacities: Sequence[Sequence[int]],
                  kv: str = "fp16", n_streams: int = 2, device="cuda", chunk_tokens: int = 0):
         """capacities[m][b]: token capacity of sequence b of mini-batch m (m = 0, 1, ...)."""
-        assert kv in ("fp16", "int8") and n_streams in (1, 2) and n_layers >= 1
+        assert kv in ("fp16", "int8", "int4") and n_streams in (1, 2) and n_layers >= 1
         self.H, self.d, self.n_layers, self.kv = H, d, n_layers, kv
         self.device = torch.device(device)
-        cls = KVCache if kv == "fp16" else KVCacheQ
         self.n_mb = len(capacities)
-        self.caches: List[List] = [[cls(len(caps), H, d, caps, self.device, chunk_tokens)
-                                    for _ in range(n_layers)] for caps in capacities]
+
+        def cache(caps):
+            if kv == "fp16":
+                return KVCache(len(caps), H, d, caps, self.device, chunk_tokens)
+            return KVCacheQ(len(caps), H, d, caps, self.device, chunk_tokens, bits=4 if kv == "int4" else 8)
+
+        self.caches: List[List] = [[cache(caps) for _ in range(n_layers)] for caps in capacities]
         self.ws = [self.caches[m][0].workspace(sum(capacities[m])) for m in range(self.n_mb)]
         self._own = [torch.cuda.Stream(self.device) for _ in range(self.n_mb)]   # default priority
         self.use_streams(n_streams)

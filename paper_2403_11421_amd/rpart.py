@@ -37,7 +37,7 @@ class fd_kvq_desc(ctypes.Structure):
         ("seq_off", _vp), ("seq_cap", _vp), ("seq_lens", _vp), ("status", _vp),
         ("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
         ("chunk_tokens", ctypes.c_int32),
-        ("seq_seen", _vp), ("n_sink", ctypes.c_int32),
+        ("seq_seen", _vp), ("n_sink", ctypes.c_int32), ("bits", ctypes.c_int32),
     ]
 
 

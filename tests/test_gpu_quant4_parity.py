@@ -1,0 +1,201 @@
+"""4-bit KV-cache path (FastDecode Section 5.2) vs the oracle, through the C ABI.
+
+Bar: lengths, code bytes and (scale, zero) pairs bit-exact (the quantiser decides integers,
+both sides decide them in binary32); out within 2e-3 * max|V_dequantised|.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rpart_oracle as O
+from paper_2403_11421_amd import rpart, workloads as W
+from paper_2403_11421_amd.kvcache import KVCacheQ
+from tests.util import bits
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+def _tm(t):
+    """device [H, cap, ...] -> host token-major [cap, H, ...]"""
+    return np.ascontiguousarray(t.permute(1, 0, *range(2, t.dim())).cpu().numpy())
+
+
+def _deq(c, sz):
+    return O.unpack_u4(c).astype(np.float64) * sz[..., 0:1].astype(np.float64) + sz[..., 1:2].astype(np.float64)
+
+
+class Q4Case:
+    def __init__(self, cfg, lens, seed=W.DEFAULT_SEED, extra_cap=1, chunk_tokens=0):
+        dev = "cuda"
+        self.cfg, self.lens0 = cfg, [int(x) for x in lens]
+        self.cache = KVCacheQ(cfg.B, cfg.H, cfg.d, [L + extra_cap for L in self.lens0], dev,
+                              chunk_tokens, bits=4)
+        for b, L in enumerate(self.lens0):
+            if L:
+                self.cache.fill("K", b, W.gen_cache_block(cfg, "K", b, L, seed, dev))
+                self.cache.fill("V", b, W.gen_cache_block(cfg, "V", b, L, seed, dev))
+        self.cache.set_lens(self.lens0)
+        self.q = W.gen_vectors(cfg, "q", seed, dev)
+        self.k_new = W.gen_vectors(cfg, "k_new", seed, dev)
+        self.v_new = W.gen_vectors(cfg, "v_new", seed, dev)
+        self.out = torch.full((cfg.B, cfg.H, cfg.d), float("nan"), dtype=torch.float16, device=dev)
+        scale = max(1, -(-256 // chunk_tokens)) if chunk_tokens else 2
+        self.ws = self.cache.workspace((sum(self.lens0) + cfg.B) * scale)
+
+    def host(self, batch):
+        c = self.cache
+        return dict(Kc=[_tm(c.codes("K", b)) for b in batch], Ksz=[_tm(c.scales("K", b)) for b in batch],
+                    Vc=[_tm(c.codes("V", b)) for b in batch], Vsz=[_tm(c.scales("V", b)) for b in batch],
+                    lens=c.seq_lens.cpu().numpy().astype(np.int32)[batch].copy())
+
+
+def check_q4step(case, batch=None, use_step=False):
+    cfg = case.cfg
+    batch = list(range(cfg.B)) if batch is None else list(batch)
+    ref = case.host(batch)                                   # snapshot BEFORE the device step
+    sel = torch.tensor(batch, dtype=torch.long)
+    k_new, v_new, q = (bits(t.cpu()[sel]) for t in (case.k_new, case.v_new, case.q))
+    if use_step:
+        rpart.fd_rpartq_step(case.cache.desc, case.q, case.k_new, case.v_new, case.out, case.ws)
+    else:
+        rpart.fd_kvq_append(case.cache.desc, case.k_new, case.v_new)
+        rpart.fd_rpartq_decode(case.cache.desc, case.q, case.out, case.ws)
+    torch.cuda.synchronize()
+    assert rpart.fd_read_status(case.cache.desc) == 0
+    O.kvq4_append(ref["Kc"], ref["Ksz"], ref["Vc"], ref["Vsz"], ref["lens"], k_new, v_new)
+    want, _ = O.rpartq4_decode(ref["Kc"], ref["Ksz"], ref["Vc"], ref["Vsz"], ref["lens"], q)
+    got_state = case.host(batch)
+    assert np.array_equal(got_state["lens"], ref["lens"])
+    for key in ("Kc", "Ksz", "Vc", "Vsz"):                   # whole blocks, appended row included
+        for a, b_ in zip(got_state[key], ref[key]):
+            assert np.array_equal(a, b_), key
+    maxv = 0.0
+    for vc, vsz, L in zip(ref["Vc"], ref["Vsz"], ref["lens"]):
+        if L:
+            maxv = max(maxv, float(np.abs(_deq(vc[:L], vsz[:L])).max()))
+    got = case.out.cpu()[sel].double().numpy()
+    assert np.all(np.isfinite(got))
+    err = float(np.abs(got - want).max())
+    assert err <= TOL * maxv, f"max|err| {err:.3e} > {TOL} * max|V| ({maxv:.3f})"
+    return err, maxv
+
+
+def _cfg(name, B, H, **kw):
+    return W.RPartConfig(name, B, H, 128, "const", 0, 0, **kw)
+
+
+def test_fill_helper_prepares_a_valid_4bit_cache():
+    """Input preparation only (see the 8-bit test of the same name): the stored rows must be a
+    sensible 4-bit cache, dequantised values within half a step of the source."""
+    cfg = _cfg("fill4", 2, 3)
+    case = Q4Case(cfg, [300, 77])
+    for b, L in enumerate(case.lens0):
+        for which in ("K", "V"):
+            rows = W.gen_cache_block(cfg, which, b, L, W.DEFAULT_SEED, "cuda").double()
+            packed = case.cache.codes(which, b)[:, :L]
+            codes = torch.stack([packed & 15, packed >> 4], dim=-1).flatten(-2).double()
+            sz = case.cache.scales(which, b)[:, :L].double()
+            assert float(codes.max()) <= 15
+            assert bool(((codes * sz[..., 0:1] + sz[..., 1:2] - rows).abs() <= 0.51 * sz[..., 0:1]).all())
+
+
+EDGE_LENS = [0, 1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513,
+             1000, 2500]
+
+
+@pytest.mark.parametrize("chunk", [0, 64, 256, 1024, 4096])
+def test_edge_lengths_all_chunk_sizes(chunk):
+    cfg = _cfg("q4edges", len(EDGE_LENS), 3)
+    case = Q4Case(cfg, EDGE_LENS, seed=21, chunk_tokens=chunk)
+    check_q4step(case)
+    assert rpart.fd_plan_info(case.ws)["total_tokens"] == sum(EDGE_LENS) + len(EDGE_LENS)
+
+
+def test_step_entry_point_many_heads_and_peaked_keys():
+    cfg = W.RPartConfig("q4step", 6, 40, 128, "const", 0, 0, peaked_keys=True)
+    case = Q4Case(cfg, [300, 17, 2049, 64, 999, 4100], seed=5)
+    check_q4step(case, use_step=True)
+
+
+def test_append_quantises_bit_exactly_including_special_rows():
+    cfg = _cfg("q4bits", 3, 2)
+    case = Q4Case(cfg, [3, 0, 9])
+    case.k_new[0, 0, :] = 0                                            # constant row: scale 0, codes 0
+    case.v_new[1, 1, :] = -2.5                                          # constant non-zero row
+    case.v_new[0, 1, :] = 0
+    case.v_new[0, 1, 5] = -3.0                                          # one value away from the rest
+    case.k_new.view(torch.int16)[2, 1, :4] = torch.tensor([0x0001, 0x8001, 0x03FF, 0x0400],
+                                                           dtype=torch.int32).to(torch.int16).cuda()  # subnormals
+    case.k_new[2, 1, 4:] = 0
+    case.v_new[2, 0, :] = (torch.arange(128, dtype=torch.float16) % 31) * 0.5   # ties: (x - 0) / 1 = k + 1/2
+    case.k_new[1, 0, :] = torch.linspace(-60000, 60000, 128).to(torch.float16)  # x - zero rounds in binary32
+    check_q4step(case)
+    assert int(case.cache.codes("K", 0)[0, 3].max()) == 0
+    assert case.cache.scales("K", 0)[0, 3].tolist() == [0.0, 0.0]
+    assert case.cache.scales("V", 1)[1, 0].tolist() == [0.0, -2.5]
+
+
+def test_single_token_returns_its_dequantised_value():
+    cfg = _cfg("q4one", 5, 4)
+    case = Q4Case(cfg, [0] * 5, seed=4)
+    check_q4step(case)
+    deq = []
+    for b in range(5):
+        packed = case.cache.codes("V", b)[:, 0]
+        codes = torch.stack([packed & 15, packed >> 4], dim=-1).flatten(-2).float()
+        sz = case.cache.scales("V", b)[:, 0]
+        deq.append(codes * sz[:, 0:1] + sz[:, 1:2])
+    deq = torch.stack(deq)
+    assert float((case.out.float() - deq).abs().max()) <= 2.0 ** -10 * float(deq.abs().max())
+
+
+def test_determinism_and_chunk_independence():
+    cfg = _cfg("q4sweep", 3, 4)
+    outs = []
+    for chunk in (256, 512, 4096, 0):
+        case = Q4Case(cfg, [4000, 777, 2048], seed=8, chunk_tokens=chunk)
+        check_q4step(case)
+        first = case.out.clone()
+        rpart.fd_rpartq_decode(case.cache.desc, case.q, case.out, case.ws)
+        torch.cuda.synchronize()
+        assert torch.equal(first, case.out)
+        outs.append(first.float())
+    for o in outs[1:]:
+        assert (o - outs[0]).abs().max() <= 2e-3
+
+
+def test_capacity_overflow_reset_and_bad_bits():
+    cfg = _cfg("q4full", 2, 2)
+    case = Q4Case(cfg, [10, 20], extra_cap=1)
+    case.cache.seq_lens[0] = case.cache.caps[0]
+    before = case.cache.k_codes.clone()
+    rpart.fd_kvq_append(case.cache.desc, case.k_new, case.v_new)
+    torch.cuda.synchronize()
+    assert rpart.fd_read_status(case.cache.desc, clear=True) == rpart.FD_ST_CAPACITY
+    assert case.cache.seq_lens.cpu().tolist() == [11, 21]
+    n = cfg.H * case.cache.caps[0] * 64
+    assert torch.equal(case.cache.k_codes[:n], before[:n])
+    rpart.fd_kvq_reset(case.cache.desc, torch.tensor([1], dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert case.cache.seq_lens.cpu().tolist() == [11, 0]
+    bad = rpart.fd_kvq_desc.from_buffer_copy(case.cache.desc)
+    bad.bits = 2
+    with pytest.raises(rpart.FdError):
+        rpart.fd_kvq_append(bad, case.k_new, case.v_new)
+
+
+@pytest.mark.parametrize("name", ["c2_7b_uniform", "c4_13b_geometric"])
+def test_full_config_sampled_parity(name):
+    cfg = W.CONFIGS[name]
+    lens = W.seq_lens(cfg)
+    n_tok = W.total_tokens_after_append(lens)
+    print(f"{name}: building 4-bit cache for {n_tok} tokens", flush=True)
+    case = Q4Case(cfg, lens, extra_cap=8)
+    case.ws = case.cache.workspace(n_tok)
+    order = np.argsort(lens, kind="stable")
+    batch = sorted({int(order[0]), int(order[-1]), int(order[len(lens) // 2]), int(order[len(lens) // 3])})
+    err, maxv = check_q4step(case, batch=batch)
+    print(f"{name}: max|err|={err:.3e} max|V|={maxv:.2f} plan={rpart.fd_plan_info(case.ws)}", flush=True)
+    assert case.cache.seq_lens.cpu().tolist() == [L + 1 for L in lens]
+    assert bool(torch.isfinite(case.out.float()).all())
