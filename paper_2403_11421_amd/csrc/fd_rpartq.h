@@ -18,6 +18,7 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
 template <int CTRL>
 __device__ inline float dpp_xmax(float x)
@@ -144,9 +145,20 @@ __global__ __launch_bounds__(256) void kvq_append_kernel(
 // the stored byte and zero = -128 * scale):
 //   q . k   = scale_k * sum_i q_i u_i + zero_k * sum_i q_i
 //   sum p v = sum_t (p_t scale_v,t) u_t  +  sum_t p_t zero_v,t   (the same for every element)
-// so an element costs one convert and one FMA (4 bit: plus a quarter of a mask/shift).
+// A code sitting in the low bits of a 16-bit half is the fp16 subnormal u * 2^-24, exactly, and
+// both v_dot2_f32_f16 and the mixed-precision FMA take fp16 subnormals at full precision (checked
+// on the device): the K side costs one mask per two codes and one dot instruction per two
+// elements with the query left in fp16, the V side one mixed FMA per element; the 2^24 goes into
+// the per-token factors.
 // ---------------------------------------------------------------------------
 __device__ inline float byte_f32(unsigned w, int i) { return (float)((w >> (8 * i)) & 0xFFu); }
+
+__device__ inline f16x2 as_f16x2(unsigned w)
+{
+    union { unsigned u; f16x2 h; } x;
+    x.u = w;
+    return x.h;
+}
 
 template <typename V>
 __device__ inline V ld_stream_u(const char *p)
@@ -161,7 +173,12 @@ __device__ inline V ld_stream_u(const char *p)
 // arithmetic per byte, and a second wave per SIMD is what hides it.
 // The 4-bit kernel takes twice the loads of half the size, so as many bytes are in flight.
 template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }   // wave loads per tile
-constexpr int kQWgPerCu = 2;        // workgroups per compute unit
+// Workgroups per compute unit: two when the sequences are long; the 8-bit kernel (164 VGPRs) fits
+// a third one, which pays when the non-empty sequences average under 512 tokens (+5 % at 256
+// tokens per sequence, -5 % at 2048), so the planner switches it on there.
+constexpr int kQWgLong = 2;
+template <int BITS> constexpr int q_wg_short() { return BITS == 8 ? 3 : 2; }
+constexpr int kQShortBelow = 512;
 
 template <int BITS, int NL_>
 struct TileQ {
@@ -240,42 +257,61 @@ struct TileQ {
         }
     }
 
-    // sum_e q[e] * u_e over this lane's 16 elements
-    __device__ static inline float dot_codes(const CV &c, const float (&q)[EPL])
+    // 2^-24 * sum_e q[e] * u_e over this lane's 16 elements.  A code in the low bits of a
+    // 16-bit half is the fp16 subnormal u * 2^-24, exactly, and v_dot2_f32_f16 takes subnormal
+    // inputs at full precision: two codes cost one mask (and shift) and one dot instruction,
+    // with the query left in fp16.  qh holds the query pairs in the order the masks produce.
+    __device__ static inline float dot_codes(const CV &c, const f16x2 (&qh)[EPL / 2])
     {
         float a = 0.f;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             if (BITS == 8) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) a = __builtin_fmaf(byte_f32(c[w], i), q[w * 4 + i], a);
+                a = __builtin_amdgcn_fdot2(as_f16x2(c[w] & 0x00FF00FFu), qh[2 * w], a, false);
+                a = __builtin_amdgcn_fdot2(as_f16x2((c[w] >> 8) & 0x00FF00FFu), qh[2 * w + 1], a, false);
             } else {
-                const unsigned lo = c[w] & 0x0F0F0F0Fu, hi = (c[w] >> 4) & 0x0F0F0F0Fu;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    a = __builtin_fmaf(byte_f32(lo, i), q[w * 8 + 2 * i], a);
-                    a = __builtin_fmaf(byte_f32(hi, i), q[w * 8 + 2 * i + 1], a);
-                }
+                for (int i = 0; i < 4; ++i)
+                    a = __builtin_amdgcn_fdot2(as_f16x2((c[w] >> (4 * i)) & 0x000F000Fu), qh[4 * w + i], a, false);
             }
         }
         return a;
     }
 
-    // acc[e] += pv * u_e
-    __device__ static inline void axpy_codes(const CV &c, float pv, float (&acc)[EPL])
+    // the query pairs for dot_codes from this lane's 16 query elements
+    __device__ static inline void pack_query(const _Float16 (&q)[EPL], f16x2 (&qh)[EPL / 2])
     {
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             if (BITS == 8) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    acc[w * 4 + i] = __builtin_fmaf(pv, byte_f32(c[w], i), acc[w * 4 + i]);
+                qh[2 * w] = f16x2{q[4 * w], q[4 * w + 2]};           // bytes 0 and 2 of word w
+                qh[2 * w + 1] = f16x2{q[4 * w + 1], q[4 * w + 3]};   // bytes 1 and 3
             } else {
-                const unsigned lo = c[w] & 0x0F0F0F0Fu, hi = (c[w] >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)       // nibble n of a word holds the word's element n
+                    qh[4 * w + i] = f16x2{q[8 * w + i], q[8 * w + i + 4]};
+            }
+        }
+    }
+
+    // acc[e] += pv24 * 2^-24 * u_e: the same subnormal halves feed a mixed-precision FMA
+    // (fp16 operand widened exactly, fp32 weight and accumulator); pv24 carries the 2^24.
+    __device__ static inline void axpy_codes(const CV &c, float pv24, float (&acc)[EPL])
+    {
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            if (BITS == 8) {
+                const f16x2 a = as_f16x2(c[w] & 0x00FF00FFu), b = as_f16x2((c[w] >> 8) & 0x00FF00FFu);
+                acc[4 * w] = __builtin_fmaf(pv24, (float)a[0], acc[4 * w]);
+                acc[4 * w + 1] = __builtin_fmaf(pv24, (float)b[0], acc[4 * w + 1]);
+                acc[4 * w + 2] = __builtin_fmaf(pv24, (float)a[1], acc[4 * w + 2]);
+                acc[4 * w + 3] = __builtin_fmaf(pv24, (float)b[1], acc[4 * w + 3]);
+            } else {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    acc[w * 8 + 2 * i] = __builtin_fmaf(pv, byte_f32(lo, i), acc[w * 8 + 2 * i]);
-                    acc[w * 8 + 2 * i + 1] = __builtin_fmaf(pv, byte_f32(hi, i), acc[w * 8 + 2 * i + 1]);
+                    const f16x2 a = as_f16x2((c[w] >> (4 * i)) & 0x000F000Fu);
+                    acc[8 * w + i] = __builtin_fmaf(pv24, (float)a[0], acc[8 * w + i]);
+                    acc[8 * w + i + 4] = __builtin_fmaf(pv24, (float)a[1], acc[8 * w + i + 4]);
                 }
             }
         }
@@ -285,8 +321,9 @@ struct TileQ {
     // two ahead (kp2, vp2, kmp2, vmp2) as soon as its last use is issued, so that close to two
     // blocks of loads per wave stay in flight during the arithmetic as well.
     template <bool MASKED, bool REFILL>
-    __device__ inline void update(const float (&q)[EPL], float qsum, float &m, float &l,
-                                  float &aux, float (&acc)[EPL], int row, int tok0, int rem,
+    __device__ inline void update(const f16x2 (&qh)[EPL / 2], float kmul, float qs, float &m,
+                                  float &l, float &aux, float (&acc)[EPL], int row, int tok0,
+                                  int rem,
                                   const char *kp2 = nullptr, const char *vp2 = nullptr,
                                   const float *kmp2 = nullptr, const float *vmp2 = nullptr)
     {
@@ -304,14 +341,14 @@ struct TileQ {
         }
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            float a = dot_codes(k[j], q);
+            float a = dot_codes(k[j], qh);
             if (REFILL) {
                 sched_fence();
                 k[j] = ld_stream_u<CV>(kp2 + j * STRIDE);
                 sched_fence();
             }
             a = row_sum<LPR>(a);
-            a = __builtin_fmaf(a, s[j], z[j] * qsum);
+            a = __builtin_fmaf(a * kmul, s[j], z[j] * qs);
             if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
             s[j] = a;
         }
@@ -331,8 +368,9 @@ struct TileQ {
             float p = fast_exp2(s[j] - mn);
             if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
             l += p;
-            s[j] = p * __shfl(vs, j * RPW + row);
-            aux += BITS == 8 ? -128.0f * s[j] : p * __shfl(vz, j * RPW + row);
+            const float pv = p * __shfl(vs, j * RPW + row);
+            aux += BITS == 8 ? -128.0f * pv : p * __shfl(vz, j * RPW + row);
+            s[j] = pv * 16777216.0f;
         }
         if (REFILL) {
             sched_fence();
@@ -353,7 +391,8 @@ struct TileQ {
 };
 
 template <int BITS>
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(kQWgPerCu, kQWgPerCu)))
+__global__ __launch_bounds__(kThreads)
+__attribute__((amdgpu_waves_per_eu(q_wg_short<BITS>(), q_wg_short<BITS>())))
 void rpartq_partial_kernel(
     const char *__restrict__ k_codes, const char *__restrict__ v_codes,
     const float *__restrict__ k_meta, const float *__restrict__ v_meta,
@@ -417,19 +456,25 @@ void rpartq_partial_kernel(
         const float *kmp = k_meta + (cur.row0 + own) * MW;
         const float *vmp = v_meta + (cur.row0 + own) * MW;
 
-        float qf[EPL], qsum = 0.f;
+        // the query stays fp16 for the dot instruction; its scale (log2 e / sqrt d) and the 2^24
+        // of the subnormal codes are applied to the dot product
+        f16x2 qh[EPL / 2];
+        float qs = 0.f;
         {
             const _Float16 *qp = q + ((int64_t)b * H + h) * D + col * EPL;
+            _Float16 qe[EPL];
 #pragma unroll
             for (int c8 = 0; c8 < EPL / 8; ++c8) {
-                const half8 qh = *reinterpret_cast<const half8 *>(qp + 8 * c8);
+                const half8 v8 = *reinterpret_cast<const half8 *>(qp + 8 * c8);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) qf[8 * c8 + i] = (float)qh[i] * qscale;
+                for (int i = 0; i < 8; ++i) qe[8 * c8 + i] = v8[i];
             }
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) qsum += qf[i];
-            qsum = row_sum<LPR>(qsum);                           // sum of the whole query
+            for (int i = 0; i < EPL; ++i) qs += (float)qe[i];
+            qs = row_sum<LPR>(qs) * qscale;                      // scaled sum of the whole query
+            T::pack_query(qe, qh);
         }
+        const float kmul = qscale * 16777216.0f;
 
         float m = kNegBig, l = 0.f, aux = 0.f, acc[EPL];
 #pragma unroll
@@ -454,10 +499,10 @@ void rpartq_partial_kernel(
                 Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kmt + MSTEP, vmt + MSTEP);
                 sched_fence();
                 do {
-                    A.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
+                    A.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0,
                                                    kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES,
                                                    kmt + 2 * MSTEP, vmt + 2 * MSTEP);
-                    Bf.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
+                    Bf.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0,
                                                     kt + 3 * T::BLK_BYTES, vt + 3 * T::BLK_BYTES,
                                                     kmt + 3 * MSTEP, vmt + 3 * MSTEP);
                     kt += 2 * T::BLK_BYTES;
@@ -472,23 +517,23 @@ void rpartq_partial_kernel(
                 sched_fence();
             }
             if (left == 3) {
-                A.template update<false, true>(qf, qsum, m, l, aux, acc, row, 0, 0,
+                A.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0,
                                                kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES,
                                                kmt + 2 * MSTEP, vmt + 2 * MSTEP);
-                Bf.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
-                A.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                Bf.template update<false, false>(qh, kmul, qs, m, l, aux, acc, row, 0, 0);
+                A.template update<false, false>(qh, kmul, qs, m, l, aux, acc, row, 0, 0);
             } else if (left == 2) {
-                A.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
-                Bf.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                A.template update<false, false>(qh, kmul, qs, m, l, aux, acc, row, 0, 0);
+                Bf.template update<false, false>(qh, kmul, qs, m, l, aux, acc, row, 0, 0);
             } else {
-                A.template update<false, false>(qf, qsum, m, l, aux, acc, row, 0, 0);
+                A.template update<false, false>(qh, kmul, qs, m, l, aux, acc, row, 0, 0);
             }
         }
         if (rem > 0 && wave * T::RPW < rem) {              // this wave has at least one valid row
             const int64_t o = (int64_t)n_blk * T::BLK_BYTES;
             const int64_t so = (int64_t)n_blk * MSTEP;
             A.load_tail(kp + o, vp + o, kmp + so, vmp + so, tok0, own, rem);
-            A.template update<true, false>(qf, qsum, m, l, aux, acc, row, tok0, rem);
+            A.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row, tok0, rem);
         }
 
         // combine the rows of this wave
@@ -633,7 +678,8 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, 64, kQWgPerCu * grid, kQWgPerCu * grid, 0, 1,
+                       desc->chunk_tokens, 64, kQWgLong * grid,
+                       (desc->bits == 4 ? q_wg_short<4>() : q_wg_short<8>()) * grid, kQShortBelow, 1,
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
@@ -655,7 +701,7 @@ int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
     char *ws = (char *)workspace;
     const float qscale = (float)(1.4426950408889634 / 11.313708498984761);
     if (desc->bits == 4)
-        hipLaunchKernelGGL(rpartq_partial_kernel<4>, dim3(kQWgPerCu * grid), dim3(kThreads), 0,
+        hipLaunchKernelGGL(rpartq_partial_kernel<4>, dim3(q_wg_short<4>() * grid), dim3(kThreads), 0,
                            (hipStream_t)stream, (const char *)desc->k_codes,
                            (const char *)desc->v_codes, desc->k_scale, desc->v_scale, desc->seq_off,
                            desc->seq_cap, (const _Float16 *)q, (_Float16 *)out, desc->H,
@@ -663,7 +709,7 @@ int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
                            (const int32_t *)(ws + w.off_order), (float *)(ws + w.off_acc),
                            (float *)(ws + w.off_ml), qscale);
     else
-        hipLaunchKernelGGL(rpartq_partial_kernel<8>, dim3(kQWgPerCu * grid), dim3(kThreads), 0,
+        hipLaunchKernelGGL(rpartq_partial_kernel<8>, dim3(q_wg_short<8>() * grid), dim3(kThreads), 0,
                            (hipStream_t)stream, (const char *)desc->k_codes,
                            (const char *)desc->v_codes, desc->k_scale, desc->v_scale, desc->seq_off,
                            desc->seq_cap, (const _Float16 *)q, (_Float16 *)out, desc->H,

@@ -106,8 +106,8 @@ def test_edge_lengths_all_chunk_sizes(chunk):
     check_qstep(case)
     info = rpart.fd_plan_info(case.ws)
     assert info["total_tokens"] == sum(EDGE_LENS) + len(EDGE_LENS)
-    # the int8 kernel always runs two workgroups per compute unit
-    assert info["grid"] == 2 * torch.cuda.get_device_properties(0).multi_processor_count
+    # the 8-bit kernel runs three workgroups per compute unit on short sequences (mean ~300 here)
+    assert info["grid"] == 3 * torch.cuda.get_device_properties(0).multi_processor_count
 
 
 def test_step_entry_point_many_heads_and_peaked_keys():
