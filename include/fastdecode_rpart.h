@@ -44,6 +44,10 @@ extern "C" {
 #define FD_ST_WINDOW   4    /* windowed cache: n_sink leaves no window row, or seq_seen and
                                seq_lens of a sequence disagree; its append was skipped           */
 
+#define FD_ST_PLAN     8    /* partial/merge found no plan for this batch shape and workspace
+                               size in the workspace (plan missing, or made for another
+                               descriptor); they wrote nothing                                  */
+
 #define FD_SLOT_FREE  (-1)  /* value of seq_lens[b] for a slot that holds no sequence            */
 
 /*
@@ -131,7 +135,9 @@ int fd_rpart_decode(const fd_kv_desc *desc, const void *q, void *out,
 /*
  * The three stages of fd_rpart_decode, exposed so that a harness can time them
  * separately.  They must be enqueued in this order on one stream with the same
- * descriptor and workspace.
+ * descriptor and workspace.  partial and merge check that the workspace holds a plan
+ * made for the same B, H and workspace size; otherwise they set FD_ST_PLAN and write
+ * nothing (their table lookups would not be safe).
  *   plan:    reads seq_lens on the device, cuts every sequence into chunks and
  *            writes the work-item table into the workspace.
  *   partial: streams each chunk's K and V rows once; per (b,h,chunk) produces

@@ -29,7 +29,9 @@ constexpr int kHdrInts = 64;           // 256-byte header
 constexpr float kNegBig = -1.0e30f;    // "no token seen yet" running max (finite: no inf-inf)
 
 // header words
-enum { HDR_NITEMS = 0, HDR_CHUNK = 2, HDR_TOKENS = 3, HDR_GRID = 4 };
+enum { HDR_NITEMS = 0, HDR_CHUNK = 2, HDR_TOKENS = 3, HDR_GRID = 4, HDR_MAGIC = 5, HDR_B = 6,
+       HDR_H = 7, HDR_MAXITEMS = 8 };
+constexpr int32_t kPlanMagic = 0x46445250;
 
 struct WsLayout {
     size_t off_item0;     // int32[B]  first item of sequence b
@@ -337,7 +339,22 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         hdr[HDR_CHUNK] = T;
         hdr[HDR_TOKENS] = total;
         hdr[HDR_GRID] = grid;
+        hdr[HDR_MAGIC] = kPlanMagic;
+        hdr[HDR_B] = B;
+        hdr[HDR_H] = H;
+        hdr[HDR_MAXITEMS] = max_items;
     }
+}
+
+// The streaming and the merge kernels index the caller's slabs with what the plan tables say:
+// they refuse a workspace that does not hold a plan made for this batch shape and workspace
+// size (never planned, or planned for another descriptor), report it and write nothing.
+__device__ inline bool plan_matches(const int32_t *hdr, int B, int H, int max_items, int32_t *status)
+{
+    const bool ok = hdr[HDR_MAGIC] == kPlanMagic && hdr[HDR_B] == B && hdr[HDR_H] == H &&
+                    hdr[HDR_MAXITEMS] == max_items;
+    if (!ok && blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, FD_ST_PLAN);
+    return ok;
 }
 
 // ---------------------------------------------------------------------------
@@ -457,7 +474,7 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
     const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
     const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
     const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
-    float qscale)
+    float qscale, int B, int max_items, int32_t *__restrict__ status)
 {
     using T = Tile<D, NL>;
     constexpr int LPR = T::LPR;
@@ -469,6 +486,7 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
     const int wave = tid >> 6;
     const int row = lane / LPR;
     const int col = lane % LPR;
+    if (!plan_matches(hdr, B, H, max_items, status)) return;
     const int n_units = hdr[HDR_NITEMS] * H;
     const int W = hdr[HDR_GRID], g = blockIdx.x;          // active workgroups, chosen by the planner
     if (g >= W) return;
@@ -631,9 +649,11 @@ template <int D>
 __global__ __launch_bounds__(256) void rpart_merge_kernel(
     const int32_t *__restrict__ item0, const int32_t *__restrict__ nchunk,
     const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-    _Float16 *__restrict__ out, int B, int H)
+    _Float16 *__restrict__ out, int B, int H, const int32_t *__restrict__ hdr, int max_items,
+    int32_t *__restrict__ status)
 {
     constexpr int PER = D / 64;                       // output elements per lane
+    if (!plan_matches(hdr, B, H, max_items, status)) return;
     const int lane = threadIdx.x & 63;
     const int64_t bh = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (bh >= (int64_t)B * H) return;
@@ -845,14 +865,16 @@ int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
                            (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
                            (const _Float16 *)q, (_Float16 *)out, desc->H, (const int32_t *)ws,
                            (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
-                           (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale);
+                           (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale, desc->B,
+                           (int)w.max_items, desc->status);
     else
         hipLaunchKernelGGL((rpart_partial_kernel<64, kTileLoads>), dim3(2 * grid), dim3(kThreads), 0,
                            (hipStream_t)stream, (const char *)desc->k_base,
                            (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
                            (const _Float16 *)q, (_Float16 *)out, desc->H, (const int32_t *)ws,
                            (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
-                           (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale);
+                           (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale, desc->B,
+                           (int)w.max_items, desc->status);
     return launched();
 }
 
@@ -873,12 +895,14 @@ int fd_rpart_merge(const fd_kv_desc *desc, void *out,
         hipLaunchKernelGGL(rpart_merge_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream,
                            (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
                            (const float *)(ws + w.off_acc), (const float *)(ws + w.off_ml),
-                           (_Float16 *)out, desc->B, desc->H);
+                           (_Float16 *)out, desc->B, desc->H, (const int32_t *)ws, (int)w.max_items,
+                           desc->status);
     else
         hipLaunchKernelGGL(rpart_merge_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream,
                            (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
                            (const float *)(ws + w.off_acc), (const float *)(ws + w.off_ml),
-                           (_Float16 *)out, desc->B, desc->H);
+                           (_Float16 *)out, desc->B, desc->H, (const int32_t *)ws, (int)w.max_items,
+                           desc->status);
     return launched();
 }
 

@@ -400,7 +400,7 @@ void rpartq_partial_kernel(
     const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
     const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
     const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
-    float qscale)
+    float qscale, int B, int max_items, int32_t *__restrict__ status)
 {
     using T = TileQ<BITS, q_tile_loads<BITS>()>;
     constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL, RB = T::RB, MW = T::MW, LB = T::LB;
@@ -414,6 +414,7 @@ void rpartq_partial_kernel(
     const int col = lane % LPR;
     const int tok0 = wave * T::RPW + row;                  // this lane's token in a block, load 0
     const int own = T::own_token(lane, wave);              // token whose parameters this lane loads
+    if (!plan_matches(hdr, B, H, max_items, status)) return;
     const int n_units = hdr[HDR_NITEMS] * H;
     const int W = hdr[HDR_GRID], g = blockIdx.x;          // active workgroups, chosen by the planner
     if (g >= W) return;
@@ -707,7 +708,7 @@ int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
                            desc->seq_cap, (const _Float16 *)q, (_Float16 *)out, desc->H,
                            (const int32_t *)ws, (const int4 *)(ws + w.off_items),
                            (const int32_t *)(ws + w.off_order), (float *)(ws + w.off_acc),
-                           (float *)(ws + w.off_ml), qscale);
+                           (float *)(ws + w.off_ml), qscale, desc->B, (int)w.max_items, desc->status);
     else
         hipLaunchKernelGGL(rpartq_partial_kernel<8>, dim3(q_wg_short<8>() * grid), dim3(kThreads), 0,
                            (hipStream_t)stream, (const char *)desc->k_codes,
@@ -715,7 +716,7 @@ int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
                            desc->seq_cap, (const _Float16 *)q, (_Float16 *)out, desc->H,
                            (const int32_t *)ws, (const int4 *)(ws + w.off_items),
                            (const int32_t *)(ws + w.off_order), (float *)(ws + w.off_acc),
-                           (float *)(ws + w.off_ml), qscale);
+                           (float *)(ws + w.off_ml), qscale, desc->B, (int)w.max_items, desc->status);
     return launched();
 }
 
@@ -734,7 +735,8 @@ int fd_rpartq_merge(const fd_kvq_desc *desc, void *out,
     hipLaunchKernelGGL(rpart_merge_kernel<128>, dim3((unsigned)((bh + 3) / 4)), dim3(256), 0,
                        (hipStream_t)stream, (const int32_t *)(ws + w.off_item0),
                        (const int32_t *)(ws + w.off_nchunk), (const float *)(ws + w.off_acc),
-                       (const float *)(ws + w.off_ml), (_Float16 *)out, desc->B, desc->H);
+                       (const float *)(ws + w.off_ml), (_Float16 *)out, desc->B, desc->H,
+                       (const int32_t *)ws, (int)w.max_items, desc->status);
     return launched();
 }
 

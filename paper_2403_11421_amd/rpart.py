@@ -15,7 +15,7 @@ import torch
 from . import build as _build
 
 FD_OK, FD_EINVAL, FD_EWORKSPACE, FD_EHIP = 0, -1, -2, -3
-FD_ST_CAPACITY, FD_ST_BADLEN, FD_ST_WINDOW = 1, 2, 4
+FD_ST_CAPACITY, FD_ST_BADLEN, FD_ST_WINDOW, FD_ST_PLAN = 1, 2, 4, 8
 FD_SLOT_FREE = -1
 
 _vp = ctypes.c_void_p

@@ -219,3 +219,56 @@ def test_invalid_arguments_enqueue_nothing():
         rpart.fd_kv_append(bad, case.k_new, case.v_new)
     torch.cuda.synchronize()
     assert case.cache.seq_lens.cpu().tolist() == [5, 6]
+
+
+def test_partial_and_merge_refuse_a_workspace_without_a_matching_plan():
+    cfg = _cfg("noplan", 3, 2, 128)
+    case = DeviceCase(cfg, [100, 5, 700], seed=31)
+    case.ws.fill_(0x5A)                                       # never planned
+    case.out.fill_(7.0)
+    rpart.fd_rpart_partial(case.cache.desc, case.q, case.out, case.ws)
+    rpart.fd_rpart_merge(case.cache.desc, case.out, case.ws)
+    torch.cuda.synchronize()
+    assert rpart.fd_read_status(case.cache.desc, clear=True) == rpart.FD_ST_PLAN
+    assert bool((case.out == 7.0).all())                      # nothing written
+    # a plan made for another batch shape is refused as well
+    other = DeviceCase(_cfg("other", 2, 2, 128), [50, 60], seed=32)
+    rpart.fd_rpart_plan(other.cache.desc, case.ws)
+    rpart.fd_rpart_partial(case.cache.desc, case.q, case.out, case.ws)
+    torch.cuda.synchronize()
+    assert rpart.fd_read_status(case.cache.desc, clear=True) == rpart.FD_ST_PLAN
+    assert bool((case.out == 7.0).all())
+    # and the regular sequence still works on the same workspace afterwards
+    check_step(case)
+
+
+def test_step_can_be_captured_in_a_hip_graph_and_replayed():
+    """Every entry point only enqueues kernels (no allocation, no synchronisation, no memset
+    node), so a whole step can be captured once and replayed; every replay must give what the
+    eager call gives, with eager work and synchronisations between the replays."""
+    cfg = _cfg("graph", 5, 4, 128)
+    lens = [300, 17, 2049, 0, 999]
+    case = DeviceCase(cfg, lens, seed=41, extra_cap=8)
+    lens0 = case.cache.seq_lens.clone()
+    rpart.fd_rpart_step(case.cache.desc, case.q, case.k_new, case.v_new, case.out, case.ws)
+    torch.cuda.synchronize()
+    eager = case.out.clone()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    case.cache.seq_lens.copy_(lens0)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        g.capture_begin()
+        rpart.fd_rpart_step(case.cache.desc, case.q, case.k_new, case.v_new, case.out, case.ws)
+        g.capture_end()
+    torch.cuda.synchronize()
+    assert case.cache.seq_lens.cpu().tolist() == lens         # capture itself runs nothing
+    for rep in range(4):
+        case.cache.seq_lens.copy_(lens0)
+        case.out.fill_(float("nan"))
+        (case.q.float() * 2).sum().item()                     # unrelated eager work and a sync
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(case.out, eager), rep
+        assert case.cache.seq_lens.cpu().tolist() == [L + 1 for L in lens]
+    assert rpart.fd_read_status(case.cache.desc) == 0
