@@ -246,7 +246,7 @@ def main() -> int:
     args = ap.parse_args()
 
     if args.gpus != 1:
-        print("bench.py: this build runs the R-Part on ONE GPU; sequences are independent, so more "
+        print("bench.py: this library runs the R-Part on ONE GPU; sequences are independent, so more "
               "GPUs would each run this same kernel on their share. Use --gpus 1.", file=sys.stderr)
         return 2
 
