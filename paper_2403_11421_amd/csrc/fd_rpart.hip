@@ -478,8 +478,11 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
 {
     using T = Tile<D, NL>;
     constexpr int LPR = T::LPR;
-    __shared__ float sm_acc[kWaves][D];
-    __shared__ float sm_m[kWaves], sm_l[kWaves];
+    // two sets, used by alternate units: one barrier per unit is then enough (a wave cannot
+    // overwrite a set before every wave has passed the barrier of the unit in between)
+    __shared__ float sm_acc2[2][kWaves][D];
+    __shared__ float sm_m2[2][kWaves], sm_l2[2][kWaves];
+    int set = 0;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -604,6 +607,10 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
             for (int i = 0; i < 8; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], off) * c;
             m = M;
         }
+        float (&sm_acc)[kWaves][D] = sm_acc2[set];
+        float (&sm_m)[kWaves] = sm_m2[set];
+        float (&sm_l)[kWaves] = sm_l2[set];
+        set ^= 1;
         if (lane < LPR) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) sm_acc[wave][lane * 8 + i] = acc[i];
@@ -636,8 +643,7 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
                 }
             }
         }
-        __syncthreads();               // LDS is reused by the next unit
-        cur = nxt;
+        cur = nxt;                     // no second barrier: the next unit uses the other LDS set
     }
 }
 

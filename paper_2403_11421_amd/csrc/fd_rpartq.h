@@ -404,8 +404,10 @@ void rpartq_partial_kernel(
 {
     using T = TileQ<BITS, q_tile_loads<BITS>()>;
     constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL, RB = T::RB, MW = T::MW, LB = T::LB;
-    __shared__ float sm_acc[kWaves][D];
-    __shared__ float sm_m[kWaves], sm_l[kWaves], sm_aux[kWaves];
+    // two sets, used by alternate units, so that one barrier per unit is enough
+    __shared__ float sm_acc2[2][kWaves][D];
+    __shared__ float sm_m2[2][kWaves], sm_l2[2][kWaves], sm_aux2[2][kWaves];
+    int set = 0;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -551,6 +553,11 @@ void rpartq_partial_kernel(
             for (int i = 0; i < EPL; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], off) * c;
             m = M;
         }
+        float (&sm_acc)[kWaves][D] = sm_acc2[set];
+        float (&sm_m)[kWaves] = sm_m2[set];
+        float (&sm_l)[kWaves] = sm_l2[set];
+        float (&sm_aux)[kWaves] = sm_aux2[set];
+        set ^= 1;
         if (lane < LPR) {
 #pragma unroll
             for (int i = 0; i < EPL; ++i) sm_acc[wave][lane * EPL + i] = acc[i];
@@ -582,8 +589,7 @@ void rpartq_partial_kernel(
                 }
             }
         }
-        __syncthreads();               // LDS is reused by the next unit
-        cur = nxt;
+        cur = nxt;                     // no second barrier: the next unit uses the other LDS set
     }
 }
 
