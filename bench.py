@@ -115,7 +115,8 @@ def schedule_mode(args) -> int:
     B, S, F = args.sched_B, args.sched_S, args.sched_F
     n_steps = 2 * S
     for kind in (["batch", "sls"] if args.schedule == "both" else [args.schedule]):
-        r = sls_run.run_schedule(kind, B, S, F, n_steps)
+        r = sls_run.run_schedule(kind, B, S, F, n_steps,
+                                 W_lim=args.sched_wlim if args.sched_wlim > 0 else None)
         ms, loads = r["ms"], r["loads"]
         steady = list(range(S, n_steps))                     # after the cold start
         tok = sum(loads[i] for i in steady)
@@ -124,7 +125,7 @@ def schedule_mode(args) -> int:
         print(json.dumps({
             "metric": "R-Part latency per decode step under a sequence schedule (Section 4.2)",
             "schedule": kind, "B": B, "S": S, "F": F, "M": r["M"], "H": r["H"], "d": r["d"],
-            "steps": n_steps, "steady_steps": len(steady),
+            "steps": n_steps, "steady_steps": len(steady), "W_lim": r.get("W_lim"),
             "peak_load_tokens": max(loads[i] for i in steady),
             "mean_load_tokens": tok / len(steady),
             "peak_ms": srt[-1], "p50_ms": srt[len(srt) // 2], "mean_ms": tms / len(steady),
@@ -225,7 +226,10 @@ def main() -> int:
     ap.add_argument("--cpu-sample", type=int, default=96, help="sequences timed on the CPU oracle (0 = skip)")
     ap.add_argument("--kv", choices=["fp16", "int8", "int4"], default="fp16",
                     help="KV-cache format: fp16 (the headline path) or a quantised cache (Section 5.2)")
-    ap.add_argument("--schedule", choices=["none", "batch", "sls", "both"], default="none",
+    ap.add_argument("--sched-wlim", type=int, default=0,
+                    help="--schedule control: load limit W_lim of Algorithm 1 in cached tokens "
+                         "(0 = Eq. 6's peak plus one step of slack)")
+    ap.add_argument("--schedule", choices=["none", "batch", "sls", "control", "both"], default="none",
                     help="instead of the fixed-length step, run a multi-step decode loop under the "
                          "large-batch or the load-stabilising schedule (Section 4.2) and report the "
                          "per-step R-Part latency")

@@ -25,15 +25,45 @@ def step_vectors(cfg: W.RPartConfig, which: str, step: int, seed: int, device) -
     return (W.normal_from_counter(seed, tid, W._counter(b, step % 16384, h, i)) * cfg.scale).to(torch.float16)
 
 
+def controlled_starts(B: int, S: int, M: int, F: int, W_lim: int, n_steps: int) -> List[int]:
+    """Start steps of micro-batches of M sequences under Algorithm 1's load control.  A
+    micro-batch arrives every F steps (the load-stabilising schedule's interval) and waits in
+    arrival order; at every step the one at the head starts (`AddMicroBatch`) if a group of M
+    slots is free and `GetEarliestStep` allows it, at most one per step.  B // M groups of
+    slots exist; a group is busy for S steps.  Host logic only (the library's scheduler);
+    returns the start step of every micro-batch in order."""
+    assert B % M == 0
+    lc = sched.LoadControl(S, W_lim)
+    free_at = [0] * (B // M)                            # step from which each group is free again
+    starts: List[int] = []
+    waiting = 0
+    for t in range(n_steps):
+        if t % F == 0:
+            waiting += 1
+        lc.retire(t)
+        g = min(range(len(free_at)), key=lambda i: free_at[i])
+        if waiting and free_at[g] <= t and lc.earliest_step(t, M) <= t:
+            lc.add_microbatch(t, M)
+            free_at[g] = t + S
+            starts.append(t)
+            waiting -= 1
+    lc.close()
+    return starts
+
+
 def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 128,
                  seed: int = W.DEFAULT_SEED, device="cuda", timed: bool = True,
-                 on_step: Optional[Callable] = None) -> Dict:
+                 on_step: Optional[Callable] = None, W_lim: Optional[int] = None) -> Dict:
     """kind = "sls": micro-batches of M = B*F/S sequences every F steps (Eq. 5);
-    kind = "batch": all B sequences together, the next batch when they finish.
+    kind = "batch": all B sequences together, the next batch when they finish;
+    kind = "control": micro-batches of M = B*F/S sequences admitted by Algorithm 1 under the
+    load limit W_lim (default: Eq. 6's peak plus one step of slack), see `run_controlled`.
 
     Sequence slots are reused round-robin; a micro-batch's slots are reset when it starts.
     During the cold start only the slots started so far take part (a prefix of the slots).
     on_step(step, cache, q, k_new, v_new, out, n_active) is called after each step (tests)."""
+    if kind == "control":
+        return run_controlled(B, S, F, n_steps, H, d, seed, device, timed, on_step, W_lim)
     assert kind in ("sls", "batch")
     cfg = W.RPartConfig(f"{kind}_B{B}_S{S}_F{F}", B, H, d, "const", 0, 0)
     M = sched.sls_microbatch_size(B, F, S) if kind == "sls" else B
@@ -76,3 +106,59 @@ def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d
     ms = [a.elapsed_time(b) for a, b in events]
     return {"kind": kind, "B": B, "S": S, "F": F, "M": M, "H": H, "d": d, "steps": n_steps,
             "loads": loads, "ms": ms, "final_lens": cache.seq_lens.cpu().tolist()}
+
+
+def run_controlled(B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 128,
+                   seed: int = W.DEFAULT_SEED, device="cuda", timed: bool = True,
+                   on_step: Optional[Callable] = None, W_lim: Optional[int] = None) -> Dict:
+    """Decode loop whose micro-batches are admitted by Algorithm 1.  Slots of finished sequences
+    are released (free slots cost nothing) and reused by the next micro-batch.
+    on_step(step, cache, q, k_new, v_new, out, live_slots) is called after each step (tests)."""
+    cfg = W.RPartConfig(f"control_B{B}_S{S}_F{F}", B, H, d, "const", 0, 0)
+    M = sched.sls_microbatch_size(B, F, S)
+    if W_lim is None:                                   # Eq. 6's peak plus the one step of slack that
+        W_lim = sched.sls_peak_load(M, F, S) + M        # the printed GetEarliestStep needs
+    starts = controlled_starts(B, S, M, F, W_lim, n_steps)
+    dev = torch.device(device)
+    cache = KVCache(B, H, d, [S] * B, dev)
+    out = torch.zeros(B, H, d, dtype=torch.float16, device=dev)
+    ws = cache.workspace(B * S)
+    n_groups = B // M
+    group_ids = [torch.arange(g * M, (g + 1) * M, dtype=torch.int32, device=dev) for g in range(n_groups)]
+    rpart.fd_kv_release(cache.desc)                     # every slot starts free
+    busy_until = [0] * n_groups                         # group g holds a micro-batch until this step
+    live: List[int] = []
+    loads, events = [], []
+    nxt = 0
+    for step in range(n_steps):
+        for g in range(n_groups):                       # finished micro-batches free their slots
+            if busy_until[g] == step and step > 0:
+                rpart.fd_kv_release(cache.desc, group_ids[g])
+                live = [s for s in live if not (g * M <= s < (g + 1) * M)]
+        if nxt < len(starts) and starts[nxt] == step:
+            g = min(range(n_groups), key=lambda i: busy_until[i])
+            assert busy_until[g] <= step
+            rpart.fd_kv_reset(cache.desc, group_ids[g])
+            busy_until[g] = step + S
+            live += list(range(g * M, (g + 1) * M))
+            nxt += 1
+        q = step_vectors(cfg, "q", step, seed, dev)
+        k_new = step_vectors(cfg, "k_new", step, seed, dev)
+        v_new = step_vectors(cfg, "v_new", step, seed, dev)
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+        rpart.fd_rpart_step(cache.desc, q, k_new, v_new, out, ws)
+        if timed:
+            e1.record()
+            events.append((e0, e1))
+        loads.append(sum(step - s0 + 1 for s0 in starts[:nxt] if s0 <= step < s0 + S) * M)
+        if on_step is not None:
+            torch.cuda.synchronize()
+            on_step(step, cache, q, k_new, v_new, out, sorted(live))
+    torch.cuda.synchronize()
+    assert rpart.fd_read_status(cache.desc) == 0
+    ms = [a.elapsed_time(b) for a, b in events]
+    return {"kind": "control", "B": B, "S": S, "F": F, "M": M, "H": H, "d": d, "steps": n_steps,
+            "W_lim": W_lim, "starts": starts, "loads": loads, "ms": ms,
+            "final_lens": cache.seq_lens.cpu().tolist()}

@@ -52,3 +52,46 @@ def test_every_step_matches_the_oracle(kind, B, S, F):
 
     res = sls_run.run_schedule(kind, B, S, F, n_steps, H=H, d=d, timed=False, on_step=on_step)
     assert seen == list(range(n_steps)) and res["loads"] == want_loads
+
+
+@pytest.mark.parametrize("frac", [None, 0.7])
+def test_load_controlled_loop_matches_the_oracle_and_respects_the_limit(frac):
+    """Micro-batches admitted by Algorithm 1 (free slots in between, released and reused): every
+    step's output and lengths against the oracle, and the total cached length never above W_lim."""
+    from paper_2403_11421_amd import rpart, sched
+    B, S, F, H, d = 8, 12, 3, 3, 128
+    M = B * F // S
+    peak = sched.sls_peak_load(M, F, S)
+    W_lim = None if frac is None else int(frac * peak)
+    n_steps = 4 * S
+    hist = {}                                                # slot -> list of (k bits, v bits)
+    seen = []
+
+    def on_step(step, cache, q, k_new, v_new, out, live):
+        lens = cache.seq_lens.cpu().tolist()
+        got = out.cpu().double().numpy()
+        kb, vb, qb = bits(k_new), bits(v_new), bits(q)
+        for s in range(B):
+            if s not in live:
+                assert lens[s] == rpart.FD_SLOT_FREE and np.all(got[s] == 0)
+                hist.pop(s, None)
+                continue
+            if lens[s] == 1:
+                hist[s] = []                                 # the slot was restarted this step
+            hist[s].append((kb[s], vb[s]))
+            K = np.stack([k for k, _ in hist[s]])
+            V = np.stack([v for _, v in hist[s]])
+            assert lens[s] == len(K)
+            want, _, _ = O.rpart_decode([K], [V], np.array([len(K)], np.int32), qb[s:s + 1])
+            assert np.abs(got[s] - want[0]).max() <= 2e-3 * float(np.abs(f64(V)).max())
+        seen.append(sum(l for l in lens if l > 0))
+
+    res = sls_run.run_schedule("control", B, S, F, n_steps, H=H, d=d, timed=False, on_step=on_step,
+                               W_lim=W_lim)
+    limit = res["W_lim"]
+    assert seen == res["loads"] and max(seen) <= limit
+    assert seen == SO.step_loads([(t, M) for t in res["starts"]], S, n_steps)
+    if frac is None:
+        assert res["starts"] == list(range(0, n_steps, F))   # nothing held back
+    else:
+        assert res["starts"] != list(range(0, n_steps, F))[:len(res["starts"])]

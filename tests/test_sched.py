@@ -253,3 +253,43 @@ def test_slots_random_walk_never_duplicates():
             assert 0 <= x < B and x not in held
             held.add(x)
         assert s.in_use() == len(held)
+
+
+# ---------------------------------------------------------------------------
+# Algorithm 1 driving the admission of micro-batches
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("B,S,F", [(6, 6, 2), (12, 12, 3), (32, 16, 4)])
+def test_controlled_starts_at_the_eq6_limit_reproduce_the_fixed_interval_schedule(B, S, F):
+    """With one step of slack over Eq. 6's peak (the printed GetEarliestStep is one step
+    conservative) nothing is ever held back: every micro-batch starts the step it arrives, which
+    is the fixed-interval schedule of Figure 7; at exactly the peak the printed rule delays some."""
+    from paper_2403_11421_amd import sls_run
+    M = B * F // S
+    peak = sched.sls_peak_load(M, F, S)
+    n = 6 * S
+    starts = sls_run.controlled_starts(B, S, M, F, peak + M, n)
+    assert starts == list(range(0, n, F))
+    loads = O.step_loads([(t, M) for t in starts], S, n)
+    assert max(loads) == peak and loads == sched.sls_step_loads(M, F, S, n)
+    late = sls_run.controlled_starts(B, S, M, F, peak, n)
+    assert late != starts and max(O.step_loads([(t, M) for t in late], S, n)) <= peak
+
+
+@pytest.mark.parametrize("frac", [0.6, 0.8])
+def test_controlled_starts_respect_a_tighter_limit(frac):
+    from paper_2403_11421_amd import sls_run
+    B, S, F = 24, 12, 2
+    M = B * F // S
+    W_lim = int(frac * sched.sls_peak_load(M, F, S))
+    n = 8 * S
+    starts = sls_run.controlled_starts(B, S, M, F, W_lim, n)
+    loads = O.step_loads([(t, M) for t in starts], S, n)
+    assert len(starts) > 5 and max(loads) <= W_lim           # the guarded quantity, by brute force
+    assert starts != list(range(0, n, F))[:len(starts)]      # the limit really holds some back
+    # a delayed micro-batch starts at most one step after the brute-force earliest step, given
+    # the micro-batches started before it and its own arrival
+    for i, t in enumerate(starts[1:], 1):
+        before = [(s0, M) for s0 in starts[:i]]
+        arrival = i * F
+        first = O.earliest_start_brute_force(before, S, W_lim, max(arrival, starts[i - 1] + 1), M, t + 2)
+        assert first <= t <= first + 1
