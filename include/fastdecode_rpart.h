@@ -177,7 +177,8 @@ int fd_read_status(const fd_kv_desc *desc, int32_t *host_status, int clear, void
  * Copy what the last fd_rpart_plan on this workspace decided to the host:
  * info[0] = work items (sequence chunks), info[1] = chunk length in tokens,
  * info[2] = total cached tokens, info[3] = workgroups that take part in the streaming
- * kernel (one per compute unit; two when the non-empty sequences average under 512 tokens).
+ * kernel (a multiple of the compute units; larger when more than a tenth of the cached
+ * tokens sits in sequences shorter than 384 tokens).
  * SYNCHRONISES `stream`.
  */
 int fd_plan_info(const void *workspace, int32_t info[4], void *stream);

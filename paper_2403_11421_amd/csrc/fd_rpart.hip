@@ -166,7 +166,7 @@ __global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, int32_t *__restr
 // is the longest-processing-time rule for units that are small against a
 // workgroup's share.
 // ---------------------------------------------------------------------------
-constexpr int kTwoWgBelow = 512;   // fp16 kernel: second workgroup per CU below this mean length
+constexpr int kShortSeq = 384;      // a sequence under this many tokens is latency-bound ("short")
 constexpr int kBuckets = 256;
 
 __device__ inline int block_sum(int v, int *sm)
@@ -231,15 +231,21 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int total = block_sum(mine, sm);
     if (bad) atomicOr(status, FD_ST_BADLEN);
 
-    // One workgroup per CU streams long sequences best (a second one costs 1-2 %); when the
-    // sequences are short a unit is a few blocks and its latency is exposed, and a second
-    // workgroup per CU hides it (+6 % at 256 tokens per sequence).  The caller names the number
-    // of workgroups for long and for short sequences and the mean length that separates them;
-    // the host launches the larger number and workgroups at or beyond `grid` leave at once.
-    int live = 0;
-    for (int b = b0; b < b1; ++b) live += clamp_len(seq_lens[b], seq_cap[b], &bad) > 0;
-    live = block_sum(live, sm);
-    const int grid = (live > 0 && total / live < short_below) ? grid_short : grid_long;
+    // One workgroup per CU streams long sequences best (a second one costs 1-2 %); a sequence of
+    // a few blocks is dominated by its fixed cost, and more workgroups per CU hide that.  Measured
+    // on the fp16 kernel, one against two per CU: 256 tokens each +3.5 %, lengths uniform in
+    // 1..1024 (the load-stabilising schedule's mix) +2.2 %, 512 each -1.1 %, uniform in 1..2048
+    // -0.6 %, exponential with mean 1024 -1.2 %.  What separates them is the share of the
+    // cached tokens that sits in sequences shorter than short_below tokens (100 %, 14 %, 0, 3.5 %,
+    // 5.5 %): above a tenth the larger grid is used.  The host launches the larger number and
+    // workgroups at or beyond `grid` leave at once.
+    int few = 0;
+    for (int b = b0; b < b1; ++b) {
+        const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+        few += L < short_below ? L : 0;
+    }
+    few = block_sum(few, sm);
+    const int grid = (long long)few * 10 > (long long)total ? grid_short : grid_long;
 
     int T;
     if (chunk_req > 0) {
@@ -843,7 +849,7 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, chunk_granule(desc->d), grid, 2 * grid, kTwoWgBelow, 0,
+                       desc->chunk_tokens, chunk_granule(desc->d), grid, 2 * grid, kShortSeq, 0,
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));

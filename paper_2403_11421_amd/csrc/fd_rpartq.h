@@ -174,11 +174,10 @@ __device__ inline V ld_stream_u(const char *p)
 // The 4-bit kernel takes twice the loads of half the size, so as many bytes are in flight.
 template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }   // wave loads per tile
 // Workgroups per compute unit: two when the sequences are long; the 8-bit kernel (164 VGPRs) fits
-// a third one, which pays when the non-empty sequences average under 512 tokens (+5 % at 256
-// tokens per sequence, -5 % at 2048), so the planner switches it on there.
+// a third one, which pays on short sequences (+5 % at 256 tokens per sequence, -5 % at 2048), so
+// the planner switches it on by the same rule as the fp16 kernel's second one.
 constexpr int kQWgLong = 2;
 template <int BITS> constexpr int q_wg_short() { return BITS == 8 ? 3 : 2; }
-constexpr int kQShortBelow = 512;
 
 template <int BITS, int NL_>
 struct TileQ {
@@ -686,7 +685,7 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
                        desc->chunk_tokens, 64, kQWgLong * grid,
-                       (desc->bits == 4 ? q_wg_short<4>() : q_wg_short<8>()) * grid, kQShortBelow, 1,
+                       (desc->bits == 4 ? q_wg_short<4>() : q_wg_short<8>()) * grid, kShortSeq, 1,
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));

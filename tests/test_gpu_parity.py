@@ -74,9 +74,10 @@ def test_minimal_workspace_forces_long_chunks():
     assert e.value.code == rpart.FD_EWORKSPACE
 
 
-def test_active_workgroups_follow_the_mean_length():
-    """Short sequences get two workgroups per compute unit, long ones one; both give the same
-    answer as the oracle (the fp16 kernel is launched with two per CU either way)."""
+def test_active_workgroups_follow_the_share_of_short_sequences():
+    """When more than a tenth of the cached tokens sits in sequences under 384 tokens two
+    workgroups per compute unit take part, otherwise one; both give the same answer as the oracle
+    (the fp16 kernel is launched with two per CU either way)."""
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     cfg = _cfg("grid", 40, 4, 128)
     short = DeviceCase(cfg, [0] * 8 + [100 + 13 * i for i in range(32)], seed=21)
@@ -85,6 +86,9 @@ def test_active_workgroups_follow_the_mean_length():
     long_ = DeviceCase(cfg, [0] * 8 + [600 + 13 * i for i in range(32)], seed=22)
     check_step(long_)
     assert rpart.fd_plan_info(long_.ws)["grid"] == cus
+    mixed = DeviceCase(cfg, [30 * i for i in range(40)], seed=23)       # uniform mix: ~11 % short
+    check_step(mixed)
+    assert rpart.fd_plan_info(mixed.ws)["grid"] == 2 * cus
 
 
 def test_decode_without_append_and_empty_sequences():
