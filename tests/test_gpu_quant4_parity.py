@@ -185,7 +185,7 @@ def test_capacity_overflow_reset_and_bad_bits():
         rpart.fd_kvq_append(bad, case.k_new, case.v_new)
 
 
-@pytest.mark.parametrize("name", ["c2_7b_uniform", "c4_13b_geometric"])
+@pytest.mark.parametrize("name", ["c2_7b_uniform", "c3_7b_ragged", "c4_13b_geometric", "c5_capacity"])
 def test_full_config_sampled_parity(name):
     cfg = W.CONFIGS[name]
     lens = W.seq_lens(cfg)

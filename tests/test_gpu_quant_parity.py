@@ -184,7 +184,7 @@ def test_invalid_arguments():
         rpart.fd_rpartq_decode(case.cache.desc, case.q, case.out, case.ws[:1024])
 
 
-@pytest.mark.parametrize("name", ["c2_7b_uniform", "c4_13b_geometric"])
+@pytest.mark.parametrize("name", ["c2_7b_uniform", "c3_7b_ragged", "c4_13b_geometric", "c5_capacity"])
 def test_full_config_sampled_parity(name):
     cfg = W.CONFIGS[name]
     lens = W.seq_lens(cfg)
