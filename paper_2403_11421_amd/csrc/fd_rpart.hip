@@ -2,8 +2,8 @@
 // split-K streaming attention and log-sum-exp merge, behind the C ABI declared
 // in fastdecode_rpart.h.
 //
-// The path is a batched GEMV (Section 3.1: "still memory-bound"): one flop per
-// KV byte, so everything here is organised around streaming each K and V row
+// The path is a batched matrix-vector product and bound by memory traffic (Section 3.1):
+// one flop per KV byte, so everything here is organised around streaming each K and V row
 // from HBM exactly once with 128-bit coalesced loads; no matrix cores.
 //
 // Lane mapping of the streaming kernel (d = 128): a row of K or V is 256 B =
