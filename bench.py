@@ -26,14 +26,23 @@ TRAFFIC_JSON = os.path.join(ROOT, "profiles", "rpart_partial_hbm_traffic.json")
 KERNEL_SRC = os.path.join(ROOT, "paper_2403_11421_amd", "csrc", "fd_rpart.hip")
 
 
+def kernel_fingerprint():
+    """sha256 of the fp16 kernels' source with comments and white space removed: it changes when
+    the code does, not when a comment is reworded."""
+    import hashlib
+    import re
+    src = open(KERNEL_SRC, encoding="utf-8").read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    src = re.sub(r"//[^\n]*", "", src)
+    return hashlib.sha256(re.sub(r"\s+", "", src).encode()).hexdigest()
+
+
 def counter_traffic(config_name):
     """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc, or None
-    when no counters were taken for this config or the kernel source changed since."""
-    import hashlib
+    when no counters were taken for this config or the kernel code changed since."""
     try:
         rec = json.load(open(TRAFFIC_JSON))
-        sha = hashlib.sha256(open(KERNEL_SRC, "rb").read()).hexdigest()
-        if rec.get("source_sha256") != sha:
+        if rec.get("code_sha256") != kernel_fingerprint():
             return None
         return rec["configs"][config_name]["traffic_bytes"]
     except (OSError, KeyError, ValueError):
