@@ -262,19 +262,28 @@ struct TileQ {
     // with the query left in fp16.  qh holds the query pairs in the order the masks produce.
     __device__ static inline float dot_codes(const CV &c, const f16x2 (&qh)[EPL / 2])
     {
-        float a = 0.f;
+        if (BITS == 8) {
+            float a = 0.f;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) {
-            if (BITS == 8) {
+            for (int w = 0; w < NW; ++w) {
                 a = __builtin_amdgcn_fdot2(as_f16x2(c[w] & 0x00FF00FFu), qh[2 * w], a, false);
                 a = __builtin_amdgcn_fdot2(as_f16x2((c[w] >> 8) & 0x00FF00FFu), qh[2 * w + 1], a, false);
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    a = __builtin_amdgcn_fdot2(as_f16x2((c[w] >> (4 * i)) & 0x000F000Fu), qh[4 * w + i], a, false);
             }
+            return a;
+        } else {
+            // a nibble in bits 4..7 of a half is still inside the mantissa field: it reads as
+            // 16 u * 2^-24, so the odd nibbles need no shift, only their own accumulator
+            float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const unsigned lo = c[w], hi = c[w] >> 8;
+                a0 = __builtin_amdgcn_fdot2(as_f16x2(lo & 0x000F000Fu), qh[4 * w], a0, false);
+                a1 = __builtin_amdgcn_fdot2(as_f16x2(lo & 0x00F000F0u), qh[4 * w + 1], a1, false);
+                a0 = __builtin_amdgcn_fdot2(as_f16x2(hi & 0x000F000Fu), qh[4 * w + 2], a0, false);
+                a1 = __builtin_amdgcn_fdot2(as_f16x2(hi & 0x00F000F0u), qh[4 * w + 3], a1, false);
+            }
+            return __builtin_fmaf(a1, 0.0625f, a0);
         }
-        return a;
     }
 
     // the query pairs for dot_codes from this lane's 16 query elements
@@ -306,12 +315,18 @@ struct TileQ {
                 acc[4 * w + 2] = __builtin_fmaf(pv24, (float)a[1], acc[4 * w + 2]);
                 acc[4 * w + 3] = __builtin_fmaf(pv24, (float)b[1], acc[4 * w + 3]);
             } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const f16x2 a = as_f16x2((c[w] >> (4 * i)) & 0x000F000Fu);
-                    acc[8 * w + i] = __builtin_fmaf(pv24, (float)a[0], acc[8 * w + i]);
-                    acc[8 * w + i + 4] = __builtin_fmaf(pv24, (float)a[1], acc[8 * w + i + 4]);
-                }
+                const float pv20 = pv24 * 0.0625f;                    // for the nibbles read as 16 u
+                const unsigned lo = c[w], hi = c[w] >> 8;
+                const f16x2 n04 = as_f16x2(lo & 0x000F000Fu), n15 = as_f16x2(lo & 0x00F000F0u);
+                const f16x2 n26 = as_f16x2(hi & 0x000F000Fu), n37 = as_f16x2(hi & 0x00F000F0u);
+                acc[8 * w] = __builtin_fmaf(pv24, (float)n04[0], acc[8 * w]);
+                acc[8 * w + 1] = __builtin_fmaf(pv20, (float)n15[0], acc[8 * w + 1]);
+                acc[8 * w + 2] = __builtin_fmaf(pv24, (float)n26[0], acc[8 * w + 2]);
+                acc[8 * w + 3] = __builtin_fmaf(pv20, (float)n37[0], acc[8 * w + 3]);
+                acc[8 * w + 4] = __builtin_fmaf(pv24, (float)n04[1], acc[8 * w + 4]);
+                acc[8 * w + 5] = __builtin_fmaf(pv20, (float)n15[1], acc[8 * w + 5]);
+                acc[8 * w + 6] = __builtin_fmaf(pv24, (float)n26[1], acc[8 * w + 6]);
+                acc[8 * w + 7] = __builtin_fmaf(pv20, (float)n37[1], acc[8 * w + 7]);
             }
         }
     }
@@ -355,11 +370,15 @@ struct TileQ {
 #pragma unroll
         for (int j = 1; j < NL; ++j) tm = fmaxf(tm, s[j]);
         const float mn = fmaxf(m, tm);
-        const float corr = fast_exp2(m - mn);
-        l *= corr;
-        aux *= corr;
+        // after the first few tiles a new maximum is rare: the rescaling is skipped when no row
+        // of the wave has one (a wave-uniform branch without memory operations)
+        if (__any(mn > m)) {
+            const float corr = fast_exp2(m - mn);
+            l *= corr;
+            aux *= corr;
 #pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] *= corr;
+            for (int i = 0; i < EPL; ++i) acc[i] *= corr;
+        }
         // weights times V scales; the weighted zero points go to aux; then the V parameter
         // registers are free as well
 #pragma unroll
