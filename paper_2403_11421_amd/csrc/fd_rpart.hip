@@ -30,7 +30,7 @@ constexpr float kNegBig = -1.0e30f;    // "no token seen yet" running max (finit
 
 // header words
 enum { HDR_NITEMS = 0, HDR_CHUNK = 2, HDR_TOKENS = 3, HDR_GRID = 4, HDR_MAGIC = 5, HDR_B = 6,
-       HDR_H = 7, HDR_MAXITEMS = 8 };
+       HDR_H = 7, HDR_MAXITEMS = 8, HDR_WAVE_UNITS = 9 };
 constexpr int32_t kPlanMagic = 0x46445250;
 
 struct WsLayout {
@@ -215,7 +215,7 @@ __device__ inline int length_bucket(int len, int T)
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
     int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid_long, int grid_short,
-    int short_below, int hashed, int max_items,
+    int short_below, int hashed, int wave_units, int max_items,
     int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
     int4 *__restrict__ items, int32_t *__restrict__ order)
 {
@@ -245,13 +245,18 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         few += L < short_below ? L : 0;
     }
     few = block_sum(few, sm);
-    const int grid = (long long)few * 10 > (long long)total ? grid_short : grid_long;
+    const bool many_short = (long long)few * 10 > (long long)total;
+    const int grid = many_short ? grid_short : grid_long;
+    // wave_units: 0 = the workgroup's waves always share a unit, 1 = each wave takes units of its
+    // own when the batch holds many short sequences, 2 = always
+    const int wave_now = wave_units == 2 || (wave_units == 1 && many_short);
 
     int T;
     if (chunk_req > 0) {
         T = chunk_req;
     } else {
-        const long long share = (long long)total * H / grid;    // token-heads per workgroup
+        // token-heads per worker: a workgroup, or a wave when each wave takes units of its own
+        const long long share = (long long)total * H / ((long long)grid * (wave_now ? kWaves : 1));
         long long t = share / 16;
         T = (int)(t < 128 ? 128 : (t > (1 << 28) ? (1 << 28) : t));
     }
@@ -349,6 +354,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         hdr[HDR_B] = B;
         hdr[HDR_H] = H;
         hdr[HDR_MAXITEMS] = max_items;
+        hdr[HDR_WAVE_UNITS] = wave_now;
     }
 }
 
@@ -849,7 +855,7 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, chunk_granule(desc->d), grid, 2 * grid, kShortSeq, 0,
+                       desc->chunk_tokens, chunk_granule(desc->d), grid, 2 * grid, kShortSeq, 0, 0,
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));

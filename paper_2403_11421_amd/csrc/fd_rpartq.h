@@ -178,8 +178,16 @@ template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }  
 // the planner switches it on by the same rule as the fp16 kernel's second one.
 constexpr int kQWgLong = 2;
 template <int BITS> constexpr int q_wg_short() { return BITS == 8 ? 3 : 2; }
+// Units per wave instead of per workgroup when the batch holds many short sequences (the
+// planner's wave_units argument).  Measured against workgroup units with the best residency:
+// 4 bit +30 % at 256 tokens per sequence, +22 % on lengths uniform in 1..1024, but -9 % at 2048
+// tokens; 8 bit +3 %, -4 %, -10 %: only the 4-bit kernel, whose unit epilogue is dear against its
+// short streaming time, uses it.
+template <int BITS> constexpr int q_wave_units() { return BITS == 4 ? 1 : 0; }
 
-template <int BITS, int NL_>
+// WPU = waves that share a unit: kWaves (the workgroup streams one (sequence, head) together,
+// its waves interleaved at one wave load) or 1 (every wave streams a unit of its own).
+template <int BITS, int NL_, int WPU>
 struct TileQ {
     using F = QFmt<BITS>;
     static constexpr int D = F::D;
@@ -191,8 +199,8 @@ struct TileQ {
     static constexpr int LPR = 8;                        // lanes per row
     static constexpr int RPW = 8;                        // rows (tokens) per wave load
     static constexpr int EPL = D / LPR;                  // elements per lane
-    static constexpr int STRIDE = kWaves * 64 * LB;      // bytes between a wave's consecutive loads
-    static constexpr int TSTEP = kWaves * RPW;           // tokens between a wave's consecutive loads
+    static constexpr int STRIDE = WPU * 64 * LB;         // bytes between a wave's consecutive loads
+    static constexpr int TSTEP = WPU * RPW;              // tokens between a wave's consecutive loads
     static constexpr int BLK_TOK = NL * TSTEP;           // tokens per workgroup block
     static constexpr int BLK_BYTES = NL * STRIDE;        // bytes of K (or V) codes per block
     static_assert(NL * RPW <= 64, "one lane per token of the tile for the row parameters");
@@ -203,7 +211,7 @@ struct TileQ {
     // token (inside a block) whose parameters lane `lane` of wave `wave` loads
     __device__ static inline int own_token(int lane, int wave)
     {
-        return (((lane / RPW) % NL) * kWaves + wave) * RPW + (lane % RPW);
+        return (((lane / RPW) % NL) * WPU + wave) * RPW + (lane % RPW);
     }
 
     __device__ inline void load_kmeta(const float *p)
@@ -408,35 +416,34 @@ struct TileQ {
     }
 };
 
-template <int BITS>
-__global__ __launch_bounds__(kThreads)
-__attribute__((amdgpu_waves_per_eu(q_wg_short<BITS>(), q_wg_short<BITS>())))
-void rpartq_partial_kernel(
+template <int BITS, int WPU>
+__device__ __forceinline__ void rpartq_body(
     const char *__restrict__ k_codes, const char *__restrict__ v_codes,
     const float *__restrict__ k_meta, const float *__restrict__ v_meta,
     const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
     const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
     const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
     const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
-    float qscale, int B, int max_items, int32_t *__restrict__ status)
+    float qscale)
 {
-    using T = TileQ<BITS, q_tile_loads<BITS>()>;
+    using T = TileQ<BITS, q_tile_loads<BITS>(), WPU>;
     constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL, RB = T::RB, MW = T::MW, LB = T::LB;
     // two sets, used by alternate units, so that one barrier per unit is enough
     __shared__ float sm_acc2[2][kWaves][D];
     __shared__ float sm_m2[2][kWaves], sm_l2[2][kWaves], sm_aux2[2][kWaves];
     int set = 0;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = WPU == 1 ? 0 : (int)(threadIdx.x >> 6);     // position among the unit's waves
+    const int tid = wave * 64 + lane;                            // thread index among them
     const int row = lane / LPR;
     const int col = lane % LPR;
     const int tok0 = wave * T::RPW + row;                  // this lane's token in a block, load 0
     const int own = T::own_token(lane, wave);              // token whose parameters this lane loads
-    if (!plan_matches(hdr, B, H, max_items, status)) return;
     const int n_units = hdr[HDR_NITEMS] * H;
-    const int W = hdr[HDR_GRID], g = blockIdx.x;          // active workgroups, chosen by the planner
+    // workers (workgroups, or single waves) that the planner's grid amounts to, and this one
+    const int W = hdr[HDR_GRID] * (kWaves / WPU);
+    const int g = WPU == 1 ? (int)(blockIdx.x * kWaves + (threadIdx.x >> 6)) : (int)blockIdx.x;
     if (g >= W) return;
 
     // same static schedule as the fp16 kernel
@@ -571,44 +578,100 @@ void rpartq_partial_kernel(
             for (int i = 0; i < EPL; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], off) * c;
             m = M;
         }
-        float (&sm_acc)[kWaves][D] = sm_acc2[set];
-        float (&sm_m)[kWaves] = sm_m2[set];
-        float (&sm_l)[kWaves] = sm_l2[set];
-        float (&sm_aux)[kWaves] = sm_aux2[set];
-        set ^= 1;
-        if (lane < LPR) {
+        if constexpr (WPU == 1) {
+            // the wave owns the unit: every lane now holds the state of all rows for its 16
+            // elements; the 8 lanes of row 0 write them
+            if (lane < LPR) {
+                if (cur.nch == 1) {
+                    _Float16 o16[EPL];
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) sm_acc[wave][lane * EPL + i] = acc[i];
-        }
-        if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; sm_aux[wave] = aux; }
-        __syncthreads();
-
-        if (tid < D) {
-            float M = sm_m[0];
+                    for (int i = 0; i < EPL; ++i) o16[i] = (_Float16)((acc[i] + aux) / l);
+                    _Float16 *op = out + ((int64_t)b * H + h) * D + lane * EPL;
 #pragma unroll
-            for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
-            float L = 0.f, X = 0.f, o = 0.f;
+                    for (int c8 = 0; c8 < EPL / 8; ++c8) {
+                        half8 v8;
 #pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                const float a = fast_exp2(sm_m[w] - M);
-                L += a * sm_l[w];
-                X += a * sm_aux[w];
-                o += a * sm_acc[w][tid];
+                        for (int i = 0; i < 8; ++i) v8[i] = o16[8 * c8 + i];
+                        __builtin_nontemporal_store(v8, reinterpret_cast<half8 *>(op + 8 * c8));
+                    }
+                } else {
+                    const int64_t rec = (int64_t)cur.item * H + h;
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i)
+                        __builtin_nontemporal_store(acc[i] + aux, &part_acc[rec * D + lane * EPL + i]);
+                    if (lane == 0) {
+                        __builtin_nontemporal_store(m, &part_ml[rec * 2]);
+                        __builtin_nontemporal_store(l, &part_ml[rec * 2 + 1]);
+                    }
+                }
             }
-            o += X;                                          // the weighted zero points
-            if (cur.nch == 1) {
-                __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
-            } else {
-                const int64_t rec = (int64_t)cur.item * H + h;
-                __builtin_nontemporal_store(o, &part_acc[rec * D + tid]);
-                if (tid == 0) {
-                    __builtin_nontemporal_store(M, &part_ml[rec * 2]);
-                    __builtin_nontemporal_store(L, &part_ml[rec * 2 + 1]);
+        } else {
+            float (&sm_acc)[kWaves][D] = sm_acc2[set];
+            float (&sm_m)[kWaves] = sm_m2[set];
+            float (&sm_l)[kWaves] = sm_l2[set];
+            float (&sm_aux)[kWaves] = sm_aux2[set];
+            set ^= 1;
+            if (lane < LPR) {
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) sm_acc[wave][lane * EPL + i] = acc[i];
+            }
+            if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; sm_aux[wave] = aux; }
+            __syncthreads();
+
+            if (tid < D) {
+                float M = sm_m[0];
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
+                float L = 0.f, X = 0.f, o = 0.f;
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    const float a = fast_exp2(sm_m[w] - M);
+                    L += a * sm_l[w];
+                    X += a * sm_aux[w];
+                    o += a * sm_acc[w][tid];
+                }
+                o += X;                                          // the weighted zero points
+                if (cur.nch == 1) {
+                    __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
+                } else {
+                    const int64_t rec = (int64_t)cur.item * H + h;
+                    __builtin_nontemporal_store(o, &part_acc[rec * D + tid]);
+                    if (tid == 0) {
+                        __builtin_nontemporal_store(M, &part_ml[rec * 2]);
+                        __builtin_nontemporal_store(L, &part_ml[rec * 2 + 1]);
+                    }
                 }
             }
         }
         cur = nxt;                     // no second barrier: the next unit uses the other LDS set
     }
+}
+
+// One kernel, two bodies: the planner decides per launch whether a workgroup's four waves share
+// a unit or take one each (short sequences: a unit's fixed cost, the epilogue with its barrier
+// and cross-wave combine, is then spread over four times as many blocks per wave).
+template <int BITS>
+__global__ __launch_bounds__(kThreads)
+__attribute__((amdgpu_waves_per_eu(q_wg_short<BITS>(), q_wg_short<BITS>())))
+void rpartq_partial_kernel(
+    const char *__restrict__ k_codes, const char *__restrict__ v_codes,
+    const float *__restrict__ k_meta, const float *__restrict__ v_meta,
+    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
+    const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
+    const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
+    const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
+    float qscale, int B, int max_items, int32_t *__restrict__ status)
+{
+    if (!plan_matches(hdr, B, H, max_items, status)) return;
+    if constexpr (q_wave_units<BITS>() != 0) {
+        if (hdr[HDR_WAVE_UNITS]) {
+            rpartq_body<BITS, 1>(k_codes, v_codes, k_meta, v_meta, seq_off, seq_cap, q, out, H, hdr,
+                                 items, order, part_acc, part_ml, qscale);
+            return;
+        }
+    }
+    rpartq_body<BITS, kWaves>(k_codes, v_codes, k_meta, v_meta, seq_off, seq_cap, q, out, H, hdr,
+                              items, order, part_acc, part_ml, qscale);
 }
 
 // ---------------------------------------------------------------------------
@@ -705,6 +768,7 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
                        desc->chunk_tokens, 64, kQWgLong * grid,
                        (desc->bits == 4 ? q_wg_short<4>() : q_wg_short<8>()) * grid, kShortSeq, 1,
+                       desc->bits == 4 ? q_wave_units<4>() : q_wave_units<8>(),
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));

@@ -112,6 +112,19 @@ def test_edge_lengths_all_chunk_sizes(chunk):
     assert rpart.fd_plan_info(case.ws)["total_tokens"] == sum(EDGE_LENS) + len(EDGE_LENS)
 
 
+def test_short_batches_run_one_unit_per_wave_and_long_ones_per_workgroup():
+    """The planner switches the 4-bit kernel to wave units when more than a tenth of the cached
+    tokens sits in sequences under 384 tokens (word 9 of the plan header); both modes, with and
+    without split sequences, must match the oracle."""
+    cfg = _cfg("q4modes", 24, 3)
+    short = Q4Case(cfg, [10 * i for i in range(23)] + [3000], seed=31, chunk_tokens=256)
+    check_q4step(short)
+    assert int(short.ws[:256].view(torch.int32)[9]) == 1
+    long_ = Q4Case(cfg, [500 + 40 * i for i in range(23)] + [3000], seed=32, chunk_tokens=256)
+    check_q4step(long_)
+    assert int(long_.ws[:256].view(torch.int32)[9]) == 0
+
+
 def test_step_entry_point_many_heads_and_peaked_keys():
     cfg = W.RPartConfig("q4step", 6, 40, 128, "const", 0, 0, peaked_keys=True)
     case = Q4Case(cfg, [300, 17, 2049, 64, 999, 4100], seed=5)
