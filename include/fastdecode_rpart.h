@@ -95,6 +95,10 @@ typedef struct fd_kv_desc {
 /* Library version (major*10000 + minor*100 + patch). */
 int fd_version(void);
 
+/* sizeof(fd_kv_desc) (which = 0) or sizeof(fd_kvq_desc) (which = 1, declared below) as this
+ * library was built: lets a foreign-language binding check its mirror of the struct. */
+size_t fd_desc_size(int which);
+
 /* Static text for an FD_* return code. */
 const char *fd_strerror(int code);
 

@@ -784,6 +784,11 @@ extern "C" {
 
 int fd_version(void) { return kVersion; }
 
+size_t fd_desc_size(int which)
+{
+    return which == 0 ? sizeof(fd_kv_desc) : which == 1 ? sizeof(fd_kvq_desc) : 0;
+}
+
 const char *fd_strerror(int code)
 {
     switch (code) {

@@ -65,6 +65,10 @@ def load() -> ctypes.CDLL:
     P = ctypes.POINTER(fd_kv_desc)
     lib.fd_version.restype = ctypes.c_int
     lib.fd_version.argtypes = []
+    lib.fd_desc_size.restype = ctypes.c_size_t
+    lib.fd_desc_size.argtypes = [ctypes.c_int]
+    if lib.fd_desc_size(0) != ctypes.sizeof(fd_kv_desc) or lib.fd_desc_size(1) != ctypes.sizeof(fd_kvq_desc):
+        raise RuntimeError("libfd_rpart.so was built from a different fastdecode_rpart.h than this binding mirrors")
     lib.fd_strerror.restype = ctypes.c_char_p
     lib.fd_strerror.argtypes = [ctypes.c_int]
     lib.fd_workspace_bytes.restype = ctypes.c_size_t
@@ -110,7 +114,7 @@ def load() -> ctypes.CDLL:
     return lib
 
 
-EXPORTS = ("fd_version", "fd_strerror", "fd_workspace_bytes", "fd_kv_append", "fd_rpart_decode",
+EXPORTS = ("fd_version", "fd_desc_size", "fd_strerror", "fd_workspace_bytes", "fd_kv_append", "fd_rpart_decode",
            "fd_rpart_plan", "fd_rpart_partial", "fd_rpart_merge", "fd_rpart_step", "fd_kv_reset",
            "fd_read_status", "fd_plan_info", "fd_hbm_read_probe",
            "fd_kvq_append", "fd_kvq_reset", "fd_rpartq_plan", "fd_rpartq_partial", "fd_rpartq_merge",

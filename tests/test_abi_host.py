@@ -34,6 +34,16 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(lib, n), n
 
 
+def test_binding_mirrors_the_descriptor_structs():
+    lib = rpart.load()
+    assert lib.fd_desc_size(0) == ctypes.sizeof(rpart.fd_kv_desc) == 80
+    assert lib.fd_desc_size(1) == ctypes.sizeof(rpart.fd_kvq_desc) == 96
+    assert lib.fd_desc_size(2) == 0
+    # field offsets the kernels rely on (pointers first, then the 32-bit fields)
+    assert rpart.fd_kv_desc.B.offset == 48 and rpart.fd_kv_desc.seq_seen.offset == 64
+    assert rpart.fd_kvq_desc.B.offset == 64 and rpart.fd_kvq_desc.bits.offset == 92
+
+
 def test_version_and_strerror():
     assert rpart.version() >= 100
     assert rpart.strerror(rpart.FD_OK) == "ok"
