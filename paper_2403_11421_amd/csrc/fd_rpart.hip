@@ -212,6 +212,18 @@ __device__ inline int length_bucket(int len, int T)
     return k < 0 ? 0 : (k >= kBuckets ? kBuckets - 1 : k);
 }
 
+// chunk k of a sequence of L tokens cut into n chunks: tokens [t0, t1)
+__device__ inline void chunk_span(int L, int n, int granule, int k, int *t0, int *t1)
+{
+    int len = (L + n - 1) / n;
+    len = (len + granule - 1) / granule * granule;      // <= the chunk length T, so (n-1)*len < L
+    *t0 = k * len;
+    *t1 = min(L, *t0 + len);
+}
+
+constexpr int kBigChunks = 16;      // a sequence cut into more chunks than this ...
+constexpr int kBigMax = 128;        // ... goes on a list of at most this many entries
+
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
     int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid_long, int grid_short,
@@ -221,6 +233,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
 {
     __shared__ int sm[kPlanThreads];
     __shared__ int hist[kBuckets];
+    __shared__ int4 big[kBigMax];
+    __shared__ int nbig, big_nmax;
     const int tid = threadIdx.x;
     const int per = (B + kPlanThreads - 1) / kPlanThreads;   // sequences per thread (contiguous)
     const int b0 = tid * per;
@@ -275,12 +289,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     }
 
     // exclusive scan of per-thread item counts
-    int c = 0;
+    int c = 0, c_big = 0;
     for (int b = b0; b < b1; ++b) {
         const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
-        c += (L + T - 1) / T;
+        const int n = (L + T - 1) / T;
+        c += n;
+        c_big += n > kBigChunks;
     }
+    // A sequence cut into many chunks (one that has the device almost to itself) is written out
+    // by the whole workgroup, a chunk per thread, instead of by the one thread that owns it:
+    // 128 chunks walked by one thread took 46 us.  The list is used only when it holds them all.
+    const bool use_list = block_sum(c_big, sm) <= kBigMax;
     if (tid < kBuckets) hist[tid] = 0;
+    if (tid == 0) { nbig = 0; big_nmax = 0; }
     const int first = block_exclusive_scan(c, sm);      // its barriers also publish hist = 0
     int pos = first;
     for (int b = b0; b < b1; ++b) {
@@ -288,12 +309,13 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         const int n = (L + T - 1) / T;
         item0[b] = pos;
         nchunk[b] = n;
-        if (n > 0) {
-            int len = (L + n - 1) / n;
-            len = (len + granule - 1) / granule * granule;      // <= T, so (n-1)*len < L
+        if (use_list && n > kBigChunks) {
+            big[atomicAdd(&nbig, 1)] = make_int4(b, L, n, pos);
+            atomicMax(&big_nmax, n);
+        } else {
             for (int k = 0; k < n; ++k) {
-                const int t0 = k * len;
-                const int t1 = min(L, t0 + len);
+                int t0, t1;
+                chunk_span(L, n, granule, k, &t0, &t1);
                 if (pos + k < max_items) {
                     items[pos + k] = make_int4(b, t0, t1, n);
                     atomicAdd(&hist[length_bucket(t1 - t0, T)], 1);
@@ -301,6 +323,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
             }
         }
         pos += n;
+    }
+    __syncthreads();
+    const int n_listed = nbig;
+    for (int s = 0; s < n_listed; ++s) {
+        const int4 e = big[s];                          // (b, L, n, first item)
+        for (int k = tid; k < e.z; k += kPlanThreads) {
+            int t0, t1;
+            chunk_span(e.y, e.z, granule, k, &t0, &t1);
+            if (e.w + k < max_items) {
+                items[e.w + k] = make_int4(e.x, t0, t1, e.z);
+                atomicAdd(&hist[length_bucket(t1 - t0, T)], 1);
+            }
+        }
     }
     __syncthreads();
     // bucket starts = exclusive scan of the 256 counters, then scatter
@@ -333,15 +368,29 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         }
         const int n = nchunk[b];
         const int base = item0[b];
-        if (n > 0) {
+        if (n > 0 && !(use_list && n > kBigChunks)) {
             const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
-            int len = (L + n - 1) / n;
-            len = (len + granule - 1) / granule * granule;
             for (int k = 0; k < n; ++k) {
-                const int t0 = k * len;
-                const int t1 = min(L, t0 + len);
+                int t0, t1;
+                chunk_span(L, n, granule, k, &t0, &t1);
                 if (base + k < max_items)
                     order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = base + k;
+            }
+        }
+    }
+    // listed sequences chunk-major (chunk 0 of each, chunk 1 of each, ...), the order in which
+    // their owner threads, side by side in one wave, would have issued the atomics: units that
+    // run at the same time then belong to different sequences where there are several
+    if (n_listed > 0) {
+        const long long k_end = (long long)big_nmax * n_listed;
+        for (long long i = tid; i < k_end; i += kPlanThreads) {
+            const int k = (int)(i / n_listed);
+            const int4 e = big[(int)(i - (long long)k * n_listed)];
+            if (k < e.z) {
+                int t0, t1;
+                chunk_span(e.y, e.z, granule, k, &t0, &t1);
+                if (e.w + k < max_items)
+                    order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = e.w + k;
             }
         }
     }
@@ -662,7 +711,15 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
 // ---------------------------------------------------------------------------
 // Log-sum-exp merge of a sequence's chunk states; one wave per (b,h).
 // States are in the base-2 exponent domain used by the streaming kernel.
+//
+// A sequence that has the device to itself is cut into over a hundred chunks per head, so the
+// wave works on many chunk states at once: maxima and sums of exponentials one chunk per lane,
+// the weighted value sums four records per load (16 lanes x 128-bit per record) with sixteen
+// records in flight, and a cross-lane sum over the four groups at the end.
 // ---------------------------------------------------------------------------
+typedef float fvec4 __attribute__((ext_vector_type(4)));
+typedef _Float16 hvec4 __attribute__((ext_vector_type(4)));
+
 template <int D>
 __global__ __launch_bounds__(256) void rpart_merge_kernel(
     const int32_t *__restrict__ item0, const int32_t *__restrict__ nchunk,
@@ -670,36 +727,85 @@ __global__ __launch_bounds__(256) void rpart_merge_kernel(
     _Float16 *__restrict__ out, int B, int H, const int32_t *__restrict__ hdr, int max_items,
     int32_t *__restrict__ status)
 {
-    constexpr int PER = D / 64;                       // output elements per lane
+    constexpr int NV = D / 64;                        // 128-bit pieces of a record per lane
     if (!plan_matches(hdr, B, H, max_items, status)) return;
     const int lane = threadIdx.x & 63;
+    const int t = lane & 15, g = lane >> 4;           // piece within the record, record within the load
     const int64_t bh = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (bh >= (int64_t)B * H) return;
     const int b = (int)(bh / H);
     const int h = (int)(bh - (int64_t)b * H);
     const int n = nchunk[b];
     if (n == 1) return;                               // written by the streaming kernel
-    _Float16 *o = out + bh * D + lane * PER;
+    _Float16 *o = out + bh * D + t * 4;               // lanes of group 0 write elements v*64 + t*4 ..
     if (n == 0) {
+        if (g == 0) {
 #pragma unroll
-        for (int i = 0; i < PER; ++i) o[i] = (_Float16)0.f;
+            for (int v = 0; v < NV; ++v) *(hvec4 *)(o + v * 64) = hvec4{0, 0, 0, 0};
+        }
         return;
     }
     const int64_t rec0 = (int64_t)item0[b] * H + h;   // chunk c of this (b,h) is record rec0 + c*H
     float M = kNegBig;
-    for (int c = 0; c < n; ++c) M = fmaxf(M, part_ml[(rec0 + (int64_t)c * H) * 2]);
-    float L = 0.f, acc[PER];
-#pragma unroll
-    for (int i = 0; i < PER; ++i) acc[i] = 0.f;
-    for (int c = 0; c < n; ++c) {
-        const int64_t rec = rec0 + (int64_t)c * H;
-        const float w = fast_exp2(part_ml[rec * 2] - M);
-        L += w * part_ml[rec * 2 + 1];
-#pragma unroll
-        for (int i = 0; i < PER; ++i) acc[i] += w * part_acc[rec * D + lane * PER + i];
+    for (int c0 = 0; c0 < n; c0 += 64) {
+        const int c = c0 + lane;
+        if (c < n) M = fmaxf(M, part_ml[(rec0 + (int64_t)c * H) * 2]);
     }
 #pragma unroll
-    for (int i = 0; i < PER; ++i) o[i] = (_Float16)(acc[i] / L);
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    float L = 0.f;
+    fvec4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) acc[v] = fvec4{0.f, 0.f, 0.f, 0.f};
+    const int64_t step = (int64_t)H * (D / 4);         // record stride of one chunk, in 128-bit pieces
+    for (int c0 = 0; c0 < n; c0 += 64) {
+        const int c = c0 + lane;
+        float w = 0.f;
+        if (c < n) {
+            const int64_t rec = rec0 + (int64_t)c * H;
+            w = fast_exp2(part_ml[rec * 2] - M);
+            L += w * part_ml[rec * 2 + 1];
+        }
+        const int nb = min(64, n - c0);
+        const fvec4 *pa = (const fvec4 *)(part_acc + (rec0 + (int64_t)c0 * H) * D) + t;
+        for (int j0 = 0; j0 < nb; j0 += 16) {
+            fvec4 x[4][NV];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = min(j0 + u * 4 + g, nb - 1);   // past the end: a valid record, weight 0
+#pragma unroll
+                for (int v = 0; v < NV; ++v) x[u][v] = pa[j * step + v * 16];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u * 4 + g;
+                float wj = __shfl(w, j & 63);
+                wj = j < nb ? wj : 0.f;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) acc[v] += wj * x[u][v];
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off);
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float a = acc[v][i];
+            a += __shfl_xor(a, 16);
+            a += __shfl_xor(a, 32);
+            acc[v][i] = a;
+        }
+    if (g == 0) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            hvec4 r;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = (_Float16)(acc[v][i] / L);
+            *(hvec4 *)(o + v * 64) = r;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------

@@ -74,6 +74,24 @@ def test_minimal_workspace_forces_long_chunks():
     assert e.value.code == rpart.FD_EWORKSPACE
 
 
+def test_sequences_cut_into_many_chunks():
+    """A sequence cut into more than 16 chunks is laid out by the planner's whole workgroup and
+    merged 64 chunk states at a time: one sequence of 94 chunks next to short ones (64 d = 64
+    chunks is the other width), 137 chunks over three merge batches, and more many-chunk
+    sequences than the planner's list holds (it then falls back to one thread per sequence)."""
+    for d, lens in ((128, [3000, 5, 0, 700, 33]), (64, [4090, 64, 1]), (128, [4380, 100])):
+        granule = 32 if d == 128 else 64
+        case = DeviceCase(_cfg("manychunks", len(lens), 2, d), lens, seed=41, chunk_tokens=granule)
+        check_step(case)
+        info = rpart.fd_plan_info(case.ws)
+        assert info["chunk_tokens"] == granule
+        assert info["items"] == sum(math.ceil((L + 1) / granule) for L in lens)
+    lens = [560 + (i % 7) for i in range(131)]
+    case = DeviceCase(_cfg("manybig", len(lens), 1, 128), lens, seed=42, chunk_tokens=32)
+    check_step(case)
+    assert rpart.fd_plan_info(case.ws)["items"] == sum(math.ceil((L + 1) / 32) for L in lens)
+
+
 def test_active_workgroups_follow_the_share_of_short_sequences():
     """When more than a tenth of the cached tokens sits in sequences under 384 tokens two
     workgroups per compute unit take part, otherwise one; both give the same answer as the oracle
