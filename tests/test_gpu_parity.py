@@ -92,6 +92,16 @@ def test_sequences_cut_into_many_chunks():
     assert rpart.fd_plan_info(case.ws)["items"] == sum(math.ceil((L + 1) / 32) for L in lens)
 
 
+def test_more_sequences_than_planner_threads():
+    """3001 sequences (three per planner thread, not a power of two), most of them a few tokens
+    long or empty, two long ones among them."""
+    lens = [(7 * i) % 23 for i in range(3001)]
+    lens[1234], lens[3000] = 1500, 700
+    case = DeviceCase(_cfg("manyseq", len(lens), 1, 128), lens, seed=43)
+    check_step(case)
+    assert rpart.fd_plan_info(case.ws)["total_tokens"] == sum(lens) + len(lens)
+
+
 def test_active_workgroups_follow_the_share_of_short_sequences():
     """When more than a tenth of the cached tokens sits in sequences under 384 tokens two
     workgroups per compute unit take part, otherwise one; both give the same answer as the oracle

@@ -125,6 +125,16 @@ def test_short_batches_run_one_unit_per_wave_and_long_ones_per_workgroup():
     assert int(long_.ws[:256].view(torch.int32)[9]) == 0
 
 
+def test_more_sequences_than_planner_threads():
+    """2001 sequences, nearly all short: wave units, scrambled visiting order, three waves of
+    planner threads' worth of sequences."""
+    lens = [(7 * i) % 23 for i in range(2001)]
+    lens[1234], lens[2000] = 1500, 700
+    case = Q4Case(_cfg("q4manyseq", len(lens), 1), lens, seed=43)
+    check_q4step(case)
+    assert rpart.fd_plan_info(case.ws)["total_tokens"] == sum(lens) + len(lens)
+
+
 def test_step_entry_point_many_heads_and_peaked_keys():
     cfg = W.RPartConfig("q4step", 6, 40, 128, "const", 0, 0, peaked_keys=True)
     case = Q4Case(cfg, [300, 17, 2049, 64, 999, 4100], seed=5)

@@ -110,6 +110,15 @@ def test_edge_lengths_all_chunk_sizes(chunk):
     assert info["grid"] == 3 * torch.cuda.get_device_properties(0).multi_processor_count
 
 
+def test_more_sequences_than_planner_threads():
+    """2001 sequences: the planner's scrambled visiting order must still reach each one once."""
+    lens = [(7 * i) % 23 for i in range(2001)]
+    lens[1234], lens[2000] = 1500, 700
+    case = QCase(_cfg("q8manyseq", len(lens), 1), lens, seed=43)
+    check_qstep(case)
+    assert rpart.fd_plan_info(case.ws)["total_tokens"] == sum(lens) + len(lens)
+
+
 def test_step_entry_point_many_heads_and_peaked_keys():
     cfg = W.RPartConfig("qstep", 6, 40, 128, "const", 0, 0, peaked_keys=True)
     case = QCase(cfg, [300, 17, 2049, 64, 999, 4100], seed=5)
