@@ -156,8 +156,12 @@ __global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, int32_t *__restr
 // be written out and merged later costs far more than its bytes (result stores
 // interleaved with the read stream lower the achieved HBM bandwidth by several
 // per cent), so a sequence is cut only when it is longer than 1/16 of a
-// workgroup's share of the step.  Sequence b with L_b tokens is cut into
-// n_b = ceil(L_b / T) chunks of equal length rounded up to the granule.
+// workgroup's share of the step (`split` = 16; 4 for the quantised caches, whose
+// units carry a half to a quarter of the bytes per token against the same fixed cost:
+// measured there, a quarter against a sixteenth is +12 % on a geometric length mix with 4-bit
+// codes, +29 % on one sequence of 131072 tokens, and nowhere slower; for fp16 the two are
+// within 1 % of each other with 1/16 ahead on the ragged mixes).  Sequence b with L_b tokens
+// is cut into n_b = ceil(L_b / T) chunks of equal length rounded up to the granule.
 //
 // The schedule is static (a shared ticket counter was measured 4-5 % slower: the
 // atomic sits in the in-order return queue in front of the unit's first loads):
@@ -227,7 +231,7 @@ constexpr int kBigMax = 128;        // ... goes on a list of at most this many e
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
     int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid_long, int grid_short,
-    int short_below, int hashed, int wave_units, int max_items,
+    int short_below, int hashed, int wave_units, int split, int max_items,
     int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
     int4 *__restrict__ items, int32_t *__restrict__ order)
 {
@@ -271,7 +275,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     } else {
         // token-heads per worker: a workgroup, or a wave when each wave takes units of its own
         const long long share = (long long)total * H / ((long long)grid * (wave_now ? kWaves : 1));
-        long long t = share / 16;
+        long long t = share / split;
         T = (int)(t < 128 ? 128 : (t > (1 << 28) ? (1 << 28) : t));
     }
     T = (T + granule - 1) / granule * granule;
@@ -967,6 +971,7 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
                        desc->chunk_tokens, chunk_granule(desc->d), grid, 2 * grid, kShortSeq, 0, 0,
+                       16 /* split */,
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));

@@ -177,6 +177,7 @@ template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }  
 // a third one, which pays on short sequences (+5 % at 256 tokens per sequence, -5 % at 2048), so
 // the planner switches it on by the same rule as the fp16 kernel's second one.
 constexpr int kQWgLong = 2;
+constexpr int kQSplit = 4;          // a sequence is cut when longer than 1/4 of a worker's share
 template <int BITS> constexpr int q_wg_short() { return BITS == 8 ? 3 : 2; }
 // Units per wave instead of per workgroup when the batch holds many short sequences (the
 // planner's wave_units argument).  Measured against workgroup units with the best residency:
@@ -768,7 +769,7 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
                        desc->chunk_tokens, 64, kQWgLong * grid,
                        (desc->bits == 4 ? q_wg_short<4>() : q_wg_short<8>()) * grid, kShortSeq, 1,
-                       desc->bits == 4 ? q_wave_units<4>() : q_wave_units<8>(),
+                       desc->bits == 4 ? q_wave_units<4>() : q_wave_units<8>(), kQSplit,
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
