@@ -173,12 +173,17 @@ __device__ inline V ld_stream_u(const char *p)
 // arithmetic per byte, and a second wave per SIMD is what hides it.
 // The 4-bit kernel takes twice the loads of half the size, so as many bytes are in flight.
 template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }   // wave loads per tile
-// Workgroups per compute unit: two when the sequences are long; the 8-bit kernel (164 VGPRs) fits
-// a third one, which pays on short sequences (+5 % at 256 tokens per sequence, -5 % at 2048), so
-// the planner switches it on by the same rule as the fp16 kernel's second one.
-constexpr int kQWgLong = 2;
+// Workgroups per compute unit.  8 bit: two when the sequences are long; the kernel (164 VGPRs)
+// fits a third one, which pays on short sequences (+5 % at 256 tokens per sequence, -5 % at
+// 2048), so the planner switches it on by the same rule as the fp16 kernel's second one.
+// 4 bit: always three (168 VGPRs at that budget, six dwords spilled outside the streaming
+// loops).  Its units stream in a quarter of the fp16 kernel's time against the same fixed cost
+// per unit, and a third resident workgroup covers more of it: against two, 2049 tokens per
+// sequence +4 %, geometric mix +5.5 %, uniform 1..4096 +1.5 %, 256 each +2.4 %; uniform
+// 1..1024 -1.5 %, 16 sequences of 32768 -1.3 %, one of 131072 -3 %.
+template <int BITS> constexpr int q_wg_long() { return BITS == 8 ? 2 : 3; }
+template <int BITS> constexpr int q_wg_short() { return 3; }
 constexpr int kQSplit = 4;          // a sequence is cut when longer than 1/4 of a worker's share
-template <int BITS> constexpr int q_wg_short() { return BITS == 8 ? 3 : 2; }
 // Units per wave instead of per workgroup when the batch holds many short sequences (the
 // planner's wave_units argument).  Measured against workgroup units with the best residency:
 // 4 bit +30 % at 256 tokens per sequence, +22 % on lengths uniform in 1..1024, but -9 % at 2048
@@ -767,7 +772,8 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
     char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, 64, kQWgLong * grid,
+                       desc->chunk_tokens, 64,
+                       (desc->bits == 4 ? q_wg_long<4>() : q_wg_long<8>()) * grid,
                        (desc->bits == 4 ? q_wg_short<4>() : q_wg_short<8>()) * grid, kShortSeq, 1,
                        desc->bits == 4 ? q_wave_units<4>() : q_wave_units<8>(), kQSplit,
                        (int)w.max_items, (int32_t *)ws,
