@@ -160,6 +160,9 @@ __device__ inline f16x2 as_f16x2(unsigned w)
     return x.h;
 }
 
+// bytes 1 and 3 of w as two zero-extended halves, (w >> 8) & 0x00FF00FF, in one instruction
+__device__ inline unsigned odd_bytes(unsigned w) { return __builtin_amdgcn_perm(w, w, 0x0C030C01u); }
+
 template <typename V>
 __device__ inline V ld_stream_u(const char *p)
 {
@@ -281,7 +284,7 @@ struct TileQ {
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
                 a = __builtin_amdgcn_fdot2(as_f16x2(c[w] & 0x00FF00FFu), qh[2 * w], a, false);
-                a = __builtin_amdgcn_fdot2(as_f16x2((c[w] >> 8) & 0x00FF00FFu), qh[2 * w + 1], a, false);
+                a = __builtin_amdgcn_fdot2(as_f16x2(odd_bytes(c[w])), qh[2 * w + 1], a, false);
             }
             return a;
         } else {
@@ -323,7 +326,7 @@ struct TileQ {
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             if (BITS == 8) {
-                const f16x2 a = as_f16x2(c[w] & 0x00FF00FFu), b = as_f16x2((c[w] >> 8) & 0x00FF00FFu);
+                const f16x2 a = as_f16x2(c[w] & 0x00FF00FFu), b = as_f16x2(odd_bytes(c[w]));
                 acc[4 * w] = __builtin_fmaf(pv24, (float)a[0], acc[4 * w]);
                 acc[4 * w + 1] = __builtin_fmaf(pv24, (float)b[0], acc[4 * w + 1]);
                 acc[4 * w + 2] = __builtin_fmaf(pv24, (float)a[1], acc[4 * w + 2]);
