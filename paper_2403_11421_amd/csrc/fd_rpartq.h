@@ -163,10 +163,31 @@ __device__ inline f16x2 as_f16x2(unsigned w)
 // bytes 1 and 3 of w as two zero-extended halves, (w >> 8) & 0x00FF00FF, in one instruction
 __device__ inline unsigned odd_bytes(unsigned w) { return __builtin_amdgcn_perm(w, w, 0x0C030C01u); }
 
-template <typename V>
-__device__ inline V ld_stream_u(const char *p)
+// Streams are read through buffer descriptors: the base lives in scalar registers (it must be
+// the same in every lane), a lane adds a 32-bit byte offset, and advancing the stream is scalar
+// arithmetic.  Against 64-bit per-lane pointers this takes the address arithmetic off the vector
+// unit and frees ten vector registers: the 4-bit kernel, which is bound by instruction issue,
+// gains 1-4 % and no longer spills; the 8-bit kernel is unchanged.  No bounds are set in the
+// descriptor (the base moves with the stream, offsets stay below a block): offsets are computed
+// exactly as for plain loads.  Word 3 = 0x00020000: untyped 32-bit data, no swizzle.
+typedef __amdgpu_buffer_rsrc_t Rsrc;
+__device__ inline Rsrc stream_rsrc(const void *ubase)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const V *>(p));
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(ubase), 0, 0x7FFFFFFF, 0x00020000);
+}
+constexpr int kAuxNt = 2;                                 // non-temporal
+template <typename V> __device__ inline V ld_buf(Rsrc r, unsigned voff, int soff);
+template <> __device__ inline u32x4 ld_buf<u32x4>(Rsrc r, unsigned voff, int soff)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, kAuxNt);
+}
+template <> __device__ inline u32x2 ld_buf<u32x2>(Rsrc r, unsigned voff, int soff)
+{
+    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, kAuxNt);
+}
+template <> __device__ inline unsigned ld_buf<unsigned>(Rsrc r, unsigned voff, int soff)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(r, voff, soff, kAuxNt);
 }
 
 // Tile size and residency, measured on MI355X over the two-block rolling prefetch below (8-bit
@@ -179,8 +200,7 @@ template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }  
 // Workgroups per compute unit.  8 bit: two when the sequences are long; the kernel (164 VGPRs)
 // fits a third one, which pays on short sequences (+5 % at 256 tokens per sequence, -5 % at
 // 2048), so the planner switches it on by the same rule as the fp16 kernel's second one.
-// 4 bit: always three (168 VGPRs at that budget, six dwords spilled outside the streaming
-// loops).  Its units stream in a quarter of the fp16 kernel's time against the same fixed cost
+// 4 bit: always three (164 VGPRs, no spills).  Its units stream in a quarter of the fp16 kernel's time against the same fixed cost
 // per unit, and a third resident workgroup covers more of it: against two, 2049 tokens per
 // sequence +4 %, geometric mix +5.5 %, uniform 1..4096 +1.5 %, 256 each +2.4 %; uniform
 // 1..1024 -1.5 %, 16 sequences of 32768 -1.3 %, one of 131072 -3 %.
@@ -223,53 +243,62 @@ struct TileQ {
         return (((lane / RPW) % NL) * WPU + wave) * RPW + (lane % RPW);
     }
 
-    __device__ inline void load_kmeta(const float *p)
+    // mo4 = byte offset of this lane's token in the parameter stream
+    __device__ inline void load_kmeta(const float *base, unsigned mo4)
     {
+        const Rsrc r = stream_rsrc(base);
         if (BITS == 8) {
-            ks = __builtin_nontemporal_load(p);
+            ks = __uint_as_float(ld_buf<unsigned>(r, mo4, 0));
         } else {
-            const f32x2 t = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(p));
-            ks = t[0];
-            kz = t[1];
+            const u32x2 t = ld_buf<u32x2>(r, mo4, 0);
+            ks = __uint_as_float(t[0]);
+            kz = __uint_as_float(t[1]);
         }
     }
-    __device__ inline void load_vmeta(const float *p)
+    __device__ inline void load_vmeta(const float *base, unsigned mo4)
     {
+        const Rsrc r = stream_rsrc(base);
         if (BITS == 8) {
-            vs = __builtin_nontemporal_load(p);
+            vs = __uint_as_float(ld_buf<unsigned>(r, mo4, 0));
         } else {
-            const f32x2 t = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(p));
-            vs = t[0];
-            vz = t[1];
+            const u32x2 t = ld_buf<u32x2>(r, mo4, 0);
+            vs = __uint_as_float(t[0]);
+            vz = __uint_as_float(t[1]);
         }
     }
 
     // issue order = consumption order (loads return in order): K parameters, K codes,
     // V parameters, V codes
-    __device__ inline void load(const char *kp, const char *vp, const float *kmp, const float *vmp)
+    __device__ inline void load(const char *kb, const char *vb, const float *kmb, const float *vmb,
+                                unsigned co, unsigned mo)
     {
-        load_kmeta(kmp);
+        const Rsrc rk = stream_rsrc(kb), rv = stream_rsrc(vb);
+        load_kmeta(kmb, mo * 4u);
 #pragma unroll
-        for (int j = 0; j < NL; ++j) k[j] = ld_stream_u<CV>(kp + j * STRIDE);
-        load_vmeta(vmp);
+        for (int j = 0; j < NL; ++j) k[j] = ld_buf<CV>(rk, co, j * STRIDE);
+        load_vmeta(vmb, mo * 4u);
 #pragma unroll
-        for (int j = 0; j < NL; ++j) v[j] = ld_stream_u<CV>(vp + j * STRIDE);
+        for (int j = 0; j < NL; ++j) v[j] = ld_buf<CV>(rv, co, j * STRIDE);
     }
 
     // ragged last block of `rem` >= 1 tokens: lanes whose token is at or beyond `rem` re-read
     // token rem-1 (in bounds) and are masked in update<true, ...>
-    __device__ inline void load_tail(const char *kp, const char *vp, const float *kmp,
-                                     const float *vmp, int tok0, int own, int rem)
+    __device__ inline void load_tail(const char *kb, const char *vb, const float *kmb,
+                                     const float *vmb, unsigned co, unsigned mo, int tok0, int own,
+                                     int rem)
     {
         const int sback = own > rem - 1 ? own - (rem - 1) : 0;
-        load_kmeta(kmp - sback * MW);
-        load_vmeta(vmp - sback * MW);
+        const unsigned mt = mo - (unsigned)(sback * MW);           // token min(own, rem-1) >= 0
+        load_kmeta(kmb, mt * 4u);
+        load_vmeta(vmb, mt * 4u);
+        const Rsrc rk = stream_rsrc(kb), rv = stream_rsrc(vb);
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             const int over = j * TSTEP + tok0 - (rem - 1);
             const int back = over > 0 ? over * RB : 0;
-            k[j] = ld_stream_u<CV>(kp + (j * STRIDE - back));
-            v[j] = ld_stream_u<CV>(vp + (j * STRIDE - back));
+            const unsigned ct = co + (unsigned)(j * STRIDE) - (unsigned)back;   // row min(., rem-1) >= 0
+            k[j] = ld_buf<CV>(rk, ct, 0);
+            v[j] = ld_buf<CV>(rv, ct, 0);
         }
     }
 
@@ -354,7 +383,7 @@ struct TileQ {
     template <bool MASKED, bool REFILL>
     __device__ inline void update(const f16x2 (&qh)[EPL / 2], float kmul, float qs, float &m,
                                   float &l, float &aux, float (&acc)[EPL], int row, int tok0,
-                                  int rem,
+                                  int rem, unsigned co = 0, unsigned mo = 0,
                                   const char *kp2 = nullptr, const char *vp2 = nullptr,
                                   const float *kmp2 = nullptr, const float *vmp2 = nullptr)
     {
@@ -367,7 +396,7 @@ struct TileQ {
         }
         if (REFILL) {
             sched_fence();
-            load_kmeta(kmp2);
+            load_kmeta(kmp2, mo * 4u);
             sched_fence();
         }
 #pragma unroll
@@ -375,7 +404,7 @@ struct TileQ {
             float a = dot_codes(k[j], qh);
             if (REFILL) {
                 sched_fence();
-                k[j] = ld_stream_u<CV>(kp2 + j * STRIDE);
+                k[j] = ld_buf<CV>(stream_rsrc(kp2), co, j * STRIDE);
                 sched_fence();
             }
             a = row_sum<LPR>(a);
@@ -409,7 +438,7 @@ struct TileQ {
         }
         if (REFILL) {
             sched_fence();
-            load_vmeta(vmp2);
+            load_vmeta(vmp2, mo * 4u);
             sched_fence();
         }
 #pragma unroll
@@ -417,13 +446,21 @@ struct TileQ {
             axpy_codes(v[j], s[j], acc);
             if (REFILL) {
                 sched_fence();
-                v[j] = ld_stream_u<CV>(vp2 + j * STRIDE);
+                v[j] = ld_buf<CV>(stream_rsrc(vp2), co, j * STRIDE);
                 sched_fence();
             }
         }
         m = mn;
     }
 };
+
+// a value that is the same in every lane of the wave, moved to scalar registers
+__device__ inline int64_t uniform64(int64_t x)
+{
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(x & 0xFFFFFFFFll));
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)((unsigned long long)x >> 32));
+    return (int64_t)(((unsigned long long)hi << 32) | lo);
+}
 
 template <int BITS, int WPU>
 __device__ __forceinline__ void rpartq_body(
@@ -488,10 +525,15 @@ __device__ __forceinline__ void rpartq_body(
         if (nxt.ntok == 0 && j < n_rounds) nxt = fetch(++j);
 
         const int b = cur.b, h = cur.h;
-        const char *kp = k_codes + cur.row0 * RB + tid * LB;    // wave w starts at its own slot
-        const char *vp = v_codes + cur.row0 * RB + tid * LB;
-        const float *kmp = k_meta + (cur.row0 + own) * MW;
-        const float *vmp = v_meta + (cur.row0 + own) * MW;
+        // wave-uniform bases (scalar registers) and per-lane 32-bit offsets: the loads take the
+        // base from scalar registers, and advancing a stream is scalar arithmetic
+        const int64_t row0 = uniform64(cur.row0);
+        const char *kp = k_codes + row0 * RB;
+        const char *vp = v_codes + row0 * RB;
+        const float *kmp = k_meta + row0 * MW;
+        const float *vmp = v_meta + row0 * MW;
+        const unsigned co = (unsigned)(tid * LB);               // wave w starts at its own slot
+        const unsigned mo = (unsigned)(own * MW);
 
         // the query stays fp16 for the dot instruction; its scale (log2 e / sqrt d) and the 2^24
         // of the subnormal codes are applied to the dot product
@@ -517,7 +559,7 @@ __device__ __forceinline__ void rpartq_body(
 #pragma unroll
         for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
 
-        const int ntok = cur.ntok;
+        const int ntok = __builtin_amdgcn_readfirstlane(cur.ntok);
         const int n_blk = ntok / T::BLK_TOK;
         const int rem = ntok - n_blk * T::BLK_TOK;
 
@@ -532,14 +574,14 @@ __device__ __forceinline__ void rpartq_body(
             if (n_blk >= 4) {
                 // both loads are issued unconditionally on the way into the loop: its wait
                 // counts can then leave a whole block outstanding behind the one in use
-                A.load(kt, vt, kmt, vmt);
-                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kmt + MSTEP, vmt + MSTEP);
+                A.load(kt, vt, kmt, vmt, co, mo);
+                Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kmt + MSTEP, vmt + MSTEP, co, mo);
                 sched_fence();
                 do {
-                    A.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0,
+                    A.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0, co, mo,
                                                    kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES,
                                                    kmt + 2 * MSTEP, vmt + 2 * MSTEP);
-                    Bf.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0,
+                    Bf.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0, co, mo,
                                                     kt + 3 * T::BLK_BYTES, vt + 3 * T::BLK_BYTES,
                                                     kmt + 3 * MSTEP, vmt + 3 * MSTEP);
                     kt += 2 * T::BLK_BYTES;
@@ -548,13 +590,21 @@ __device__ __forceinline__ void rpartq_body(
                     vmt += 2 * MSTEP;
                     left -= 2;
                 } while (left > 3);
+                // the counters are the same in every lane; say so, so that the stream bases
+                // below stay in scalar registers
+                left = __builtin_amdgcn_readfirstlane(left);
+                const int64_t done = n_blk - left;
+                kt = kp + done * T::BLK_BYTES;
+                vt = vp + done * T::BLK_BYTES;
+                kmt = kmp + done * MSTEP;
+                vmt = vmp + done * MSTEP;
             } else {
-                A.load(kt, vt, kmt, vmt);
-                if (n_blk > 1) Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kmt + MSTEP, vmt + MSTEP);
+                A.load(kt, vt, kmt, vmt, co, mo);
+                if (n_blk > 1) Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES, kmt + MSTEP, vmt + MSTEP, co, mo);
                 sched_fence();
             }
             if (left == 3) {
-                A.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0,
+                A.template update<false, true>(qh, kmul, qs, m, l, aux, acc, row, 0, 0, co, mo,
                                                kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES,
                                                kmt + 2 * MSTEP, vmt + 2 * MSTEP);
                 Bf.template update<false, false>(qh, kmul, qs, m, l, aux, acc, row, 0, 0);
@@ -569,7 +619,7 @@ __device__ __forceinline__ void rpartq_body(
         if (rem > 0 && wave * T::RPW < rem) {              // this wave has at least one valid row
             const int64_t o = (int64_t)n_blk * T::BLK_BYTES;
             const int64_t so = (int64_t)n_blk * MSTEP;
-            A.load_tail(kp + o, vp + o, kmp + so, vmp + so, tok0, own, rem);
+            A.load_tail(kp + o, vp + o, kmp + so, vmp + so, co, mo, tok0, own, rem);
             A.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row, tok0, rem);
         }
 
