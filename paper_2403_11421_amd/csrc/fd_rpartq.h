@@ -318,17 +318,17 @@ struct TileQ {
             return a;
         } else {
             // a nibble in bits 4..7 of a half is still inside the mantissa field: it reads as
-            // 16 u * 2^-24, so the odd nibbles need no shift, only their own accumulator
-            float a0 = 0.f, a1 = 0.f;
+            // 16 u * 2^-24, so the odd nibbles need no shift; their query elements carry the 1/16
+            float a = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
                 const unsigned lo = c[w], hi = c[w] >> 8;
-                a0 = __builtin_amdgcn_fdot2(as_f16x2(lo & 0x000F000Fu), qh[4 * w], a0, false);
-                a1 = __builtin_amdgcn_fdot2(as_f16x2(lo & 0x00F000F0u), qh[4 * w + 1], a1, false);
-                a0 = __builtin_amdgcn_fdot2(as_f16x2(hi & 0x000F000Fu), qh[4 * w + 2], a0, false);
-                a1 = __builtin_amdgcn_fdot2(as_f16x2(hi & 0x00F000F0u), qh[4 * w + 3], a1, false);
+                a = __builtin_amdgcn_fdot2(as_f16x2(lo & 0x000F000Fu), qh[4 * w], a, false);
+                a = __builtin_amdgcn_fdot2(as_f16x2(lo & 0x00F000F0u), qh[4 * w + 1], a, false);
+                a = __builtin_amdgcn_fdot2(as_f16x2(hi & 0x000F000Fu), qh[4 * w + 2], a, false);
+                a = __builtin_amdgcn_fdot2(as_f16x2(hi & 0x00F000F0u), qh[4 * w + 3], a, false);
             }
-            return __builtin_fmaf(a1, 0.0625f, a0);
+            return a;
         }
     }
 
@@ -341,9 +341,14 @@ struct TileQ {
                 qh[2 * w] = f16x2{q[4 * w], q[4 * w + 2]};           // bytes 0 and 2 of word w
                 qh[2 * w + 1] = f16x2{q[4 * w + 1], q[4 * w + 3]};   // bytes 1 and 3
             } else {
+                // nibble n of a word holds the word's element n; odd nibbles are read as 16 u, so
+                // their query elements are divided by 16 here (exact but for elements below
+                // 2^-10, whose lost bits are far below the result's precision)
 #pragma unroll
-                for (int i = 0; i < 4; ++i)       // nibble n of a word holds the word's element n
+                for (int i = 0; i < 4; ++i) {
                     qh[4 * w + i] = f16x2{q[8 * w + i], q[8 * w + i + 4]};
+                    if (i & 1) qh[4 * w + i] *= f16x2{(_Float16)0.0625f, (_Float16)0.0625f};
+                }
             }
         }
     }
@@ -387,12 +392,18 @@ struct TileQ {
                                   const char *kp2 = nullptr, const char *vp2 = nullptr,
                                   const float *kmp2 = nullptr, const float *vmp2 = nullptr)
     {
-        // hand every row its tokens' K parameters first: after that the registers are free to refill
+        // score = kmul * scale * a + qs * zero.  Every lane scales the parameters of its own
+        // token once, then hands them to the rows that use them (a lane uses NL tokens): after
+        // that the registers are free to refill.  8 bit: zero = -128 scale, so the score is
+        // (kmul * scale) * (a + c0).
+        const float ksm = ks * kmul;
+        const float kzq = BITS == 8 ? 0.f : kz * qs;
+        const float c0 = -128.0f * qs / kmul;                    // the same for the whole unit
         float s[NL], z[NL];
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            s[j] = __shfl(ks, j * RPW + row);
-            z[j] = BITS == 8 ? -128.0f * s[j] : __shfl(kz, j * RPW + row);
+            s[j] = __shfl(ksm, j * RPW + row);
+            z[j] = BITS == 8 ? 0.f : __shfl(kzq, j * RPW + row);
         }
         if (REFILL) {
             sched_fence();
@@ -408,7 +419,7 @@ struct TileQ {
                 sched_fence();
             }
             a = row_sum<LPR>(a);
-            a = __builtin_fmaf(a * kmul, s[j], z[j] * qs);
+            a = BITS == 8 ? (a + c0) * s[j] : __builtin_fmaf(a, s[j], z[j]);
             if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
             s[j] = a;
         }
@@ -425,16 +436,19 @@ struct TileQ {
 #pragma unroll
             for (int i = 0; i < EPL; ++i) acc[i] *= corr;
         }
-        // weights times V scales; the weighted zero points go to aux; then the V parameter
-        // registers are free as well
+        // weights times V scales (with the 2^24 of the subnormal codes, applied by the token's
+        // own lane); the weighted zero points go to aux; then the V parameter registers are free
+        // as well
+        const float vsm = vs * 16777216.0f;
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             float p = fast_exp2(s[j] - mn);
             if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
             l += p;
-            const float pv = p * __shfl(vs, j * RPW + row);
-            aux += BITS == 8 ? -128.0f * pv : p * __shfl(vz, j * RPW + row);
-            s[j] = pv * 16777216.0f;
+            const float pv24 = p * __shfl(vsm, j * RPW + row);
+            aux = BITS == 8 ? __builtin_fmaf(pv24, -128.0f / 16777216.0f, aux)
+                            : __builtin_fmaf(p, __shfl(vz, j * RPW + row), aux);
+            s[j] = pv24;
         }
         if (REFILL) {
             sched_fence();
