@@ -366,19 +366,29 @@ struct TileQ {
                 acc[4 * w + 2] = __builtin_fmaf(pv24, (float)a[1], acc[4 * w + 2]);
                 acc[4 * w + 3] = __builtin_fmaf(pv24, (float)b[1], acc[4 * w + 3]);
             } else {
-                const float pv20 = pv24 * 0.0625f;                    // for the nibbles read as 16 u
+                // the odd nibbles are read as 16 u: their accumulators run 16 times too high
+                // and are put right once per unit (fix_odd)
                 const unsigned lo = c[w], hi = c[w] >> 8;
                 const f16x2 n04 = as_f16x2(lo & 0x000F000Fu), n15 = as_f16x2(lo & 0x00F000F0u);
                 const f16x2 n26 = as_f16x2(hi & 0x000F000Fu), n37 = as_f16x2(hi & 0x00F000F0u);
                 acc[8 * w] = __builtin_fmaf(pv24, (float)n04[0], acc[8 * w]);
-                acc[8 * w + 1] = __builtin_fmaf(pv20, (float)n15[0], acc[8 * w + 1]);
+                acc[8 * w + 1] = __builtin_fmaf(pv24, (float)n15[0], acc[8 * w + 1]);
                 acc[8 * w + 2] = __builtin_fmaf(pv24, (float)n26[0], acc[8 * w + 2]);
-                acc[8 * w + 3] = __builtin_fmaf(pv20, (float)n37[0], acc[8 * w + 3]);
+                acc[8 * w + 3] = __builtin_fmaf(pv24, (float)n37[0], acc[8 * w + 3]);
                 acc[8 * w + 4] = __builtin_fmaf(pv24, (float)n04[1], acc[8 * w + 4]);
-                acc[8 * w + 5] = __builtin_fmaf(pv20, (float)n15[1], acc[8 * w + 5]);
+                acc[8 * w + 5] = __builtin_fmaf(pv24, (float)n15[1], acc[8 * w + 5]);
                 acc[8 * w + 6] = __builtin_fmaf(pv24, (float)n26[1], acc[8 * w + 6]);
-                acc[8 * w + 7] = __builtin_fmaf(pv20, (float)n37[1], acc[8 * w + 7]);
+                acc[8 * w + 7] = __builtin_fmaf(pv24, (float)n37[1], acc[8 * w + 7]);
             }
+        }
+    }
+
+    // end of a unit: the accumulators of the 4-bit kernel's odd elements (see axpy_codes)
+    __device__ static inline void fix_odd(float (&acc)[EPL])
+    {
+        if (BITS == 4) {
+#pragma unroll
+            for (int i = 1; i < EPL; i += 2) acc[i] *= 0.0625f;
         }
     }
 
@@ -637,6 +647,7 @@ __device__ __forceinline__ void rpartq_body(
             A.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row, tok0, rem);
         }
 
+        T::fix_odd(acc);
         // combine the rows of this wave
 #pragma unroll
         for (int off = LPR; off < 64; off <<= 1) {
