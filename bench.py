@@ -110,7 +110,7 @@ def cpu_baseline(cfg, cache, vec, lens_after, n_sample):
     return {
         "value": kv_bytes / dt / 1e9, "unit": "GB/s", "cores": min(threads, len(batch)),
         "kind": "oracle",
-        "sample": f"{len(batch)} of {cfg.B} sequences (every {step}th), all {cfg.H} heads, "
+        "sample": f"{len(batch)} of {cfg.B} sequences (a stride of {step}), all {cfg.H} heads, "
                   f"{int(hl.sum())} cached tokens, decode only, {dt:.2f} s wall",
         "seq_per_s": len(batch) / dt,
     }
