@@ -59,3 +59,20 @@ def test_full_config_sampled_parity_and_global_properties(name):
         span = (hi - lo).clamp_min(1e-3)
         assert bool((out[b] <= hi + 2e-3 * span + 1e-3).all())
         assert bool((out[b] >= lo - 2e-3 * span - 1e-3).all())
+
+
+def test_long_context_few_sequences():
+    """Long-context decoding at small batch: one sequence of 131071 cached tokens (cut into 128
+    chunks per head, laid out by the planner's whole workgroup and merged 64 chunk states at a
+    time) and, in the same step, two of 40000 and 70001 and a short one; every sequence against
+    the oracle, in the library's own chunking."""
+    cfg = W.RPartConfig("long_context", 4, 8, 128, "const", 0, 0)
+    lens = [131071, 40000, 70001, 300]
+    n_tok = W.total_tokens_after_append(lens)
+    case = DeviceCase(cfg, lens, extra_cap=8)
+    case.ws = case.cache.workspace(n_tok)
+    err, maxv = check_step(case, nthreads=16)
+    plan = rpart.fd_plan_info(case.ws)
+    print(f"long context: max|err|={err:.3e} max|V|={maxv:.2f} plan={plan}", flush=True)
+    assert plan["total_tokens"] == n_tok and plan["items"] > 64
+    assert case.cache.seq_lens.cpu().tolist() == [L + 1 for L in lens]

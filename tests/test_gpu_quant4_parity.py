@@ -222,3 +222,16 @@ def test_full_config_sampled_parity(name):
     print(f"{name}: max|err|={err:.3e} max|V|={maxv:.2f} plan={rpart.fd_plan_info(case.ws)}", flush=True)
     assert case.cache.seq_lens.cpu().tolist() == [L + 1 for L in lens]
     assert bool(torch.isfinite(case.out.float()).all())
+
+
+def test_long_context_few_sequences():
+    """One sequence of 100001 cached tokens next to two shorter ones: many chunks per head
+    (planner's cooperative lay-out, batched merge), library-chosen chunking."""
+    cfg = _cfg("q4long", 3, 8)
+    lens = [100001, 30000, 257]
+    case = Q4Case(cfg, lens, seed=77, extra_cap=4)
+    case.ws = case.cache.workspace(sum(lens) + len(lens))
+    check_q4step(case)
+    plan = rpart.fd_plan_info(case.ws)
+    print(f"long context: plan={plan}", flush=True)
+    assert plan["items"] > 16

@@ -208,3 +208,16 @@ def test_full_config_sampled_parity(name):
     assert case.cache.seq_lens.cpu().tolist() == [L + 1 for L in lens]
     out = case.out.float()
     assert bool(torch.isfinite(out).all())
+
+
+def test_long_context_few_sequences():
+    """One sequence of 100001 cached tokens next to two shorter ones: many chunks per head
+    (planner's cooperative lay-out, batched merge), library-chosen chunking."""
+    cfg = _cfg("q8long", 3, 8)
+    lens = [100001, 30000, 257]
+    case = QCase(cfg, lens, seed=77, extra_cap=4)
+    case.ws = case.cache.workspace(sum(lens) + len(lens))
+    check_qstep(case)
+    plan = rpart.fd_plan_info(case.ws)
+    print(f"long context: plan={plan}", flush=True)
+    assert plan["items"] > 16
