@@ -656,11 +656,23 @@ __device__ __forceinline__ void rpartq_body(
                 A.template update<false, false>(qh, kmul, qs, m, l, aux, acc, row, 0, 0);
             }
         }
-        if (rem > 0 && wave * T::RPW < rem) {              // this wave has at least one valid row
-            const int64_t o = (int64_t)n_blk * T::BLK_BYTES;
-            const int64_t so = (int64_t)n_blk * MSTEP;
-            A.load_tail(kp + o, vp + o, kmp + so, vmp + so, co, mo, tok0, own, rem);
-            A.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row, tok0, rem);
+        // The ragged rest of the unit goes through tiles of one wave load (8 tokens per wave): a
+        // rest of a few tokens then costs a few tokens' arithmetic, not a whole block's (uniform
+        // 2048-token batches leave exactly one token, the one just appended).
+        {
+            using T1 = TileQ<BITS, 1, WPU>;
+            const unsigned mo1 = (unsigned)(T1::own_token(lane, wave) * MW);
+            for (int t0 = 0; t0 < rem; t0 += T1::BLK_TOK) {
+                const int r1 = min(rem - t0, T1::BLK_TOK);
+                if (wave * T::RPW < r1) {                  // this wave has at least one valid row
+                    const int64_t o = (int64_t)n_blk * T::BLK_BYTES + (int64_t)t0 * RB;
+                    const int64_t so = (int64_t)n_blk * MSTEP + (int64_t)t0 * MW;
+                    T1 C;
+                    C.load_tail(kp + o, vp + o, kmp + so, vmp + so, co, mo1, tok0,
+                                T1::own_token(lane, wave), r1);
+                    C.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row, tok0, r1);
+                }
+            }
         }
 
         T::fix_odd(acc);
