@@ -31,7 +31,7 @@ def _tm16(t):
 
 
 @pytest.mark.parametrize("n_streams", [2, 1])
-@pytest.mark.parametrize("kv", ["fp16", "int8"])
+@pytest.mark.parametrize("kv", ["fp16", "int8", "int4"])
 def test_every_block_of_every_token_matches_the_oracle(kv, n_streams):
     dev = "cuda"
     H, d, N, n_tokens = 3, 128, 3, 3
@@ -82,10 +82,17 @@ def test_every_block_of_every_token_matches_the_oracle(kv, n_streams):
                         assert np.array_equal(_tm16(c.block("K", b)), h["K"][b])
                         assert np.array_equal(_tm16(c.block("V", b)), h["V"][b])
                 else:
-                    O.kvq_append(h["Kc"], h["Ks"], h["Vc"], h["Vs"], h["lens"], kb, vb)
-                    want, _ = O.rpartq_decode(h["Kc"], h["Ks"], h["Vc"], h["Vs"], h["lens"], qb)
-                    maxv = max(float(np.abs((vc[:L].astype(np.float64) - 128) * vs[:L, :, None]).max())
-                               for vc, vs, L in zip(h["Vc"], h["Vs"], h["lens"]) if L)
+                    if kv == "int8":
+                        O.kvq_append(h["Kc"], h["Ks"], h["Vc"], h["Vs"], h["lens"], kb, vb)
+                        want, _ = O.rpartq_decode(h["Kc"], h["Ks"], h["Vc"], h["Vs"], h["lens"], qb)
+                        maxv = max(float(np.abs((vc[:L].astype(np.float64) - 128) * vs[:L, :, None]).max())
+                                   for vc, vs, L in zip(h["Vc"], h["Vs"], h["lens"]) if L)
+                    else:                                    # 4 bit: packed codes, (scale, zero) pairs
+                        O.kvq4_append(h["Kc"], h["Ks"], h["Vc"], h["Vs"], h["lens"], kb, vb)
+                        want, _ = O.rpartq4_decode(h["Kc"], h["Ks"], h["Vc"], h["Vs"], h["lens"], qb)
+                        maxv = max(float(np.abs(O.unpack_u4(vc[:L]).astype(np.float64) * vs[:L, :, 0:1]
+                                                + vs[:L, :, 1:2]).max())
+                                   for vc, vs, L in zip(h["Vc"], h["Vs"], h["lens"]) if L)
                     for b in range(cfgs[m].B):
                         assert np.array_equal(_tm(c.codes("K", b)), h["Kc"][b])
                         assert np.array_equal(_tm(c.scales("K", b)), h["Ks"][b])
