@@ -66,17 +66,27 @@ def test_windowed_fp16_cache_every_step(n_sink, windows, steps):
     assert rpart.fd_read_status(cache.desc) == 0
 
 
-def test_windowed_int8_cache_every_step():
+@pytest.mark.parametrize("nbits", [8, 4])
+def test_windowed_quantised_cache_every_step(nbits):
     H, d, n_sink, windows, steps = 2, 128, 3, [6, 70], 120
     B = len(windows)
     cfg = W.RPartConfig("winq", B, H, d, "const", 0, 0)
     caps = [n_sink + w for w in windows]
-    cache = KVCacheQ(B, H, d, caps, n_sink=n_sink)
+    cache = KVCacheQ(B, H, d, caps, n_sink=n_sink, bits=nbits)
     ws = cache.workspace(sum(caps))
     out = torch.empty(B, H, d, dtype=torch.float16, device="cuda")
-    hist = [dict(Kc=np.zeros((steps, H, d), np.uint8), Ks=np.zeros((steps, H), np.float32),
-                 Vc=np.zeros((steps, H, d), np.uint8), Vs=np.zeros((steps, H), np.float32))
+    cshape = (steps, H, d) if nbits == 8 else (steps, H, d // 2)       # codes; 4 bit: two per byte
+    pshape = (steps, H) if nbits == 8 else (steps, H, 2)               # scale; 4 bit: (scale, zero)
+    hist = [dict(Kc=np.zeros(cshape, np.uint8), Ks=np.zeros(pshape, np.float32),
+                 Vc=np.zeros(cshape, np.uint8), Vs=np.zeros(pshape, np.float32))
             for _ in range(B)]
+    quantise = O.quantize_rows_i8 if nbits == 8 else O.quantize_rows_u4
+    decode = O.rpartq_decode if nbits == 8 else O.rpartq4_decode
+
+    def dequant(c, p):
+        if nbits == 8:
+            return (c.astype(np.float64) - 128) * p[:, :, None]
+        return O.unpack_u4(c).astype(np.float64) * p[:, :, 0:1] + p[:, :, 1:2]
     sims = [WO.BoundedCache(n_sink, w) for w in windows]
 
     def tm(t):
@@ -86,8 +96,8 @@ def test_windowed_int8_cache_every_step():
         q, kn, vn = _vec(cfg, "q", t), _vec(cfg, "k_new", t), _vec(cfg, "v_new", t)
         rpart.fd_rpartq_step(cache.desc, q, kn, vn, out, ws)
         torch.cuda.synchronize()
-        kc, ks = O.quantize_rows_i8(bits(kn))                # the oracle's quantiser on the inputs
-        vc, vs = O.quantize_rows_i8(bits(vn))
+        kc, ks = quantise(bits(kn))                          # the oracle's quantiser on the inputs
+        vc, vs = quantise(bits(vn))
         got = out.cpu().double().numpy()
         for b in range(B):
             h = hist[b]
@@ -98,10 +108,10 @@ def test_windowed_int8_cache_every_step():
                              ("Vc", cache.codes("V", b)), ("Vs", cache.scales("V", b))):
                 assert np.array_equal(tm(dev)[:len(rows)], h[key][rows]), (t, b, key)
             S = WO.token_set(t + 1, n_sink, windows[b])
-            want, _ = O.rpartq_decode([np.ascontiguousarray(h["Kc"][S])], [np.ascontiguousarray(h["Ks"][S])],
-                                      [np.ascontiguousarray(h["Vc"][S])], [np.ascontiguousarray(h["Vs"][S])],
-                                      np.array([len(S)], np.int32), bits(q)[b:b + 1])
-            maxv = float(np.abs((h["Vc"][S].astype(np.float64) - 128) * h["Vs"][S][:, :, None]).max())
+            want, _ = decode([np.ascontiguousarray(h["Kc"][S])], [np.ascontiguousarray(h["Ks"][S])],
+                             [np.ascontiguousarray(h["Vc"][S])], [np.ascontiguousarray(h["Vs"][S])],
+                             np.array([len(S)], np.int32), bits(q)[b:b + 1])
+            maxv = float(np.abs(dequant(h["Vc"][S], h["Vs"][S])).max())
             assert np.abs(got[b] - want[0]).max() <= TOL * maxv, (t, b)
     assert rpart.fd_read_status(cache.desc) == 0
 
