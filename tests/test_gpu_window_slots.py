@@ -132,15 +132,15 @@ def test_window_state_errors_are_reported_and_skip_the_append():
     assert cache.seq_lens.cpu().tolist() == [3, 1] and cache.seq_seen.cpu().tolist() == [0, 1]
 
 
-@pytest.mark.parametrize("kv", ["fp16", "int8"])
+@pytest.mark.parametrize("kv", ["fp16", "int8", "int4"])
 def test_slots_are_released_and_reused(kv):
     """Sequences of random lengths come and go; a host free list hands out slots, the device
     side is fd_kv_release / fd_kv_reset.  Every step is checked against the oracle."""
     rng = random.Random(11)
     B, H, d, cap, steps = 6, 2, 128, 48, 90
     cfg = W.RPartConfig("slots", B, H, d, "const", 0, 0)
-    cls = KVCache if kv == "fp16" else KVCacheQ
-    cache = cls(B, H, d, [cap] * B)
+    cache = KVCache(B, H, d, [cap] * B) if kv == "fp16" else \
+        KVCacheQ(B, H, d, [cap] * B, bits=4 if kv == "int4" else 8)
     ws = cache.workspace(B * cap)
     out = torch.empty(B, H, d, dtype=torch.float16, device="cuda")
     slots = sched.Slots(B)
@@ -168,10 +168,10 @@ def test_slots_are_released_and_reused(kv):
             live[s] = [rng.randint(1, cap), []]
             started.append(s)
         if started:
-            (rpart.fd_kvq_reset if kv == "int8" else rpart.fd_kv_reset)(cache.desc, ids(started))
+            (rpart.fd_kv_reset if kv == "fp16" else rpart.fd_kvq_reset)(cache.desc, ids(started))
         q, kn, vn = _vec(cfg, "q", t), _vec(cfg, "k_new", t), _vec(cfg, "v_new", t)
         out.fill_(float("nan"))
-        (rpart.fd_rpartq_step if kv == "int8" else rpart.fd_rpart_step)(cache.desc, q, kn, vn, out, ws)
+        (rpart.fd_rpart_step if kv == "fp16" else rpart.fd_rpartq_step)(cache.desc, q, kn, vn, out, ws)
         torch.cuda.synchronize()
         got = out.cpu().double().numpy()
         lens = cache.seq_lens.cpu().tolist()
@@ -188,11 +188,16 @@ def test_slots_are_released_and_reused(kv):
             if kv == "fp16":
                 want, _, _ = O.rpart_decode([Kh], [Vh], np.array([len(Kh)], np.int32), qb[s:s + 1])
                 maxv = float(np.abs(f64(Vh)).max())
-            else:
+            elif kv == "int8":
                 kc, ks = O.quantize_rows_i8(Kh)
                 vc, vs = O.quantize_rows_i8(Vh)
                 want, _ = O.rpartq_decode([kc], [ks], [vc], [vs], np.array([len(Kh)], np.int32), qb[s:s + 1])
                 maxv = float(np.abs((vc.astype(np.float64) - 128) * vs[:, :, None]).max())
+            else:
+                kc, ks = O.quantize_rows_u4(Kh)
+                vc, vs = O.quantize_rows_u4(Vh)
+                want, _ = O.rpartq4_decode([kc], [ks], [vc], [vs], np.array([len(Kh)], np.int32), qb[s:s + 1])
+                maxv = float(np.abs(O.unpack_u4(vc).astype(np.float64) * vs[:, :, 0:1] + vs[:, :, 1:2]).max())
             assert np.abs(got[s] - want[0]).max() <= TOL * maxv, (t, s)
     assert reused > 5 and rpart.fd_read_status(cache.desc) == 0
     assert slots.in_use() == len(live)
