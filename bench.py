@@ -125,7 +125,9 @@ def schedule_mode(args) -> int:
     n_steps = 2 * S
     for kind in (["batch", "sls"] if args.schedule == "both" else [args.schedule]):
         r = sls_run.run_schedule(kind, B, S, F, n_steps,
-                                 W_lim=args.sched_wlim if args.sched_wlim > 0 else None)
+                                 W_lim=args.sched_wlim if args.sched_wlim > 0 else None, kv=args.kv)
+        from paper_2403_11421_amd import workloads as W
+        bpt = kv_bytes_per_token(W.RPartConfig("sched", B, r["H"], r["d"], "const", 0, 0), args.kv)
         ms, loads = r["ms"], r["loads"]
         steady = list(range(S, n_steps))                     # after the cold start
         tok = sum(loads[i] for i in steady)
@@ -133,12 +135,12 @@ def schedule_mode(args) -> int:
         srt = sorted(ms[i] for i in steady)
         print(json.dumps({
             "metric": "R-Part latency per decode step under a sequence schedule (Section 4.2)",
-            "schedule": kind, "B": B, "S": S, "F": F, "M": r["M"], "H": r["H"], "d": r["d"],
+            "schedule": kind, "kv": args.kv, "B": B, "S": S, "F": F, "M": r["M"], "H": r["H"], "d": r["d"],
             "steps": n_steps, "steady_steps": len(steady), "W_lim": r.get("W_lim"),
             "peak_load_tokens": max(loads[i] for i in steady),
             "mean_load_tokens": tok / len(steady),
             "peak_ms": srt[-1], "p50_ms": srt[len(srt) // 2], "mean_ms": tms / len(steady),
-            "steady_kv_gbps": 4 * r["H"] * r["d"] * tok / (tms * 1e-3) / 1e9,
+            "steady_kv_gbps": bpt * tok / (tms * 1e-3) / 1e9,
             "tokens_per_s_one_layer": len(steady) * B / (tms * 1e-3),
             "unit": "ms", "n_gpus": 1, "data": "synthetic", "dtype": "f32"}))
     return 0

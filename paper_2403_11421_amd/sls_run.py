@@ -13,7 +13,16 @@ from typing import Callable, Dict, List, Optional
 import torch
 
 from . import rpart, sched, workloads as W
-from .kvcache import KVCache
+from .kvcache import KVCache, KVCacheQ
+
+
+def _make_cache(kv: str, B: int, H: int, d: int, S: int, dev):
+    """A cache of B slots of S rows in the given format and the step / reset calls that go with it."""
+    assert kv in ("fp16", "int8", "int4")
+    if kv == "fp16":
+        return KVCache(B, H, d, [S] * B, dev), rpart.fd_rpart_step, rpart.fd_kv_reset
+    return (KVCacheQ(B, H, d, [S] * B, dev, bits=4 if kv == "int4" else 8),
+            rpart.fd_rpartq_step, rpart.fd_kvq_reset)
 
 
 def step_vectors(cfg: W.RPartConfig, which: str, step: int, seed: int, device) -> torch.Tensor:
@@ -53,7 +62,8 @@ def controlled_starts(B: int, S: int, M: int, F: int, W_lim: int, n_steps: int) 
 
 def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 128,
                  seed: int = W.DEFAULT_SEED, device="cuda", timed: bool = True,
-                 on_step: Optional[Callable] = None, W_lim: Optional[int] = None) -> Dict:
+                 on_step: Optional[Callable] = None, W_lim: Optional[int] = None,
+                 kv: str = "fp16") -> Dict:
     """kind = "sls": micro-batches of M = B*F/S sequences every F steps (Eq. 5);
     kind = "batch": all B sequences together, the next batch when they finish;
     kind = "control": micro-batches of M = B*F/S sequences admitted by Algorithm 1 under the
@@ -61,9 +71,10 @@ def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d
 
     Sequence slots are reused round-robin; a micro-batch's slots are reset when it starts.
     During the cold start only the slots started so far take part (a prefix of the slots).
-    on_step(step, cache, q, k_new, v_new, out, n_active) is called after each step (tests)."""
+    on_step(step, cache, q, k_new, v_new, out, n_active) is called after each step (tests).
+    kv = "fp16", "int8" or "int4" chooses the cache format (Section 5.2)."""
     if kind == "control":
-        return run_controlled(B, S, F, n_steps, H, d, seed, device, timed, on_step, W_lim)
+        return run_controlled(B, S, F, n_steps, H, d, seed, device, timed, on_step, W_lim, kv)
     assert kind in ("sls", "batch")
     cfg = W.RPartConfig(f"{kind}_B{B}_S{S}_F{F}", B, H, d, "const", 0, 0)
     M = sched.sls_microbatch_size(B, F, S) if kind == "sls" else B
@@ -74,7 +85,7 @@ def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d
              else sched.batch_step_loads(B, S, n_steps))
 
     dev = torch.device(device)
-    cache = KVCache(B, H, d, [S] * B, dev)
+    cache, step_fn, reset_fn = _make_cache(kv, B, H, d, S, dev)
     out = torch.zeros(B, H, d, dtype=torch.float16, device=dev)
     ws = cache.workspace(B * S)
     group_ids = [torch.arange(g * M, (g + 1) * M, dtype=torch.int32, device=dev) for g in range(n_groups)]
@@ -83,7 +94,7 @@ def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d
     for step in range(n_steps):
         if step % period == 0:                          # a micro-batch starts: recycle its slots
             g = (step // period) % n_groups
-            rpart.fd_kv_reset(cache.desc, group_ids[g])
+            reset_fn(cache.desc, group_ids[g])
             started = min(n_groups, started + 1)
         n_active = started * M
         cache.desc.B = n_active                         # cold start: only a prefix of the slots is live
@@ -93,7 +104,7 @@ def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d
         if timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-        rpart.fd_rpart_step(cache.desc, q, k_new, v_new, out, ws)
+        step_fn(cache.desc, q, k_new, v_new, out, ws)
         if timed:
             e1.record()
             events.append((e0, e1))
@@ -104,13 +115,14 @@ def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d
     cache.desc.B = B
     assert rpart.fd_read_status(cache.desc) == 0
     ms = [a.elapsed_time(b) for a, b in events]
-    return {"kind": kind, "B": B, "S": S, "F": F, "M": M, "H": H, "d": d, "steps": n_steps,
+    return {"kind": kind, "kv": kv, "B": B, "S": S, "F": F, "M": M, "H": H, "d": d, "steps": n_steps,
             "loads": loads, "ms": ms, "final_lens": cache.seq_lens.cpu().tolist()}
 
 
 def run_controlled(B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 128,
                    seed: int = W.DEFAULT_SEED, device="cuda", timed: bool = True,
-                   on_step: Optional[Callable] = None, W_lim: Optional[int] = None) -> Dict:
+                   on_step: Optional[Callable] = None, W_lim: Optional[int] = None,
+                   kv: str = "fp16") -> Dict:
     """Decode loop whose micro-batches are admitted by Algorithm 1.  Slots of finished sequences
     are released (free slots cost nothing) and reused by the next micro-batch.
     on_step(step, cache, q, k_new, v_new, out, live_slots) is called after each step (tests)."""
@@ -120,7 +132,7 @@ def run_controlled(B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 1
         W_lim = sched.sls_peak_load(M, F, S) + M        # the printed GetEarliestStep needs
     starts = controlled_starts(B, S, M, F, W_lim, n_steps)
     dev = torch.device(device)
-    cache = KVCache(B, H, d, [S] * B, dev)
+    cache, step_fn, reset_fn = _make_cache(kv, B, H, d, S, dev)
     out = torch.zeros(B, H, d, dtype=torch.float16, device=dev)
     ws = cache.workspace(B * S)
     n_groups = B // M
@@ -138,7 +150,7 @@ def run_controlled(B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 1
         if nxt < len(starts) and starts[nxt] == step:
             g = min(range(n_groups), key=lambda i: busy_until[i])
             assert busy_until[g] <= step
-            rpart.fd_kv_reset(cache.desc, group_ids[g])
+            reset_fn(cache.desc, group_ids[g])
             busy_until[g] = step + S
             live += list(range(g * M, (g + 1) * M))
             nxt += 1
@@ -148,7 +160,7 @@ def run_controlled(B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 1
         if timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
-        rpart.fd_rpart_step(cache.desc, q, k_new, v_new, out, ws)
+        step_fn(cache.desc, q, k_new, v_new, out, ws)
         if timed:
             e1.record()
             events.append((e0, e1))
@@ -159,6 +171,6 @@ def run_controlled(B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 1
     torch.cuda.synchronize()
     assert rpart.fd_read_status(cache.desc) == 0
     ms = [a.elapsed_time(b) for a, b in events]
-    return {"kind": "control", "B": B, "S": S, "F": F, "M": M, "H": H, "d": d, "steps": n_steps,
+    return {"kind": "control", "kv": kv, "B": B, "S": S, "F": F, "M": M, "H": H, "d": d, "steps": n_steps,
             "W_lim": W_lim, "starts": starts, "loads": loads, "ms": ms,
             "final_lens": cache.seq_lens.cpu().tolist()}

@@ -54,6 +54,62 @@ def test_every_step_matches_the_oracle(kind, B, S, F):
     assert seen == list(range(n_steps)) and res["loads"] == want_loads
 
 
+@pytest.mark.parametrize("kv", ["int8", "int4"])
+def test_every_step_matches_the_oracle_on_quantised_caches(kv):
+    """The same loop over a quantised cache (Section 5.2 with Section 4.2): per step, code bytes,
+    row parameters and lengths bit-exact, output within tolerance of the oracle's own
+    append-and-attend on host copies."""
+    kind, B, S, F, H, d = "sls", 8, 12, 3, 3, 128
+    n_steps = 3 * S + 1
+    M = B * F // S
+    n_groups = B // M
+    four = kv == "int4"
+    host = {"Kc": [np.zeros((S, H, d // 2 if four else d), np.uint8) for _ in range(B)],
+            "Vc": [np.zeros((S, H, d // 2 if four else d), np.uint8) for _ in range(B)],
+            "Kp": [np.zeros((S, H, 2) if four else (S, H), np.float32) for _ in range(B)],
+            "Vp": [np.zeros((S, H, 2) if four else (S, H), np.float32) for _ in range(B)],
+            "lens": np.zeros(B, np.int32)}
+    append = O.kvq4_append if four else O.kvq_append
+    decode = O.rpartq4_decode if four else O.rpartq_decode
+    want_loads = SO.step_loads(SO.sls_starts(M, F, n_steps), S, n_steps)
+    seen = []
+
+    def tm(t):
+        return np.ascontiguousarray(t.permute(1, 0, *range(2, t.dim())).cpu().numpy())
+
+    def dequant(c, p):
+        if four:
+            return O.unpack_u4(c).astype(np.float64) * p[..., 0:1] + p[..., 1:2]
+        return (c.astype(np.float64) - 128) * p[..., None]
+
+    def on_step(step, cache, q, k_new, v_new, out, n_active):
+        if step % F == 0:
+            g = (step // F) % n_groups
+            host["lens"][g * M:(g + 1) * M] = 0
+        act = list(range(n_active))
+        sel = [[host[k][b] for b in act] for k in ("Kc", "Kp", "Vc", "Vp")]
+        lens = host["lens"][:n_active].copy()
+        append(sel[0], sel[1], sel[2], sel[3], lens, bits(k_new.cpu()[:n_active]), bits(v_new.cpu()[:n_active]))
+        host["lens"][:n_active] = lens
+        want, _ = decode(sel[0], sel[1], sel[2], sel[3], lens, bits(q.cpu()[:n_active]))
+        assert np.array_equal(cache.seq_lens.cpu().numpy()[:n_active], lens)
+        assert int(lens.sum()) == want_loads[step]
+        maxv = 0.0
+        for b in act:
+            L = int(lens[b])
+            assert np.array_equal(tm(cache.codes("K", b))[:L], host["Kc"][b][:L])
+            assert np.array_equal(tm(cache.scales("K", b))[:L], host["Kp"][b][:L])
+            assert np.array_equal(tm(cache.codes("V", b))[:L], host["Vc"][b][:L])
+            assert np.array_equal(tm(cache.scales("V", b))[:L], host["Vp"][b][:L])
+            maxv = max(maxv, float(np.abs(dequant(host["Vc"][b][:L], host["Vp"][b][:L])).max()))
+        err = float(np.abs(out.cpu()[:n_active].double().numpy() - want).max())
+        assert err <= 2e-3 * maxv
+        seen.append(step)
+
+    res = sls_run.run_schedule(kind, B, S, F, n_steps, H=H, d=d, timed=False, on_step=on_step, kv=kv)
+    assert seen == list(range(n_steps)) and res["loads"] == want_loads and res["kv"] == kv
+
+
 @pytest.mark.parametrize("frac", [None, 0.7])
 def test_load_controlled_loop_matches_the_oracle_and_respects_the_limit(frac):
     """Micro-batches admitted by Algorithm 1 (free slots in between, released and reused): every
