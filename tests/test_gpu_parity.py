@@ -304,3 +304,18 @@ def test_step_can_be_captured_in_a_hip_graph_and_replayed():
         assert torch.equal(case.out, eager), rep
         assert case.cache.seq_lens.cpu().tolist() == [L + 1 for L in lens]
     assert rpart.fd_read_status(case.cache.desc) == 0
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_random_length_mixes(seed):
+    """Random ragged batches (empty, a few tokens, a few blocks, a few thousand tokens) under a
+    random chunk length: whatever mix of whole blocks, ragged rests and split sequences comes up."""
+    rng = np.random.default_rng(1000 + seed)
+    kinds = rng.integers(0, 4, size=14)
+    lens = [int(x) for x in np.where(kinds == 0, rng.integers(0, 3, 14),
+                                     np.where(kinds == 1, rng.integers(1, 41, 14),
+                                              np.where(kinds == 2, rng.integers(200, 901, 14),
+                                                       rng.integers(1000, 3001, 14))))]
+    chunk = int(rng.choice([0, 64, 96, 160, 512, 1000]))
+    case = DeviceCase(_cfg("rand%d" % seed, len(lens), 2, 128), lens, seed=50 + seed, chunk_tokens=chunk)
+    check_step(case)
