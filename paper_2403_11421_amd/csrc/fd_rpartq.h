@@ -197,10 +197,10 @@ template <> __device__ inline unsigned ld_buf<unsigned>(Rsrc r, unsigned voff, i
 // arithmetic per byte, and a second wave per SIMD is what hides it.
 // The 4-bit kernel takes twice the loads of half the size, so as many bytes are in flight.
 template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }   // wave loads per tile
-// Workgroups per compute unit.  8 bit: two when the sequences are long; the kernel (164 VGPRs)
+// Workgroups per compute unit.  8 bit: two when the sequences are long; the kernel (147 VGPRs)
 // fits a third one, which pays on short sequences (+5 % at 256 tokens per sequence, -5 % at
 // 2048), so the planner switches it on by the same rule as the fp16 kernel's second one.
-// 4 bit: always three (164 VGPRs, no spills).  Its units stream in a quarter of the fp16 kernel's time against the same fixed cost
+// 4 bit: always three (the 168-register budget, no spills).  Its units stream in a quarter of the fp16 kernel's time against the same fixed cost
 // per unit, and a third resident workgroup covers more of it: against two, 2049 tokens per
 // sequence +4 %, geometric mix +5.5 %, uniform 1..4096 +1.5 %, 256 each +2.4 %; uniform
 // 1..1024 -1.5 %, 16 sequences of 32768 -1.3 %, one of 131072 -3 %.
