@@ -116,6 +116,31 @@ def cpu_baseline(cfg, cache, vec, lens_after, n_sample):
     }
 
 
+def softmax_entropy(cfg, cache, vec, lens_after, n_sample=4):
+    """How peaked the attention of a config with per-head key spread really is: mean entropy (bits)
+    of softmax(q K^T / sqrt d) per spread class (head h has spread {1, 2, 4, 8}[h % 4]) over a few
+    sample sequences, next to log2 of their mean length (the entropy of uniform weights).
+    Plain torch on the cached fp16 rows; a description of the input, not part of the path."""
+    import math
+    import torch
+    ent = torch.zeros(4, dtype=torch.float64)
+    cnt = torch.zeros(4, dtype=torch.float64)
+    picks = list(range(0, cfg.B, max(1, cfg.B // n_sample)))[:n_sample]
+    for b in picks:
+        L = lens_after[b]
+        K = cache.block("K", b)[:, :L, :].float()                   # [H, L, d]
+        s = torch.einsum("hld,hd->hl", K, vec["q"][b].float()) / math.sqrt(cfg.d)
+        logp = torch.log_softmax(s.double(), dim=1)
+        e = -(logp.exp() * logp).sum(dim=1) / math.log(2.0)          # [H] bits
+        for c in range(4):
+            sel = e[c::4]
+            ent[c] += float(sel.sum())
+            cnt[c] += sel.numel()
+    mean_len = sum(lens_after[b] for b in picks) / len(picks)
+    return {"bits_by_spread_1_2_4_8": [float(x) for x in (ent / cnt)],
+            "uniform_bits_at_mean_length": math.log2(mean_len), "sequences": picks}
+
+
 def schedule_mode(args) -> int:
     """Per-step R-Part latency of a decode loop under the schedules of Section 4.2 (one layer,
     Llama-7B head shape): one JSON line per schedule."""
@@ -381,6 +406,8 @@ def main() -> int:
     torch.cuda.synchronize()
     res["roofline"]["read_only_ceiling_gbps"] = nread * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
 
+    if cfg.peaked_keys and not q8 and args.window == 0:
+        res["softmax_entropy"] = softmax_entropy(cfg, cache, vec, [L + 1 for L in lens])
     if args.cpu_sample > 0 and not q8 and args.window == 0:
         res["cpu_baseline"] = cpu_baseline(cfg, cache, vec, [L + 1 for L in lens], args.cpu_sample)
     print(json.dumps(res))
