@@ -23,28 +23,35 @@ if ROOT not in sys.path:
 METRIC = "R-Part decode attention: achieved KV HBM GB/s (% of peak) and sequences/sec"
 HBM_PEAK_GBPS = 8000.0
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "rpart_partial_hbm_traffic.json")
+TRAFFIC_JSON_Q = os.path.join(ROOT, "profiles", "rpartq_partial_hbm_traffic.json")
 KERNEL_SRC = os.path.join(ROOT, "paper_2403_11421_amd", "csrc", "fd_rpart.hip")
+KERNEL_SRC_Q = os.path.join(ROOT, "paper_2403_11421_amd", "csrc", "fd_rpartq.h")
 
 
-def kernel_fingerprint():
-    """sha256 of the fp16 kernels' source with comments and white space removed: it changes when
-    the code does, not when a comment is reworded."""
+def kernel_fingerprint(quantised=False):
+    """sha256 of the kernels' source with comments and white space removed: it changes when the
+    code does, not when a comment is reworded.  The quantised kernels include the fp16 file's
+    planner and helpers, so their fingerprint covers both files."""
     import hashlib
     import re
     src = open(KERNEL_SRC, encoding="utf-8").read()
+    if quantised:
+        src += open(KERNEL_SRC_Q, encoding="utf-8").read()
     src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
     src = re.sub(r"//[^\n]*", "", src)
     return hashlib.sha256(re.sub(r"\s+", "", src).encode()).hexdigest()
 
 
-def counter_traffic(config_name):
+def counter_traffic(config_name, kv="fp16"):
     """HBM bytes per launch of the dominant kernel as measured with rocprofv3 --pmc, or None
-    when no counters were taken for this config or the kernel code changed since."""
+    when no counters were taken for this config and cache format or the kernel code changed since."""
     try:
-        rec = json.load(open(TRAFFIC_JSON))
-        if rec.get("code_sha256") != kernel_fingerprint():
+        quantised = kv != "fp16"
+        rec = json.load(open(TRAFFIC_JSON_Q if quantised else TRAFFIC_JSON))
+        if rec.get("code_sha256") != kernel_fingerprint(quantised):
             return None
-        return rec["configs"][config_name]["traffic_bytes"]
+        node = rec["configs"][config_name]
+        return (node[kv] if quantised else node)["traffic_bytes"]
     except (OSError, KeyError, ValueError):
         return None
 
@@ -389,7 +396,7 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "rpartq_partial_kernel" if q8 else "rpart_partial_kernel",
                      "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "avg_kernel_ms": part_ms, "launches_timed": len(timed), "traffic": None if q8 else counter_traffic(cfg.name),
+                     "avg_kernel_ms": part_ms, "launches_timed": len(timed), "traffic": counter_traffic(cfg.name, args.kv) if args.window == 0 else None,
                      "algorithmic_bytes": kv_bytes},
     }
     # the device's pure-read ceiling, timed beside the kernel over the K slab (context for `frac`)
