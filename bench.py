@@ -65,9 +65,11 @@ def kv_bytes_per_token(cfg, kv):
     return 2 * cfg.H * (cfg.d + 4) if kv == "int8" else 2 * cfg.H * (cfg.d // 2 + 8)
 
 
-def build_case(cfg, lens, seed, chunk_tokens, growth=8, kv="fp16", window=0, sinks=0):
+def build_case(cfg, lens, seed, chunk_tokens, growth=8, kv="fp16", window=0, sinks=0, capacity=0):
     """window > 0: a windowed cache of sinks + window rows per sequence that has already seen
-    lens[b] tokens (its rows hold that many, or all of them when the history is longer)."""
+    lens[b] tokens (its rows hold that many, or all of them when the history is longer).
+    capacity > 0: every sequence gets a block of that many rows (equal slots, as a slot allocator
+    hands them out) instead of one fitted to its length."""
     import torch
     from paper_2403_11421_amd import workloads as W
     from paper_2403_11421_amd.kvcache import KVCache, KVCacheQ
@@ -79,7 +81,9 @@ def build_case(cfg, lens, seed, chunk_tokens, growth=8, kv="fp16", window=0, sin
         cache = cls(cfg.B, cfg.H, cfg.d, [sinks + window] * cfg.B, dev, chunk_tokens, n_sink=sinks, **kw)
         held = [min(L, sinks + window) for L in lens]
     else:
-        cache = cls(cfg.B, cfg.H, cfg.d, [L + growth for L in lens], dev, chunk_tokens, **kw)
+        caps = [capacity] * cfg.B if capacity > 0 else [L + growth for L in lens]
+        assert all(c > L for c, L in zip(caps, lens)), "capacity must exceed every cached length"
+        cache = cls(cfg.B, cfg.H, cfg.d, caps, dev, chunk_tokens, **kw)
         held = lens
     for b, L in enumerate(held):
         if L:
@@ -266,6 +270,8 @@ def main() -> int:
     ap.add_argument("--config", default="c2_7b_uniform")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--chunk-tokens", type=int, default=0, help="split-K chunk length, 0 = library's choice")
+    ap.add_argument("--capacity", type=int, default=0,
+                    help="rows of every sequence's cache block (equal slots); 0 = fitted to its length")
     ap.add_argument("--cpu-sample", type=int, default=96, help="sequences timed on the CPU oracle (0 = skip)")
     ap.add_argument("--kv", choices=["fp16", "int8", "int4"], default="fp16",
                     help="KV-cache format: fp16 (the headline path) or a quantised cache (Section 5.2)")
@@ -324,7 +330,7 @@ def main() -> int:
     f_partial = rpart.fd_rpartq_partial if q8 else rpart.fd_rpart_partial
     f_merge = rpart.fd_rpartq_merge if q8 else rpart.fd_rpart_merge
 
-    cache, vec = build_case(cfg, lens, seed, args.chunk_tokens, kv=args.kv, window=args.window,
+    cache, vec = build_case(cfg, lens, seed, args.chunk_tokens, kv=args.kv, capacity=args.capacity, window=args.window,
                             sinks=args.sinks)
     out = torch.empty_like(vec["q"])
     ws = cache.workspace(n_tok)

@@ -185,18 +185,21 @@ template <> __device__ inline u32x2 ld_buf<u32x2>(Rsrc r, unsigned voff, int sof
 {
     return __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, kAuxNt);
 }
-// The row parameters are read WITHOUT the non-temporal hint.  A wave asks for the 32 B (8 bit) or
-// 64 B (4 bit) of its eight tokens per load, the neighbouring waves for the rest of the same
-// memory line; cached, the later requests hit.  With the hint the counters showed the lines
-// fetched more than once (traffic 1.013 x and 1.031 x the algorithmic bytes), and dropping it
-// gave the 8-bit kernel +2 to +5 % and the 4-bit kernel +4 to +11 % on every workload.
+// The row parameters are read with the non-temporal hint like the codes.  A wave asks for the
+// 32 B (8 bit) or 64 B (4 bit) of its eight tokens per load and the neighbouring waves for the
+// rest of the same memory line, so part of the lines is fetched twice (counters: 1.013 x and
+// 1.031 x the algorithmic bytes).  Reading them cached removes that and looked 2-11 % faster
+// in a loop that repeats one layer's step, but only because the parameters (3-11 % of the
+// bytes) then survive in the memory-side cache from one step to the next; with other work
+// between the steps (cache lines dirtied by other kernels) the cached variant lost 7-26 %.
+// A cache that is streamed once per token of a many-layer model must not count on that.
 __device__ inline unsigned ld_meta32(Rsrc r, unsigned voff)
 {
-    return __builtin_amdgcn_raw_buffer_load_b32(r, voff, 0, 0);
+    return __builtin_amdgcn_raw_buffer_load_b32(r, voff, 0, kAuxNt);
 }
 __device__ inline u32x2 ld_meta64(Rsrc r, unsigned voff)
 {
-    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, 0, 0);
+    return __builtin_amdgcn_raw_buffer_load_b64(r, voff, 0, kAuxNt);
 }
 
 // Tile size and residency, measured on MI355X over the two-block rolling prefetch below (8-bit
@@ -237,10 +240,14 @@ struct TileQ {
     static constexpr int LPR = 8;                        // lanes per row
     static constexpr int RPW = 8;                        // rows (tokens) per wave load
     static constexpr int EPL = D / LPR;                  // elements per lane
-    static constexpr int STRIDE = WPU * 64 * LB;         // bytes between a wave's consecutive loads
-    static constexpr int TSTEP = WPU * RPW;              // tokens between a wave's consecutive loads
-    static constexpr int BLK_TOK = NL * TSTEP;           // tokens per workgroup block
-    static constexpr int BLK_BYTES = NL * STRIDE;        // bytes of K (or V) codes per block
+    // A wave's NL loads of a block are consecutive: it owns NL * RPW consecutive tokens, so the
+    // row parameters it needs are one contiguous 64 B (8 bit) or 256 B (4 bit) run and no other
+    // wave asks for a part of the same run.  (With the waves interleaved load by load, a wave's
+    // parameters came in 32 B / 64 B pieces of memory lines that its neighbours fetched again.)
+    static constexpr int STRIDE = 64 * LB;               // bytes between a wave's consecutive loads
+    static constexpr int TSTEP = RPW;                    // tokens between a wave's consecutive loads
+    static constexpr int BLK_TOK = NL * WPU * RPW;       // tokens per workgroup block
+    static constexpr int BLK_BYTES = NL * WPU * 64 * LB; // bytes of K (or V) codes per block
     static_assert(NL * RPW <= 64, "one lane per token of the tile for the row parameters");
     typedef typename CodeVec<BITS>::type CV;
     CV k[NL], v[NL];
@@ -249,7 +256,13 @@ struct TileQ {
     // token (inside a block) whose parameters lane `lane` of wave `wave` loads
     __device__ static inline int own_token(int lane, int wave)
     {
-        return (((lane / RPW) % NL) * WPU + wave) * RPW + (lane % RPW);
+        return first_token(wave) + lane % (NL * RPW);
+    }
+    // first token (inside a block) of the wave's run, and the byte offset of a lane's part of load 0
+    __device__ static inline int first_token(int wave) { return wave * NL * RPW; }
+    __device__ static inline unsigned lane_offset(int lane, int wave)
+    {
+        return (unsigned)((wave * NL * 64 + lane) * LB);
     }
 
     // mo4 = byte offset of this lane's token in the parameter stream
@@ -506,7 +519,7 @@ __device__ __forceinline__ void rpartq_body(
     float qscale)
 {
     using T = TileQ<BITS, q_tile_loads<BITS>(), WPU>;
-    constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL, RB = T::RB, MW = T::MW, LB = T::LB;
+    constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL, RB = T::RB, MW = T::MW;
     // two sets, used by alternate units, so that one barrier per unit is enough
     __shared__ float sm_acc2[2][kWaves][D];
     __shared__ float sm_m2[2][kWaves], sm_l2[2][kWaves], sm_aux2[2][kWaves];
@@ -517,7 +530,6 @@ __device__ __forceinline__ void rpartq_body(
     const int tid = wave * 64 + lane;                            // thread index among them
     const int row = lane / LPR;
     const int col = lane % LPR;
-    const int tok0 = wave * T::RPW + row;                  // this lane's token in a block, load 0
     const int own = T::own_token(lane, wave);              // token whose parameters this lane loads
     const int n_units = hdr[HDR_NITEMS] * H;
     // workers (workgroups, or single waves) that the planner's grid amounts to, and this one
@@ -581,7 +593,7 @@ __device__ __forceinline__ void rpartq_body(
         const char *vp = v_codes + row0 * RB;
         const float *kmp = k_meta + row0 * MW;
         const float *vmp = v_meta + row0 * MW;
-        const unsigned co = (unsigned)(tid * LB);               // wave w starts at its own slot
+        const unsigned co = T::lane_offset(lane, wave);         // wave w starts at its own run
         const unsigned mo = (unsigned)(own * MW);
 
         // the query stays fp16 for the dot instruction; its scale (log2 e / sqrt d) and the 2^24
@@ -671,15 +683,17 @@ __device__ __forceinline__ void rpartq_body(
         {
             using T1 = TileQ<BITS, 1, WPU>;
             const unsigned mo1 = (unsigned)(T1::own_token(lane, wave) * MW);
+            const unsigned co1 = T1::lane_offset(lane, wave);
+            const int tok1 = T1::first_token(wave) + row;
             for (int t0 = 0; t0 < rem; t0 += T1::BLK_TOK) {
                 const int r1 = min(rem - t0, T1::BLK_TOK);
-                if (wave * T::RPW < r1) {                  // this wave has at least one valid row
+                if (T1::first_token(wave) < r1) {          // this wave has at least one valid row
                     const int64_t o = (int64_t)n_blk * T::BLK_BYTES + (int64_t)t0 * RB;
                     const int64_t so = (int64_t)n_blk * MSTEP + (int64_t)t0 * MW;
                     T1 C;
-                    C.load_tail(kp + o, vp + o, kmp + so, vmp + so, co, mo1, tok0,
+                    C.load_tail(kp + o, vp + o, kmp + so, vmp + so, co1, mo1, tok1,
                                 T1::own_token(lane, wave), r1);
-                    C.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row, tok0, r1);
+                    C.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row, tok1, r1);
                 }
             }
         }
