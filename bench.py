@@ -270,6 +270,10 @@ def main() -> int:
     ap.add_argument("--config", default="c2_7b_uniform")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--chunk-tokens", type=int, default=0, help="split-K chunk length, 0 = library's choice")
+    ap.add_argument("--flush-mib", type=int, default=0,
+                    help="before every step, read-modify-write this many MiB through the caches (other work "
+                         "between two steps of a layer, as in a model of many layers); the step time is then "
+                         "the sum of HIP-event times around the steps, not the wall clock")
     ap.add_argument("--capacity", type=int, default=0,
                     help="rows of every sequence's cache block (equal slots); 0 = fitted to its length")
     ap.add_argument("--cpu-sample", type=int, default=96, help="sequences timed on the CPU oracle (0 = skip)")
@@ -364,14 +368,26 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    flush = torch.zeros(args.flush_mib << 20, dtype=torch.uint8, device="cuda") if args.flush_mib > 0 else None
+    step_ev = []
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        step(ev[k])
+        if flush is not None:                      # cold caches: time the step alone, by events
+            flush.add_(1)
+            se = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            se[0].record()
+            step(ev[k])
+            se[1].record()
+            step_ev.append(se)
+        else:
+            step(ev[k])
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    if flush is not None:
+        dt = sum(a.elapsed_time(b) for a, b in step_ev) * 1e-3
 
     assert rpart.fd_read_status(desc) == 0
     plan = rpart.fd_plan_info(ws)
@@ -395,6 +411,7 @@ def main() -> int:
                                   if args.window > 0 else ""),
                    "B": cfg.B, "H": cfg.H, "d": cfg.d, "total_tokens": n_tok,
                    "kv_bytes_per_step": kv_bytes, "seed": seed, "plan": plan},
+        "flush_mib_between_steps": args.flush_mib,
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "seq_per_s": cfg.B / (ms_step * 1e-3),
         "seq_per_s_whole_model": cfg.B / (ms_step * 1e-3) / cfg.n_layers,
