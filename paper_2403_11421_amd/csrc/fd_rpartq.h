@@ -227,7 +227,7 @@ constexpr int kQSplit = 4;          // a sequence is cut when longer than 1/4 of
 template <int BITS> constexpr int q_wave_units() { return BITS == 4 ? 1 : 0; }
 
 // WPU = waves that share a unit: kWaves (the workgroup streams one (sequence, head) together,
-// its waves interleaved at one wave load) or 1 (every wave streams a unit of its own).
+// wave w the w-th quarter of every block) or 1 (every wave streams a unit of its own).
 template <int BITS, int NL_, int WPU>
 struct TileQ {
     using F = QFmt<BITS>;
