@@ -871,19 +871,16 @@ int block_tokens(int d) { return kWaves * kTileLoads * (d == 128 ? 4 : 8); }
 // chunk boundaries are multiples of this many tokens (one wave load of rows)
 int chunk_granule(int d) { return d == 128 ? 32 : 64; }
 
-// Compute units of the current device.  The streaming kernels are launched with two
-// workgroups per CU; the planner decides whether the second one takes part.
+// Compute units of the current device, asked for at every call: the library keeps no state
+// between calls, and a process may use several devices.  The streaming kernels are launched
+// with two (or three) workgroups per CU; the planner decides how many take part.
 int persistent_grid()
 {
-    static int grid = 0;
-    if (grid == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-            return 0;
-        grid = cus;
-    }
-    return grid;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+        return 0;
+    return cus;
 }
 
 int launched(void) { return hipGetLastError() == hipSuccess ? FD_OK : FD_EHIP; }
