@@ -38,6 +38,7 @@ extern "C" {
 #define FD_EINVAL     (-1)  /* null/misaligned pointer, B<0, H<=0, d not in {64,128}, bad chunk_tokens */
 #define FD_EWORKSPACE (-2)  /* workspace smaller than fd_workspace_bytes(B,H,d,0)               */
 #define FD_EHIP       (-3)  /* a HIP runtime call or kernel launch failed                        */
+#define FD_ETOOBIG    (-4)  /* fd_rpart_decode_noalloc: the batch needs more than the built-in scratch */
 
 #define FD_ST_CAPACITY 1    /* append skipped for a sequence whose cache is full                 */
 #define FD_ST_BADLEN   2    /* a seq_lens entry was outside [0, seq_cap]; it was clamped         */
@@ -155,6 +156,27 @@ int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
                      void *workspace, size_t workspace_bytes, void *stream);
 int fd_rpart_merge(const fd_kv_desc *desc, void *out,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * fd_rpart_decode for callers that cannot allocate device memory or hand over a workspace:
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  Same inputs, outputs, semantics and kernels as fd_rpart_decode, but the plan
+ * tables and split-K chunk states live in an array of FD_NOALLOC_SCRATCH_BYTES that is part
+ * of the library's device code (every GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates and frees nothing.
+ *   - Returns FD_ETOOBIG, before anything is enqueued, when the array cannot hold the tables
+ *     and one chunk state per sequence, i.e. when fd_workspace_bytes(B, H, d, 0) exceeds
+ *     FD_NOALLOC_SCRATCH_BYTES (B * H * (d + 2) * 4 bytes, roughly: B * H <= 129 000 at
+ *     d = 128).  With less room than fd_workspace_bytes(B, H, d, tokens) the planner uses
+ *     longer chunks, as for any small workspace.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on one GPU (two
+ *     streams, two threads) race and must be ordered by the caller.  The array keeps the
+ *     previous call's contents; nothing in it needs clearing between calls.
+ *   - The first call on a device looks the array's address up (a host-side query, no stream
+ *     work); make it once before starting a graph capture.
+ */
+#define FD_NOALLOC_SCRATCH_BYTES (64u << 20)
+int fd_rpart_decode_noalloc(const fd_kv_desc *desc, const void *q, void *out, void *stream);
 
 /* fd_kv_append followed by fd_rpart_decode (one R-worker step of Section 4.1). */
 int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, const void *v_new,

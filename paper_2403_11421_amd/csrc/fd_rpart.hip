@@ -18,6 +18,13 @@
 
 #include "fastdecode_rpart.h"
 
+// ---------------------------------------------------------------------------
+// Built-in scratch for the entry point that allocates nothing.  The array lives in every
+// device's copy of the code object; host code must not use its name as an address (that is a
+// host-side stand-in): the device address is asked for once per device and kept.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[FD_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr int kVersion = 100;          // 0.1.0
@@ -885,6 +892,26 @@ int persistent_grid()
 
 int launched(void) { return hipGetLastError() == hipSuccess ? FD_OK : FD_EHIP; }
 
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];          // device address of `scratch` on device i, or null
+
+// Address of the current device's scratch array; null on failure.  The first call on a device
+// looks the symbol up with that device current; later calls return the kept address.  Two
+// threads racing through the first call both obtain the same address.
+void *scratch_address()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+    return p;
+}
+
 } // namespace
 
 extern "C" {
@@ -903,6 +930,7 @@ const char *fd_strerror(int code)
     case FD_EINVAL: return "invalid argument (null or misaligned pointer, bad shape)";
     case FD_EWORKSPACE: return "workspace too small";
     case FD_EHIP: return "HIP runtime call or kernel launch failed";
+    case FD_ETOOBIG: return "batch too large for the built-in scratch of the no-allocation entry point";
     default: return "unknown error code";
     }
 }
@@ -1053,6 +1081,22 @@ int fd_rpart_decode(const fd_kv_desc *desc, const void *q, void *out,
     rc = fd_rpart_partial(desc, q, out, workspace, workspace_bytes, stream);
     if (rc != FD_OK) return rc;
     return fd_rpart_merge(desc, out, workspace, workspace_bytes, stream);
+}
+
+int fd_rpart_decode_noalloc(const fd_kv_desc *desc, const void *q, void *out, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
+    // the plan tables and one chunk state per sequence must fit the fixed array
+    const WsLayout w = ws_layout(desc->B, desc->H, desc->d, FD_NOALLOC_SCRATCH_BYTES);
+    if (w.max_items < desc->B) return FD_ETOOBIG;
+    void *ws = scratch_address();
+    if (!ws) return FD_EHIP;
+    // nothing in the array has to start at zero: the planner rewrites the header and every
+    // table entry the other kernels read, and chunk states are written before they are merged
+    return fd_rpart_decode(desc, q, out, ws, FD_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, const void *v_new,

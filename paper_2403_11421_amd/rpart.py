@@ -14,7 +14,8 @@ import torch
 
 from . import build as _build
 
-FD_OK, FD_EINVAL, FD_EWORKSPACE, FD_EHIP = 0, -1, -2, -3
+FD_OK, FD_EINVAL, FD_EWORKSPACE, FD_EHIP, FD_ETOOBIG = 0, -1, -2, -3, -4
+FD_NOALLOC_SCRATCH_BYTES = 64 << 20
 FD_ST_CAPACITY, FD_ST_BADLEN, FD_ST_WINDOW, FD_ST_PLAN = 1, 2, 4, 8
 FD_SLOT_FREE = -1
 
@@ -77,6 +78,8 @@ def load() -> ctypes.CDLL:
     lib.fd_kv_append.argtypes = [P, _vp, _vp, _vp]
     lib.fd_rpart_decode.restype = ctypes.c_int
     lib.fd_rpart_decode.argtypes = [P, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.fd_rpart_decode_noalloc.restype = ctypes.c_int
+    lib.fd_rpart_decode_noalloc.argtypes = [P, _vp, _vp, _vp]
     lib.fd_rpart_plan.restype = ctypes.c_int
     lib.fd_rpart_plan.argtypes = [P, _vp, ctypes.c_size_t, _vp]
     lib.fd_rpart_partial.restype = ctypes.c_int
@@ -119,7 +122,7 @@ EXPORTS = ("fd_version", "fd_desc_size", "fd_strerror", "fd_workspace_bytes", "f
            "fd_read_status", "fd_plan_info", "fd_hbm_read_probe",
            "fd_kvq_append", "fd_kvq_reset", "fd_rpartq_plan", "fd_rpartq_partial", "fd_rpartq_merge",
            "fd_rpartq_decode", "fd_rpartq_step", "fd_rpart_layer_step", "fd_rpartq_layer_step",
-           "fd_kv_release", "fd_kvq_release")
+           "fd_kv_release", "fd_kvq_release", "fd_rpart_decode_noalloc")
 
 
 def version() -> int:
@@ -161,6 +164,12 @@ def fd_rpart_decode(desc: fd_kv_desc, q: torch.Tensor, out: torch.Tensor,
     p, n = _ws(workspace)
     _check(load().fd_rpart_decode(ctypes.byref(desc), _ptr(q), _ptr(out), p, n, _stream()),
            "fd_rpart_decode")
+
+
+def fd_rpart_decode_noalloc(desc: fd_kv_desc, q: torch.Tensor, out: torch.Tensor) -> None:
+    """fd_rpart_decode on the library's built-in scratch array (no workspace, no allocation)."""
+    _check(load().fd_rpart_decode_noalloc(ctypes.byref(desc), _ptr(q), _ptr(out), _stream()),
+           "fd_rpart_decode_noalloc")
 
 
 def fd_rpart_plan(desc: fd_kv_desc, workspace: torch.Tensor) -> None:
