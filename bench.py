@@ -281,7 +281,7 @@ def main() -> int:
                     help="KV-cache format: fp16 (the headline path) or a quantised cache (Section 5.2)")
     ap.add_argument("--sched-wlim", type=int, default=0,
                     help="--schedule control: load limit W_lim of Algorithm 1 in cached tokens "
-                         "(0 = Eq. 6's peak plus one step of slack)")
+                         "(0 = Eq. 6's peak)")
     ap.add_argument("--schedule", choices=["none", "batch", "sls", "control", "both"], default="none",
                     help="instead of the fixed-length step, run a multi-step decode loop under the "
                          "large-batch or the load-stabilising schedule (Section 4.2) and report the "

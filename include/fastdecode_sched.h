@@ -43,11 +43,14 @@ int fd_batch_step_loads(int64_t B, int64_t S, int64_t n_steps, int64_t *loads);
  *   fd_lc_add_microbatch(t, m): records a micro-batch of m sequences started at step t:
  *       appends (m, t+S, m*S) and adds (E[i]-t)*m to W[i] of every micro-batch that
  *       existed before the call (the new one's length at their last step).
- *   fd_lc_earliest_step(t, m): the paper's GetEarliestStep: r = t; for every current
- *       micro-batch x = floor((W_lim - W[i]) / m), r = max(r, E[i] - x + 1).  Under the step
- *       convention above this is safe and at most one step later than the exact minimum
- *       E[i] - x.  Micro-batches whose W[i] already exceeds W_lim give x < 0 and push r
- *       past their end.
+ *   fd_lc_earliest_step(t, m): GetEarliestStep: the smallest step r >= t at which a
+ *       micro-batch of m sequences can start without pushing any W[i] over W_lim.  A start at
+ *       r < E[i] adds m * (E[i] - r) to W[i], so with x = floor((W_lim - W[i]) / m) the bound
+ *       is r >= E[i] - max(x, 0), taken over the current micro-batches.  (The paper's listing
+ *       prints E[i] - x + 1, the bound for an E[i] that is the last step itself; with
+ *       E[i] = start + S as AddMicroBatch sets it, that is one step later than the load
+ *       definition of Figure 7 requires.)  FD_EINVAL if t < 0 or if m * S alone exceeds
+ *       W_lim, in which case no step is ever admissible.
  *   fd_lc_retire(t): forgets micro-batches with E[i] <= t ("current" means still running).
  * The handle is host memory owned by the library until fd_lc_destroy.
  */
@@ -60,6 +63,20 @@ int64_t fd_lc_retire(fd_load_ctl *lc, int64_t t);
 int64_t fd_lc_count(const fd_load_ctl *lc);
 /* Copies up to `n` entries of (M[i], E[i], W[i]) into the caller's arrays; returns the count. */
 int64_t fd_lc_snapshot(const fd_load_ctl *lc, int64_t n, int64_t *M, int64_t *E, int64_t *W);
+
+/*
+ * The admission loop of Algorithm 1's driver, start to finish, for micro-batches of M
+ * sequences that arrive every F steps (Eq. 5's schedule) on an R-worker with room for B
+ * sequences (B / M groups of slots, B a multiple of M; a group is busy for S steps):
+ * arrivals wait in order; at every step 0 .. n_steps-1 the one at the head starts if a group
+ * of slots is free and fd_lc_earliest_step allows that step, at most one start per step.
+ * Writes the start steps, in order, to starts[0 .. min(count, max_starts)) (host array owned
+ * by the caller) and returns the count.  With W_lim >= Eq. 6's peak every micro-batch starts
+ * on arrival (the fixed-interval schedule of Figure 7); with a tighter limit starts are held
+ * back and the load never exceeds it.
+ */
+int64_t fd_lc_controlled_starts(int64_t B, int64_t S, int64_t M, int64_t F, int64_t W_lim,
+                                int64_t n_steps, int64_t *starts, int64_t max_starts);
 
 /*
  * Slot bookkeeping for an R-worker with room for B sequences (Section 4.1: the cache of a

@@ -6,6 +6,11 @@ step.  It shares no code with the library's scheduler.
 
 Conventions (fixed by the worked example of Figure 7): a sequence started at step t has length
 s - t + 1 at step s and lives for S steps (s = t .. t+S-1), so its last step carries length S.
+
+Pins (tests/test_sched.py): `step_loads` against the arrays and peaks printed with Figure 7 and
+against Eq. 6's closed form; `earliest_start_brute_force` against cases worked by hand from the
+figure's example (tests/golden/alg1_earliest_start.txt); the Section 4.3 functions against
+hand-worked numbers and the simulated schedule's mean load.
 """
 from __future__ import annotations
 

@@ -88,17 +88,47 @@ int fd_lc_add_microbatch(fd_load_ctl *lc, int64_t t, int64_t m)
 
 int64_t fd_lc_earliest_step(const fd_load_ctl *lc, int64_t t, int64_t m)
 {
-    if (!lc || m <= 0) return FD_EINVAL;
+    if (!lc || m <= 0 || t < 0) return FD_EINVAL;
+    if (m > lc->W_lim / lc->S) return FD_EINVAL;             // m*S alone exceeds the limit: never admissible
+    // A micro-batch of m sequences started at step r < E[i] is E[i] - r tokens long at the last
+    // step E[i] - 1 of micro-batch i, so it adds m * (E[i] - r) to W[i].  Keeping
+    // W[i] + m * (E[i] - r) <= W_lim means E[i] - r <= x with x = floor((W_lim - W[i]) / m),
+    // i.e. r >= E[i] - x; with no room at all (x <= 0) the start has to wait until i has ended.
     int64_t r = t;
     for (size_t i = 0; i < lc->M.size(); ++i) {
         if (lc->E[i] <= t) continue;                          // already finished: not current
         const int64_t margin = lc->W_lim - lc->W[i];
-        // floor division (margin may be negative)
-        int64_t x = margin / m;
+        int64_t x = margin / m;                               // floor division (margin may be negative)
         if (margin % m != 0 && margin < 0) --x;
-        r = std::max(r, lc->E[i] - x + 1);
+        r = std::max(r, lc->E[i] - std::max<int64_t>(x, 0));
     }
     return r;
+}
+
+int64_t fd_lc_controlled_starts(int64_t B, int64_t S, int64_t M, int64_t F, int64_t W_lim,
+                                int64_t n_steps, int64_t *starts, int64_t max_starts)
+{
+    if (B <= 0 || S <= 0 || M <= 0 || F <= 0 || W_lim <= 0 || n_steps < 0 || max_starts < 0 ||
+        (max_starts > 0 && !starts) || B % M != 0 || M > W_lim / S)
+        return FD_EINVAL;
+    fd_load_ctl lc;
+    lc.S = S;
+    lc.W_lim = W_lim;
+    std::vector<int64_t> free_at((size_t)(B / M), 0);         // step from which a group of M slots is free
+    int64_t waiting = 0, n = 0;
+    for (int64_t t = 0; t < n_steps; ++t) {
+        if (t % F == 0) ++waiting;                            // a micro-batch arrives
+        fd_lc_retire(&lc, t);
+        const size_t g = (size_t)(std::min_element(free_at.begin(), free_at.end()) - free_at.begin());
+        if (waiting > 0 && free_at[g] <= t && fd_lc_earliest_step(&lc, t, M) <= t) {
+            fd_lc_add_microbatch(&lc, t, M);
+            free_at[g] = t + S;
+            if (n < max_starts) starts[n] = t;
+            ++n;
+            --waiting;
+        }
+    }
+    return n;
 }
 
 int64_t fd_lc_retire(fd_load_ctl *lc, int64_t t)

@@ -37,6 +37,8 @@ def _lib():
         lib.fd_lc_count.argtypes = [ctypes.c_void_p]
         lib.fd_lc_snapshot.restype = _i64
         lib.fd_lc_snapshot.argtypes = [ctypes.c_void_p, _i64, P, P, P]
+        lib.fd_lc_controlled_starts.restype = _i64
+        lib.fd_lc_controlled_starts.argtypes = [_i64] * 6 + [P, _i64]
         lib.fd_slots_create.restype = ctypes.c_void_p
         lib.fd_slots_create.argtypes = [ctypes.c_int32]
         lib.fd_slots_destroy.restype = None
@@ -64,7 +66,7 @@ def _lib():
 
 EXPORTS = ("fd_sls_microbatch_size", "fd_sls_peak_load", "fd_sls_step_loads", "fd_batch_step_loads",
            "fd_lc_create", "fd_lc_destroy", "fd_lc_add_microbatch", "fd_lc_earliest_step",
-           "fd_lc_retire", "fd_lc_count", "fd_lc_snapshot",
+           "fd_lc_retire", "fd_lc_count", "fd_lc_snapshot", "fd_lc_controlled_starts",
            "fd_model_sequence_latency", "fd_model_max_batch", "fd_model_sworker_throughput",
            "fd_model_min_rworkers_memory", "fd_model_num_rworkers",
            "fd_slots_create", "fd_slots_destroy", "fd_slots_acquire", "fd_slots_release",
@@ -116,10 +118,7 @@ class LoadControl:
         _ok(_lib().fd_lc_add_microbatch(self._h, t, m), "fd_lc_add_microbatch")
 
     def earliest_step(self, t: int, m: int) -> int:
-        lib = _lib()
-        if m <= 0:
-            raise rpart.FdError(rpart.FD_EINVAL, "fd_lc_earliest_step")
-        return int(lib.fd_lc_earliest_step(self._h, t, m))
+        return _ok(_lib().fd_lc_earliest_step(self._h, t, m), "fd_lc_earliest_step")
 
     def retire(self, t: int) -> int:
         return _ok(_lib().fd_lc_retire(self._h, t), "fd_lc_retire")
@@ -132,6 +131,14 @@ class LoadControl:
         M, E, W = ((_i64 * max(1, n))() for _ in range(3))
         c = _ok(_lib().fd_lc_snapshot(self._h, n, M, E, W), "fd_lc_snapshot")
         return [(M[i], E[i], W[i]) for i in range(c)]
+
+
+def controlled_starts(B: int, S: int, M: int, F: int, W_lim: int, n_steps: int) -> List[int]:
+    """Start steps of the micro-batches admitted by Algorithm 1's driver (fd_lc_controlled_starts)."""
+    cap = max(1, n_steps)
+    buf = (_i64 * cap)()
+    n = _ok(_lib().fd_lc_controlled_starts(B, S, M, F, W_lim, n_steps, buf, cap), "fd_lc_controlled_starts")
+    return list(buf)[:n]
 
 
 # ---------------------------------------------------------------------------

@@ -35,29 +35,9 @@ def step_vectors(cfg: W.RPartConfig, which: str, step: int, seed: int, device) -
 
 
 def controlled_starts(B: int, S: int, M: int, F: int, W_lim: int, n_steps: int) -> List[int]:
-    """Start steps of micro-batches of M sequences under Algorithm 1's load control.  A
-    micro-batch arrives every F steps (the load-stabilising schedule's interval) and waits in
-    arrival order; at every step the one at the head starts (`AddMicroBatch`) if a group of M
-    slots is free and `GetEarliestStep` allows it, at most one per step.  B // M groups of
-    slots exist; a group is busy for S steps.  Host logic only (the library's scheduler);
-    returns the start step of every micro-batch in order."""
-    assert B % M == 0
-    lc = sched.LoadControl(S, W_lim)
-    free_at = [0] * (B // M)                            # step from which each group is free again
-    starts: List[int] = []
-    waiting = 0
-    for t in range(n_steps):
-        if t % F == 0:
-            waiting += 1
-        lc.retire(t)
-        g = min(range(len(free_at)), key=lambda i: free_at[i])
-        if waiting and free_at[g] <= t and lc.earliest_step(t, M) <= t:
-            lc.add_microbatch(t, M)
-            free_at[g] = t + S
-            starts.append(t)
-            waiting -= 1
-    lc.close()
-    return starts
+    """Start steps of micro-batches of M sequences under Algorithm 1's load control: the
+    library's admission loop (`fd_lc_controlled_starts`)."""
+    return sched.controlled_starts(B, S, M, F, W_lim, n_steps)
 
 
 def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 128,
@@ -67,7 +47,7 @@ def run_schedule(kind: str, B: int, S: int, F: int, n_steps: int, H: int = 32, d
     """kind = "sls": micro-batches of M = B*F/S sequences every F steps (Eq. 5);
     kind = "batch": all B sequences together, the next batch when they finish;
     kind = "control": micro-batches of M = B*F/S sequences admitted by Algorithm 1 under the
-    load limit W_lim (default: Eq. 6's peak plus one step of slack), see `run_controlled`.
+    load limit W_lim (default: Eq. 6's peak), see `run_controlled`.
 
     Sequence slots are reused round-robin; a micro-batch's slots are reset when it starts.
     During the cold start only the slots started so far take part (a prefix of the slots).
@@ -128,8 +108,8 @@ def run_controlled(B: int, S: int, F: int, n_steps: int, H: int = 32, d: int = 1
     on_step(step, cache, q, k_new, v_new, out, live_slots) is called after each step (tests)."""
     cfg = W.RPartConfig(f"control_B{B}_S{S}_F{F}", B, H, d, "const", 0, 0)
     M = sched.sls_microbatch_size(B, F, S)
-    if W_lim is None:                                   # Eq. 6's peak plus the one step of slack that
-        W_lim = sched.sls_peak_load(M, F, S) + M        # the printed GetEarliestStep needs
+    if W_lim is None:                                   # Eq. 6's peak: nothing is held back
+        W_lim = sched.sls_peak_load(M, F, S)
     starts = controlled_starts(B, S, M, F, W_lim, n_steps)
     dev = torch.device(device)
     cache, step_fn, reset_fn = _make_cache(kv, B, H, d, S, dev)

@@ -12,6 +12,19 @@ from oracle import sls_oracle as O
 from paper_2403_11421_amd import rpart, sched
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "fig7_loads.txt")
+GOLD_ALG1 = os.path.join(os.path.dirname(__file__), "golden", "alg1_earliest_start.txt")
+
+
+def _alg1_cases():
+    """(S, W_lim, t, m, expected, existing micro-batches) of the hand-worked cases."""
+    out = []
+    for line in open(GOLD_ALG1):
+        if line.startswith("#") or not line.strip():
+            continue
+        p = line.split()
+        S, W_lim, t, m, want = (int(x) for x in p[:5])
+        out.append((S, W_lim, t, m, want, [tuple(int(y) for y in x.split(":")) for x in p[5:]]))
+    return out
 
 
 def _gold():
@@ -121,9 +134,29 @@ def test_figure7_steady_state_is_admissible_at_the_eq6_limit():
     assert max(O.step_loads(starts, S, 20 + S)) == W_lim
 
 
-def test_earliest_step_is_safe_and_at_most_one_step_late():
+def test_oracle_earliest_start_matches_the_hand_worked_cases():
+    """The brute-force search itself, before it judges the library: cases worked on paper from
+    Figure 7's load definition (tests/golden/alg1_earliest_start.txt)."""
+    cases = _alg1_cases()
+    assert len(cases) >= 10
+    for S, W_lim, t, m, want, existing in cases:
+        assert O.earliest_start_brute_force(existing, S, W_lim, t, m, horizon=t + 4 * S) == want
+
+
+def test_library_earliest_step_matches_the_hand_worked_cases():
+    for S, W_lim, t, m, want, existing in _alg1_cases():
+        lc = sched.LoadControl(S, W_lim)
+        for t0, mm in existing:
+            lc.add_microbatch(t0, mm)
+        lc.retire(t)
+        assert lc.earliest_step(t, m) == want, (S, W_lim, t, m, existing)
+        lc.close()
+
+
+def test_earliest_step_is_exact_and_the_printed_rule_is_one_step_later():
     rng = random.Random(5)
-    for trial in range(200):
+    n_printed_late = 0
+    for trial in range(300):
         S = rng.randint(3, 12)
         W_lim = rng.randint(S * 4, S * 30)
         lc = sched.LoadControl(S, W_lim)
@@ -142,11 +175,33 @@ def test_earliest_step_is_safe_and_at_most_one_step_late():
         r = lc.earliest_step(t, m)
         current = [(t0, mm) for t0, mm in starts if t0 + S > t]
         exact = O.earliest_start_brute_force(current, S, W_lim, t, m, horizon=t + 4 * S)
-        assert exact <= r <= exact + 1, (trial, S, W_lim, starts, t, m, r, exact)
-        # starting at r keeps every guarded peak within the limit
+        assert r == exact, (trial, S, W_lim, starts, t, m, r, exact)
+        # starting at r keeps every guarded peak within the limit, one step earlier does not
         loads = O.step_loads(starts + [(r, m)], S, r + 2 * S)
         for t0, _ in current:
             assert loads[t0 + S - 1] <= W_lim
+        if r > t:
+            early = O.step_loads(starts + [(r - 1, m)], S, r + 2 * S)
+            assert any(early[t0 + S - 1] > W_lim for t0, _ in current if t0 + S - 1 >= r - 1)
+        # the rule as the paper's listing prints it, from the same bookkeeping: never earlier,
+        # at most one step later
+        printed = t
+        for mm, e, w in lc.snapshot():
+            printed = max(printed, e - (W_lim - w) // m + 1)
+        assert r <= printed <= max(r + 1, t + 1)
+        n_printed_late += printed > r
+    assert n_printed_late > 10
+
+
+def test_earliest_step_rejects_a_microbatch_that_can_never_fit():
+    lc = sched.LoadControl(6, 23)                             # 4 sequences of 6 tokens are 24
+    assert lc.earliest_step(0, 3) == 0
+    with pytest.raises(rpart.FdError):
+        lc.earliest_step(0, 4)
+    with pytest.raises(rpart.FdError):
+        lc.earliest_step(-1, 1)
+    with pytest.raises(rpart.FdError):
+        lc.earliest_step(0, 0)
 
 
 def test_retire_forgets_finished_microbatches():
@@ -260,36 +315,59 @@ def test_slots_random_walk_never_duplicates():
 # ---------------------------------------------------------------------------
 @pytest.mark.parametrize("B,S,F", [(6, 6, 2), (12, 12, 3), (32, 16, 4)])
 def test_controlled_starts_at_the_eq6_limit_reproduce_the_fixed_interval_schedule(B, S, F):
-    """With one step of slack over Eq. 6's peak (the printed GetEarliestStep is one step
-    conservative) nothing is ever held back: every micro-batch starts the step it arrives, which
-    is the fixed-interval schedule of Figure 7; at exactly the peak the printed rule delays some."""
-    from paper_2403_11421_amd import sls_run
+    """At Eq. 6's peak nothing is ever held back: every micro-batch starts the step it arrives,
+    which is the fixed-interval schedule of Figure 7; one token below the peak some are."""
     M = B * F // S
     peak = sched.sls_peak_load(M, F, S)
     n = 6 * S
-    starts = sls_run.controlled_starts(B, S, M, F, peak + M, n)
+    starts = sched.controlled_starts(B, S, M, F, peak, n)
     assert starts == list(range(0, n, F))
     loads = O.step_loads([(t, M) for t in starts], S, n)
     assert max(loads) == peak and loads == sched.sls_step_loads(M, F, S, n)
-    late = sls_run.controlled_starts(B, S, M, F, peak, n)
-    assert late != starts and max(O.step_loads([(t, M) for t in late], S, n)) <= peak
+    late = sched.controlled_starts(B, S, M, F, peak - 1, n)
+    assert late != starts and max(O.step_loads([(t, M) for t in late], S, n)) <= peak - 1
+
+
+def _controlled_starts_by_hand(B, S, M, F, W_lim, n_steps):
+    """The admission loop written out with the brute-force search: arrivals every F steps wait
+    in order; the head starts at the first step at which a group of slots is free and the
+    search over the load definition allows it; one start per step."""
+    free_at = [0] * (B // M)
+    starts, waiting = [], 0
+    for t in range(n_steps):
+        waiting += t % F == 0
+        g = min(range(len(free_at)), key=lambda i: free_at[i])
+        current = [(t0, M) for t0 in starts if t0 + S > t]
+        if waiting and free_at[g] <= t and O.earliest_start_brute_force(current, S, W_lim, t, M, t + 1) == t:
+            starts.append(t)
+            free_at[g] = t + S
+            waiting -= 1
+    return starts
 
 
 @pytest.mark.parametrize("frac", [0.6, 0.8])
 def test_controlled_starts_respect_a_tighter_limit(frac):
-    from paper_2403_11421_amd import sls_run
     B, S, F = 24, 12, 2
     M = B * F // S
     W_lim = int(frac * sched.sls_peak_load(M, F, S))
     n = 8 * S
-    starts = sls_run.controlled_starts(B, S, M, F, W_lim, n)
+    starts = sched.controlled_starts(B, S, M, F, W_lim, n)
     loads = O.step_loads([(t, M) for t in starts], S, n)
     assert len(starts) > 5 and max(loads) <= W_lim           # the guarded quantity, by brute force
     assert starts != list(range(0, n, F))[:len(starts)]      # the limit really holds some back
-    # a delayed micro-batch starts at most one step after the brute-force earliest step, given
-    # the micro-batches started before it and its own arrival
-    for i, t in enumerate(starts[1:], 1):
-        before = [(s0, M) for s0 in starts[:i]]
-        arrival = i * F
-        first = O.earliest_start_brute_force(before, S, W_lim, max(arrival, starts[i - 1] + 1), M, t + 2)
-        assert first <= t <= first + 1
+    assert starts == _controlled_starts_by_hand(B, S, M, F, W_lim, n)
+
+
+def test_controlled_starts_random_cases_and_bad_arguments():
+    rng = random.Random(11)
+    for _ in range(40):
+        S = rng.randint(2, 10)
+        M = rng.randint(1, 3)
+        B = M * rng.randint(1, 6)
+        F = rng.randint(1, 4)
+        W_lim = rng.randint(M * S, M * S * 6)
+        n = rng.randint(0, 5 * S)
+        assert sched.controlled_starts(B, S, M, F, W_lim, n) == _controlled_starts_by_hand(B, S, M, F, W_lim, n)
+    for bad in ((7, 4, 2, 1, 100, 10), (8, 4, 2, 0, 100, 10), (8, 4, 2, 1, 7, 10), (8, 4, 2, 1, 100, -1)):
+        with pytest.raises(rpart.FdError):
+            sched.controlled_starts(*bad)
