@@ -45,9 +45,9 @@ extern "C" {
 #define FD_ST_WINDOW   4    /* windowed cache: n_sink leaves no window row, or seq_seen and
                                seq_lens of a sequence disagree; its append was skipped           */
 
-#define FD_ST_PLAN     8    /* partial/merge found no plan for this batch shape and workspace
-                               size in the workspace (plan missing, or made for another
-                               descriptor); they wrote nothing                                  */
+#define FD_ST_PLAN     8    /* partial/merge found no plan for this batch shape, cache format,
+                               launch and workspace size in the workspace (plan missing, or
+                               made for another kind of descriptor); they wrote nothing       */
 
 #define FD_SLOT_FREE  (-1)  /* value of seq_lens[b] for a slot that holds no sequence            */
 
@@ -141,8 +141,10 @@ int fd_rpart_decode(const fd_kv_desc *desc, const void *q, void *out,
  * The three stages of fd_rpart_decode, exposed so that a harness can time them
  * separately.  They must be enqueued in this order on one stream with the same
  * descriptor and workspace.  partial and merge check that the workspace holds a plan
- * made for the same B, H and workspace size; otherwise they set FD_ST_PLAN and write
- * nothing (their table lookups would not be safe).
+ * made for the same B, H, head dimension, cache format and workspace size and for no more
+ * workgroups than they are launched with; otherwise they set FD_ST_PLAN and write nothing.
+ * Token ranges from the plan are clamped to this descriptor's seq_cap, so a plan made from
+ * other lengths gives wrong results but no access outside a sequence's block.
  *   plan:    reads seq_lens on the device, cuts every sequence into chunks and
  *            writes the work-item table into the workspace.
  *   partial: streams each chunk's K and V rows once; per (b,h,chunk) produces
@@ -194,9 +196,33 @@ int fd_kv_reset(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void 
 int fd_kv_release(const fd_kv_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
 
 /*
- * Copy the sticky status word to the host.  SYNCHRONISES `stream`.
- * If `clear` is non-zero the device word is zeroed afterwards.
+ * Bulk store (prompt ingestion; Section 4.1: the worker's cache holds every token of the
+ * sequence, the prompt's included): rows t0 .. t0+n-1 of sequence b receive the n token rows
+ * given as device fp16 [H][n][d] (16-byte aligned), K from k_rows, V from v_rows; either may
+ * be NULL and that side is then left alone.  fp16 caches copy the rows bit for bit; quantised
+ * caches quantise every row exactly as fd_kvq_append does.  Rows are raw row indices (in a
+ * windowed cache, positions in the bounded buffer).  With set_len non-zero seq_lens[b] (and
+ * seq_seen[b], if present) becomes t0 + n, otherwise lengths are untouched and rows beyond
+ * seq_lens[b] stay invisible to decode.  If t0 + n exceeds seq_cap[b] nothing is written and
+ * FD_ST_CAPACITY is raised.  FD_EINVAL for b outside [0, B) or negative t0, n.
  */
+int fd_kv_store_rows(const fd_kv_desc *desc, int32_t b, int32_t t0, int32_t n, const void *k_rows,
+                     const void *v_rows, int set_len, void *stream);
+
+/*
+ * Device status (errors only the device can see are OR-ed into the sticky word *desc->status).
+ * Both calls SYNCHRONISE `stream`.
+ *   fd_last_device_status  takes the word: *host_out receives the FD_ST_* bits raised since the
+ *       previous take and the device word is cleared in the same atomic step, so a bit raised by
+ *       a kernel that runs meanwhile is never lost.  `workspace` (device, 256-byte aligned, any
+ *       workspace of this library or 256 bytes of its own) lends one header word as the staging
+ *       slot; plan tables in it are untouched.  Section 4.1's worker reports per step whether
+ *       its appends took place; this is that report.
+ *   fd_read_status  copies the word without a workspace; with `clear` non-zero the bits it
+ *       reported (only those) are cleared afterwards.
+ * For a quantised cache pass an fd_kv_desc whose `status` field is the quantised descriptor's.
+ */
+int fd_last_device_status(const fd_kv_desc *desc, void *workspace, int32_t *host_out, void *stream);
 int fd_read_status(const fd_kv_desc *desc, int32_t *host_status, int clear, void *stream);
 
 /*
@@ -259,6 +285,8 @@ typedef struct fd_kvq_desc {
  * Eq. 2 + Eq. 3 over the dequantised rows with fp32 arithmetic and an fp16 result; workspace size comes from fd_workspace_bytes(B, H, 128, n).
  */
 int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new, void *stream);
+int fd_kvq_store_rows(const fd_kvq_desc *desc, int32_t b, int32_t t0, int32_t n, const void *k_rows,
+                      const void *v_rows, int set_len, void *stream);
 int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
 int fd_kvq_release(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);
 int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_bytes, void *stream);

@@ -216,6 +216,13 @@ void fdo_quantize_row_i8(const uint16_t *x, int d, uint8_t *codes, float *scale)
     }
 }
 
+/* n_rows consecutive rows, one after the other (codes [n_rows][d], scales [n_rows]). */
+void fdo_quantize_rows_i8(const uint16_t *x, int64_t n_rows, int d, uint8_t *codes, float *scales)
+{
+    for (int64_t r = 0; r < n_rows; ++r)
+        fdo_quantize_row_i8(x + r * d, d, codes + r * d, scales + r);
+}
+
 /* Append for a quantised cache: Kc[b], Vc[b] are token-major [cap_b][H][d] bytes,
  * Ks[b], Vs[b] token-major [cap_b][H] binary32 scales.  k_new, v_new: [B][H][d] binary16. */
 void fdo_kvq_append(int B, int H, int d, int32_t *seq_lens,
@@ -314,6 +321,13 @@ void fdo_quantize_row_u4(const uint16_t *x, int d, uint8_t *packed, float *scale
         }
         packed[j] = (uint8_t)(c[0] | (c[1] << 4));
     }
+}
+
+/* n_rows consecutive rows, one after the other (packed [n_rows][d/2], sz [n_rows][2]). */
+void fdo_quantize_rows_u4(const uint16_t *x, int64_t n_rows, int d, uint8_t *packed, float *sz)
+{
+    for (int64_t r = 0; r < n_rows; ++r)
+        fdo_quantize_row_u4(x + r * d, d, packed + r * (d / 2), sz + 2 * r, sz + 2 * r + 1);
 }
 
 /* Append for a 4-bit cache: Kc[b], Vc[b] token-major [cap_b][H][d/2] bytes; Ksz[b], Vsz[b]

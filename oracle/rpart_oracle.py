@@ -41,6 +41,10 @@ def _load():
         lib.fdo_rpart_decode.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 8 + [ctypes.c_int]
         lib.fdo_quantize_row_i8.restype = None
         lib.fdo_quantize_row_i8.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        lib.fdo_quantize_rows_i8.restype = None
+        lib.fdo_quantize_rows_i8.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        lib.fdo_quantize_rows_u4.restype = None
+        lib.fdo_quantize_rows_u4.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         lib.fdo_kvq_append.restype = None
         lib.fdo_kvq_append.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 7
         lib.fdo_rpartq_decode.restype = ctypes.c_int
@@ -134,10 +138,7 @@ def quantize_rows_i8(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     flat = x.reshape(-1, d)
     codes = np.empty(flat.shape, dtype=np.uint8)
     scales = np.empty(flat.shape[0], dtype=np.float32)
-    lib = _load()
-    for r in range(flat.shape[0]):
-        lib.fdo_quantize_row_i8(flat[r].ctypes.data, d, codes[r].ctypes.data,
-                                scales[r:r + 1].ctypes.data)
+    _load().fdo_quantize_rows_i8(flat.ctypes.data, flat.shape[0], d, codes.ctypes.data, scales.ctypes.data)
     return codes.reshape(x.shape), scales.reshape(x.shape[:-1])
 
 
@@ -183,10 +184,7 @@ def quantize_rows_u4(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     flat = x.reshape(-1, d)
     packed = np.empty((flat.shape[0], d // 2), dtype=np.uint8)
     sz = np.empty((flat.shape[0], 2), dtype=np.float32)
-    lib = _load()
-    for r in range(flat.shape[0]):
-        lib.fdo_quantize_row_u4(flat[r].ctypes.data, d, packed[r].ctypes.data,
-                                sz[r, 0:1].ctypes.data, sz[r, 1:2].ctypes.data)
+    _load().fdo_quantize_rows_u4(flat.ctypes.data, flat.shape[0], d, packed.ctypes.data, sz.ctypes.data)
     return packed.reshape(x.shape[:-1] + (d // 2,)), sz.reshape(x.shape[:-1] + (2,))
 
 

@@ -19,23 +19,47 @@ HIPCC_FLAGS = [
 ]
 
 
+DEPS = SOURCES + [os.path.join(_PKG, "csrc", "fd_rpartq.h"), os.path.join(INCLUDE, "fastdecode_rpart.h"),
+                  os.path.join(INCLUDE, "fastdecode_sched.h")]
+STAMP = LIB + ".srchash"            # written beside the library: what it was built from
+
+
+def source_hash(extra_flags=()) -> str:
+    """sha256 over the sources, the headers they include and the compiler flags."""
+    import hashlib
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS + list(extra_flags)).encode())
+    for p in DEPS:
+        with open(p, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
 def build(verbose: bool = False, extra_flags=()) -> str:
     """Compile every HIP source into the shared library; always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-I", INCLUDE, "-o", LIB] + SOURCES
     if verbose:
         print(" ".join(cmd), flush=True)
+    if os.path.exists(STAMP):
+        os.remove(STAMP)
     subprocess.check_call(cmd)
+    with open(STAMP, "w") as f:
+        f.write(source_hash(extra_flags) + "\n")
     return LIB
 
 
+def have_compiler() -> bool:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    return os.path.isfile(hipcc) and os.access(hipcc, os.X_OK)
+
+
 def is_stale() -> bool:
-    if not os.path.exists(LIB):
+    """True when the library is missing or was built from other sources than the tree holds now
+    (by content, not by file time: a copied tree keeps no reliable times)."""
+    if not os.path.exists(LIB) or not os.path.exists(STAMP):
         return True
-    t = os.path.getmtime(LIB)
-    deps = SOURCES + [os.path.join(_PKG, "csrc", "fd_rpartq.h"), os.path.join(INCLUDE, "fastdecode_rpart.h"),
-                      os.path.join(INCLUDE, "fastdecode_sched.h")]
-    return any(os.path.getmtime(p) > t for p in deps)
+    with open(STAMP) as f:
+        return f.read().strip() != source_hash()
 
 
 if __name__ == "__main__":

@@ -37,7 +37,9 @@ constexpr float kNegBig = -1.0e30f;    // "no token seen yet" running max (finit
 
 // header words
 enum { HDR_NITEMS = 0, HDR_CHUNK = 2, HDR_TOKENS = 3, HDR_GRID = 4, HDR_MAGIC = 5, HDR_B = 6,
-       HDR_H = 7, HDR_MAXITEMS = 8, HDR_WAVE_UNITS = 9 };
+       HDR_H = 7, HDR_MAXITEMS = 8, HDR_WAVE_UNITS = 9, HDR_KIND = 10, HDR_STATUS_OUT = 16 };
+// cache format a plan was made for: head dimension and bits per element (16 = fp16)
+constexpr int plan_kind(int d, int bits) { return d | (bits << 16); }
 constexpr int32_t kPlanMagic = 0x46445250;
 
 struct WsLayout {
@@ -155,6 +157,45 @@ __global__ void kv_reset_kernel(int32_t *__restrict__ seq_lens, int32_t *__restr
     }
 }
 
+// Bulk store of n consecutive token rows of one sequence (prompt ingestion): raw 128-bit copies
+// of rows given as fp16 [H][n][d] into tokens t0 .. t0+n-1.  One thread per 16-byte word.
+__global__ __launch_bounds__(256) void kv_store_rows_kernel(
+    uint4 *__restrict__ k_base, uint4 *__restrict__ v_base, const int64_t *__restrict__ seq_off,
+    const int32_t *__restrict__ seq_cap, int32_t *__restrict__ seq_lens,
+    int32_t *__restrict__ seq_seen, int32_t *__restrict__ status, const uint4 *__restrict__ k_rows,
+    const uint4 *__restrict__ v_rows, int H, int d, int b, int t0, int n, int set_len)
+{
+    const int cap = seq_cap[b];
+    if (t0 + n > cap) {                                      // uniform over the grid: nothing is written
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
+        return;
+    }
+    const int vpr = d / 8;
+    const int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;    // word index in [H][n][vpr]
+    if (x < (int64_t)H * n * vpr) {
+        const int64_t r = x / vpr;
+        const int c = (int)(x - r * vpr);
+        const int h = (int)(r / n), j = (int)(r - (int64_t)h * n);
+        const int64_t dst = seq_off[b] / 8 + ((int64_t)h * cap + t0 + j) * vpr + c;
+        if (k_rows) k_base[dst] = k_rows[x];
+        if (v_rows) v_base[dst] = v_rows[x];
+    }
+    if (set_len && blockIdx.x == 0 && threadIdx.x == 0) {
+        seq_lens[b] = t0 + n;
+        if (seq_seen) seq_seen[b] = t0 + n;
+    }
+}
+
+// sticky status word: take it (read and clear in one atomic step) or clear the bits just read
+__global__ void status_take_kernel(int32_t *__restrict__ status, int32_t *__restrict__ dst)
+{
+    *dst = atomicExch(status, 0);
+}
+__global__ void status_clear_bits_kernel(int32_t *__restrict__ status, int32_t bits)
+{
+    atomicAnd(status, ~bits);
+}
+
 // ---------------------------------------------------------------------------
 // Planner: one workgroup.  Reads the ragged lengths on the device, picks the
 // chunk length, writes the work-item table and a static schedule.
@@ -238,7 +279,7 @@ constexpr int kBigMax = 128;        // ... goes on a list of at most this many e
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
     int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid_long, int grid_short,
-    int short_below, int hashed, int wave_units, int split, int max_items,
+    int short_below, int hashed, int wave_units, int split, int kind, int max_items,
     int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
     int4 *__restrict__ items, int32_t *__restrict__ order)
 {
@@ -415,16 +456,24 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         hdr[HDR_H] = H;
         hdr[HDR_MAXITEMS] = max_items;
         hdr[HDR_WAVE_UNITS] = wave_now;
+        hdr[HDR_KIND] = kind;
     }
 }
 
 // The streaming and the merge kernels index the caller's slabs with what the plan tables say:
-// they refuse a workspace that does not hold a plan made for this batch shape and workspace
-// size (never planned, or planned for another descriptor), report it and write nothing.
-__device__ inline bool plan_matches(const int32_t *hdr, int B, int H, int max_items, int32_t *status)
+// they refuse a workspace that does not hold a plan made for this batch shape, cache format and
+// workspace size (never planned, or planned for another kind of descriptor), report it and write
+// nothing.  `launched` is the number of workgroups this launch has, 0 where that does not
+// matter: a plan that deals units to more workgroups than exist would leave outputs unwritten.
+// Token ranges are clamped to the current descriptor's capacities when a unit is fetched, so a
+// plan made for other lengths gives wrong results but never an access outside a block.
+__device__ inline bool plan_matches(const int32_t *hdr, int B, int H, int kind, int max_items,
+                                    int launched, int32_t *status)
 {
     const bool ok = hdr[HDR_MAGIC] == kPlanMagic && hdr[HDR_B] == B && hdr[HDR_H] == H &&
-                    hdr[HDR_MAXITEMS] == max_items;
+                    hdr[HDR_KIND] == kind && hdr[HDR_MAXITEMS] == max_items &&
+                    hdr[HDR_NITEMS] >= 0 && hdr[HDR_NITEMS] <= max_items &&
+                    (launched == 0 || (hdr[HDR_GRID] > 0 && hdr[HDR_GRID] <= launched));
     if (!ok && blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, FD_ST_PLAN);
     return ok;
 }
@@ -561,7 +610,7 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
     const int wave = tid >> 6;
     const int row = lane / LPR;
     const int col = lane % LPR;
-    if (!plan_matches(hdr, B, H, max_items, status)) return;
+    if (!plan_matches(hdr, B, H, plan_kind(D, 16), max_items, (int)gridDim.x, status)) return;
     const int n_units = hdr[HDR_NITEMS] * H;
     const int W = hdr[HDR_GRID], g = blockIdx.x;          // active workgroups, chosen by the planner
     if (g >= W) return;
@@ -586,12 +635,15 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
                 const int sidx = (int)(p / H);
                 const int item = order[sidx];
                 const int4 it = items[item];
+                const int cap = seq_cap[it.x];
+                // inside this cache's block, and not empty, whatever lengths the plan was made from
+                const int t1 = min(it.z, cap), t0 = min(it.y, max(t1 - 1, 0));
                 u.h = (int)(p - (long long)sidx * H);
                 u.b = it.x;
                 u.item = item;
                 u.nch = it.w;
-                u.ntok = it.z - it.y;
-                u.row0 = seq_off[it.x] + ((int64_t)u.h * seq_cap[it.x] + it.y) * D;
+                u.ntok = t1 - t0;
+                u.row0 = seq_off[it.x] + ((int64_t)u.h * cap + t0) * D;
             }
         }
         return u;
@@ -735,11 +787,11 @@ template <int D>
 __global__ __launch_bounds__(256) void rpart_merge_kernel(
     const int32_t *__restrict__ item0, const int32_t *__restrict__ nchunk,
     const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-    _Float16 *__restrict__ out, int B, int H, const int32_t *__restrict__ hdr, int max_items,
-    int32_t *__restrict__ status)
+    _Float16 *__restrict__ out, int B, int H, const int32_t *__restrict__ hdr, int kind,
+    int max_items, int32_t *__restrict__ status)
 {
     constexpr int NV = D / 64;                        // 128-bit pieces of a record per lane
-    if (!plan_matches(hdr, B, H, max_items, status)) return;
+    if (!plan_matches(hdr, B, H, kind, max_items, 0, status)) return;
     const int lane = threadIdx.x & 63;
     const int t = lane & 15, g = lane >> 4;           // piece within the record, record within the load
     const int64_t bh = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -996,7 +1048,7 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
                        desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
                        desc->chunk_tokens, chunk_granule(desc->d), grid, 2 * grid, kShortSeq, 0, 0,
-                       16 /* split */,
+                       16 /* split */, plan_kind(desc->d, 16),
                        (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
@@ -1054,14 +1106,14 @@ int fd_rpart_merge(const fd_kv_desc *desc, void *out,
         hipLaunchKernelGGL(rpart_merge_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream,
                            (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
                            (const float *)(ws + w.off_acc), (const float *)(ws + w.off_ml),
-                           (_Float16 *)out, desc->B, desc->H, (const int32_t *)ws, (int)w.max_items,
-                           desc->status);
+                           (_Float16 *)out, desc->B, desc->H, (const int32_t *)ws,
+                           plan_kind(128, 16), (int)w.max_items, desc->status);
     else
         hipLaunchKernelGGL(rpart_merge_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream,
                            (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
                            (const float *)(ws + w.off_acc), (const float *)(ws + w.off_ml),
-                           (_Float16 *)out, desc->B, desc->H, (const int32_t *)ws, (int)w.max_items,
-                           desc->status);
+                           (_Float16 *)out, desc->B, desc->H, (const int32_t *)ws,
+                           plan_kind(64, 16), (int)w.max_items, desc->status);
     return launched();
 }
 
@@ -1162,11 +1214,43 @@ int fd_read_status(const fd_kv_desc *desc, int32_t *host_status, int clear, void
         hipSuccess)
         return FD_EHIP;
     if (hipStreamSynchronize(s) != hipSuccess) return FD_EHIP;
-    if (clear) {
-        if (hipMemsetAsync(desc->status, 0, sizeof(int32_t), s) != hipSuccess) return FD_EHIP;
+    if (clear && *host_status != 0) {
+        // only the bits just reported are cleared: one raised since the copy stays for the next read
+        hipLaunchKernelGGL(status_clear_bits_kernel, dim3(1), dim3(1), 0, s, desc->status, *host_status);
+        if (launched() != FD_OK) return FD_EHIP;
         if (hipStreamSynchronize(s) != hipSuccess) return FD_EHIP;
     }
     return FD_OK;
+}
+
+int fd_last_device_status(const fd_kv_desc *desc, void *workspace, int32_t *host_out, void *stream)
+{
+    if (!desc || !desc->status || !host_out || !workspace || !aligned(workspace, 256)) return FD_EINVAL;
+    hipStream_t s = (hipStream_t)stream;
+    int32_t *slot = (int32_t *)workspace + HDR_STATUS_OUT;   // a header word no kernel reads
+    hipLaunchKernelGGL(status_take_kernel, dim3(1), dim3(1), 0, s, desc->status, slot);
+    if (launched() != FD_OK) return FD_EHIP;
+    if (hipMemcpyAsync(host_out, slot, sizeof(int32_t), hipMemcpyDeviceToHost, s) != hipSuccess)
+        return FD_EHIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return FD_EHIP;
+    return FD_OK;
+}
+
+int fd_kv_store_rows(const fd_kv_desc *desc, int32_t b, int32_t t0, int32_t n, const void *k_rows,
+                     const void *v_rows, int set_len, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (b < 0 || b >= desc->B || t0 < 0 || n < 0 || (int64_t)t0 + n > INT32_MAX) return FD_EINVAL;
+    if ((k_rows && !aligned(k_rows, 16)) || (v_rows && !aligned(v_rows, 16))) return FD_EINVAL;
+    if (n == 0 && !set_len) return FD_OK;
+    const int64_t words = (int64_t)desc->H * n * (desc->d / 8);
+    const unsigned grid = (unsigned)(words > 0 ? (words + 255) / 256 : 1);
+    hipLaunchKernelGGL(kv_store_rows_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                       (uint4 *)desc->k_base, (uint4 *)desc->v_base, desc->seq_off, desc->seq_cap,
+                       desc->seq_lens, desc->seq_seen, desc->status, (const uint4 *)k_rows,
+                       (const uint4 *)v_rows, desc->H, desc->d, b, t0, n, set_len);
+    return launched();
 }
 
 int fd_plan_info(const void *workspace, int32_t info[4], void *stream)

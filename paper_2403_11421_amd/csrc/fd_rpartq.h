@@ -49,8 +49,71 @@ template <> struct CodeVec<8> { typedef u32x4 type; };
 template <> struct CodeVec<4> { typedef u32x2 type; };
 
 // ---------------------------------------------------------------------------
-// Quantising append.  One workgroup per sequence; a row (128 fp16) is handled by 16
-// lanes with 8 values each.
+// Row quantiser.  A row (128 fp16) is handled by 16 consecutive lanes with 8 values each:
+// `sub` is the lane's position among them, f its values, dst the row's first code byte,
+// meta the row's parameters.  Every step is a correctly rounded binary32 operation, so the
+// stored bytes are those of the definition evaluated in IEEE binary32.
+// ---------------------------------------------------------------------------
+template <int BITS>
+__device__ inline void quantize_row_store(const float (&f)[8], int sub, uint8_t *dst, float *meta)
+{
+    using F = QFmt<BITS>;
+    dst += sub * (F::RB / 16);                                // this lane's 8 codes
+    if (BITS == 8) {
+        float amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
+        amax = dpp_xmax<0xB1>(amax);           // max over the 16 lanes of the row
+        amax = dpp_xmax<0x4E>(amax);
+        amax = dpp_xmax<0x141>(amax);
+        amax = dpp_xmax<0x140>(amax);
+        const float scale = __fdiv_rn(amax, 127.0f);
+        unsigned lo = 0, hi = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float c = scale > 0.f ? rintf(__fdiv_rn(f[i], scale)) : 0.f;
+            const unsigned u = (unsigned)((int)c + 128) & 0xFFu;
+            if (i < 4) lo |= u << (8 * i);
+            else       hi |= u << (8 * (i - 4));
+        }
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
+        if (sub == 0) meta[0] = scale;
+    } else {
+        float mn = f[0], mx = f[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) {
+            mn = fminf(mn, f[i]);
+            mx = fmaxf(mx, f[i]);
+        }
+        mn = dpp_xmin<0xB1>(mn);  mx = dpp_xmax<0xB1>(mx);
+        mn = dpp_xmin<0x4E>(mn);  mx = dpp_xmax<0x4E>(mx);
+        mn = dpp_xmin<0x141>(mn); mx = dpp_xmax<0x141>(mx);
+        mn = dpp_xmin<0x140>(mn); mx = dpp_xmax<0x140>(mx);
+        const float scale = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
+        unsigned w = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float c = scale > 0.f ? rintf(__fdiv_rn(__fsub_rn(f[i], mn), scale)) : 0.f;
+            c = fminf(fmaxf(c, 0.f), 15.f);
+            w |= (unsigned)(int)c << (4 * i);
+        }
+        *reinterpret_cast<unsigned *>(dst) = w;
+        if (sub == 0) {
+            meta[0] = scale;
+            meta[1] = mn;
+        }
+    }
+}
+
+__device__ inline void load_row_f32(const _Float16 *src, float (&f)[8])
+{
+    const half8 x = *reinterpret_cast<const half8 *>(src);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (float)x[i];
+}
+
+// ---------------------------------------------------------------------------
+// Quantising append.  One workgroup per sequence, 16 rows in flight per pass.
 // ---------------------------------------------------------------------------
 template <int BITS>
 __global__ __launch_bounds__(256) void kvq_append_kernel(
@@ -69,68 +132,61 @@ __global__ __launch_bounds__(256) void kvq_append_kernel(
     const int L = append_row(seq_lens, seq_cap, seq_seen, n_sink, status, b, &new_len);
     if (L < 0) return;
     const int sub = threadIdx.x & 15;          // position inside the 16-lane group of a row
-    const int group = threadIdx.x >> 4;        // 16 rows in flight per pass
+    const int group = threadIdx.x >> 4;
     const int64_t off = seq_off[b];
     for (int r = group; r < 2 * H; r += 16) {
         const int which = r >= H;
         const int h = which ? r - H : r;
-        const _Float16 *src = (which ? v_new : k_new) + ((int64_t)b * H + h) * D + sub * 8;
-        const half8 x = *reinterpret_cast<const half8 *>(src);
         float f[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) f[i] = (float)x[i];
+        load_row_f32((which ? v_new : k_new) + ((int64_t)b * H + h) * D + sub * 8, f);
         const int64_t row = (int64_t)h * cap + L;
-        uint8_t *dst = (which ? v_codes : k_codes) + off + row * F::RB + sub * (F::RB / 16);   // 8 codes
-        float *meta = (which ? v_meta : k_meta) + (off / F::RB + row) * F::MW;
-        if (BITS == 8) {
-            float amax = 0.f;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
-            amax = dpp_xmax<0xB1>(amax);           // max over the 16 lanes of the row
-            amax = dpp_xmax<0x4E>(amax);
-            amax = dpp_xmax<0x141>(amax);
-            amax = dpp_xmax<0x140>(amax);
-            const float scale = __fdiv_rn(amax, 127.0f);
-            unsigned lo = 0, hi = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float c = scale > 0.f ? rintf(__fdiv_rn(f[i], scale)) : 0.f;
-                const unsigned u = (unsigned)((int)c + 128) & 0xFFu;
-                if (i < 4) lo |= u << (8 * i);
-                else       hi |= u << (8 * (i - 4));
-            }
-            *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
-            if (sub == 0) meta[0] = scale;
-        } else {
-            float mn = f[0], mx = f[0];
-#pragma unroll
-            for (int i = 1; i < 8; ++i) {
-                mn = fminf(mn, f[i]);
-                mx = fmaxf(mx, f[i]);
-            }
-            mn = dpp_xmin<0xB1>(mn);  mx = dpp_xmax<0xB1>(mx);
-            mn = dpp_xmin<0x4E>(mn);  mx = dpp_xmax<0x4E>(mx);
-            mn = dpp_xmin<0x141>(mn); mx = dpp_xmax<0x141>(mx);
-            mn = dpp_xmin<0x140>(mn); mx = dpp_xmax<0x140>(mx);
-            const float scale = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
-            unsigned w = 0;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                float c = scale > 0.f ? rintf(__fdiv_rn(__fsub_rn(f[i], mn), scale)) : 0.f;
-                c = fminf(fmaxf(c, 0.f), 15.f);
-                w |= (unsigned)(int)c << (4 * i);
-            }
-            *reinterpret_cast<unsigned *>(dst) = w;
-            if (sub == 0) {
-                meta[0] = scale;
-                meta[1] = mn;
-            }
-        }
+        quantize_row_store<BITS>(f, sub, (which ? v_codes : k_codes) + off + row * F::RB,
+                                 (which ? v_meta : k_meta) + (off / F::RB + row) * F::MW);
     }
     __syncthreads();
     if (threadIdx.x == 0) {
         seq_lens[b] = new_len;
         if (seq_seen) seq_seen[b] += 1;
+    }
+}
+
+// Bulk store of n consecutive token rows of one sequence (prompt ingestion): the same quantiser
+// as the append, rows given as fp16 [H][n][128].  grid.x covers the H * n rows, 16 per workgroup.
+template <int BITS>
+__global__ __launch_bounds__(256) void kvq_store_rows_kernel(
+    uint8_t *__restrict__ k_codes, uint8_t *__restrict__ v_codes,
+    float *__restrict__ k_meta, float *__restrict__ v_meta,
+    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
+    int32_t *__restrict__ seq_lens, int32_t *__restrict__ seq_seen, int32_t *__restrict__ status,
+    const _Float16 *__restrict__ k_rows, const _Float16 *__restrict__ v_rows, int H, int b, int t0,
+    int n, int set_len)
+{
+    using F = QFmt<BITS>;
+    constexpr int D = F::D;
+    const int cap = seq_cap[b];
+    if (t0 + n > cap) {                                      // uniform over the grid: nothing is written
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
+        return;
+    }
+    const int sub = threadIdx.x & 15;
+    const int64_t r = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);   // row index in [H][n]
+    const int64_t off = seq_off[b];
+    if (r < (int64_t)H * n) {
+        const int h = (int)(r / n), j = (int)(r - (int64_t)h * n);
+        const int64_t row = (int64_t)h * cap + t0 + j;
+        float f[8];
+        if (k_rows) {
+            load_row_f32(k_rows + r * D + sub * 8, f);
+            quantize_row_store<BITS>(f, sub, k_codes + off + row * F::RB, k_meta + (off / F::RB + row) * F::MW);
+        }
+        if (v_rows) {
+            load_row_f32(v_rows + r * D + sub * 8, f);
+            quantize_row_store<BITS>(f, sub, v_codes + off + row * F::RB, v_meta + (off / F::RB + row) * F::MW);
+        }
+    }
+    if (set_len && blockIdx.x == 0 && threadIdx.x == 0) {
+        seq_lens[b] = t0 + n;
+        if (seq_seen) seq_seen[b] = t0 + n;
     }
 }
 
@@ -551,12 +607,15 @@ __device__ __forceinline__ void rpartq_body(
                 const int sidx = (int)(p / H);
                 const int item = order[sidx];
                 const int4 it = items[item];
+                const int cap = seq_cap[it.x];
+                // inside this cache's block, and not empty, whatever lengths the plan was made from
+                const int t1 = min(it.z, cap), t0 = min(it.y, max(t1 - 1, 0));
                 u.h = (int)(p - (long long)sidx * H);
                 u.b = it.x;
                 u.item = item;
                 u.nch = it.w;
-                u.ntok = it.z - it.y;
-                u.row0 = seq_off[it.x] / RB + (int64_t)u.h * seq_cap[it.x] + it.y;   // row index
+                u.ntok = t1 - t0;
+                u.row0 = seq_off[it.x] / RB + (int64_t)u.h * cap + t0;   // row index
             }
         }
         return u;
@@ -797,7 +856,7 @@ void rpartq_partial_kernel(
     const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
     float qscale, int B, int max_items, int32_t *__restrict__ status)
 {
-    if (!plan_matches(hdr, B, H, max_items, status)) return;
+    if (!plan_matches(hdr, B, H, plan_kind(128, BITS), max_items, (int)gridDim.x, status)) return;
     if constexpr (q_wave_units<BITS>() != 0) {
         if (hdr[HDR_WAVE_UNITS]) {
             rpartq_body<BITS, 1>(k_codes, v_codes, k_meta, v_meta, seq_off, seq_cap, q, out, H, hdr,
@@ -863,6 +922,31 @@ int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new,
     return launched();
 }
 
+int fd_kvq_store_rows(const fd_kvq_desc *desc, int32_t b, int32_t t0, int32_t n, const void *k_rows,
+                      const void *v_rows, int set_len, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (b < 0 || b >= desc->B || t0 < 0 || n < 0 || (int64_t)t0 + n > INT32_MAX) return FD_EINVAL;
+    if ((k_rows && !aligned(k_rows, 16)) || (v_rows && !aligned(v_rows, 16))) return FD_EINVAL;
+    if (n == 0 && !set_len) return FD_OK;
+    const int64_t rows = (int64_t)desc->H * n;
+    const unsigned grid = (unsigned)((rows + 15) / 16 > 0 ? (rows + 15) / 16 : 1);
+    if (desc->bits == 4)
+        hipLaunchKernelGGL(kvq_store_rows_kernel<4>, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                           (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
+                           desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens, desc->seq_seen,
+                           desc->status, (const _Float16 *)k_rows, (const _Float16 *)v_rows, desc->H,
+                           b, t0, n, set_len);
+    else
+        hipLaunchKernelGGL(kvq_store_rows_kernel<8>, dim3(grid), dim3(256), 0, (hipStream_t)stream,
+                           (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
+                           desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens, desc->seq_seen,
+                           desc->status, (const _Float16 *)k_rows, (const _Float16 *)v_rows, desc->H,
+                           b, t0, n, set_len);
+    return launched();
+}
+
 static int reset_qslots(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, int value,
                         void *stream)
 {
@@ -905,7 +989,7 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
                        (desc->bits == 4 ? q_wg_long<4>() : q_wg_long<8>()) * grid,
                        (desc->bits == 4 ? q_wg_short<4>() : q_wg_short<8>()) * grid, kShortSeq, 1,
                        desc->bits == 4 ? q_wave_units<4>() : q_wave_units<8>(), kQSplit,
-                       (int)w.max_items, (int32_t *)ws,
+                       plan_kind(128, desc->bits == 4 ? 4 : 8), (int)w.max_items, (int32_t *)ws,
                        (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
                        (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
     return launched();
@@ -960,7 +1044,8 @@ int fd_rpartq_merge(const fd_kvq_desc *desc, void *out,
                        (hipStream_t)stream, (const int32_t *)(ws + w.off_item0),
                        (const int32_t *)(ws + w.off_nchunk), (const float *)(ws + w.off_acc),
                        (const float *)(ws + w.off_ml), (_Float16 *)out, desc->B, desc->H,
-                       (const int32_t *)ws, (int)w.max_items, desc->status);
+                       (const int32_t *)ws, plan_kind(128, desc->bits == 4 ? 4 : 8),
+                       (int)w.max_items, desc->status);
     return launched();
 }
 

@@ -1,7 +1,8 @@
-"""Device-resident KV-cache of one layer in the layout of ``fd_kv_desc``.
+"""Device-resident KV-cache of one layer in the layout of ``fd_kv_desc`` / ``fd_kvq_desc``.
 
-Plumbing only: allocates the K and V slabs and the per-sequence arrays with
-torch, fills them from tensors the caller supplies, and exposes the descriptor.
+Plumbing only: allocates the slabs and the per-sequence arrays with torch and exposes the
+descriptor.  Rows are written by the library (``fd_kv_store_rows`` / ``fd_kvq_store_rows``, the
+same quantiser as the append): no cache arithmetic lives on this side of the C ABI.
 Sequence b owns a ``[H][cap_b][d]`` block at element offset ``seq_off[b]``.
 """
 from __future__ import annotations
@@ -52,8 +53,10 @@ class KVCache:
 
     def fill(self, which: str, b: int, rows: torch.Tensor, t0: int = 0) -> None:
         """Store fp16 ``rows [H, L, d]`` at tokens t0..t0+L-1 of sequence b (no length change)."""
-        L = rows.shape[1]
-        self.block(which, b)[:, t0:t0 + L, :].copy_(rows)
+        rows = rows.to(device=self.device, dtype=torch.float16).contiguous()
+        assert rows.shape[0] == self.H and rows.shape[2] == self.d and t0 + rows.shape[1] <= self.caps[b]
+        rpart.fd_kv_store_rows(self.desc, b, t0, rows if which == "K" else None,
+                               rows if which == "V" else None)
 
     def set_lens(self, lens: Sequence[int]) -> None:
         """Cached tokens per sequence; a windowed cache is told the tokens seen so far, which
@@ -67,39 +70,6 @@ class KVCache:
     def workspace(self, max_total_tokens: int) -> torch.Tensor:
         n = rpart.workspace_bytes(self.B, self.H, self.d, max_total_tokens)
         return torch.empty(n, dtype=torch.uint8, device=self.device)
-
-
-def quantize_rows_i8(rows: torch.Tensor):
-    """fp16 rows [..., d] -> (uint8 codes [..., d], float32 scales [...]).
-
-    Input preparation for tests and benchmarks (the product path quantises in
-    ``fd_kvq_append``): scale = max|x| / 127 and code = rint(x / scale) in float32,
-    byte = code + 128, all-zero rows get scale 0 and byte 128.  On a GPU torch's division is
-    not correctly rounded, so scales can be 1 ulp off that definition; what is stored is the
-    input either way."""
-    x = rows.float()
-    scale = x.abs().amax(dim=-1) / 127.0
-    safe = torch.where(scale > 0, scale, torch.ones_like(scale))
-    code = torch.where(scale.unsqueeze(-1) > 0, torch.round(x / safe.unsqueeze(-1)),
-                       torch.zeros_like(x))
-    return (code + 128.0).to(torch.uint8), scale
-
-
-def quantize_rows_u4(rows: torch.Tensor):
-    """fp16 rows [..., d] -> (packed uint8 [..., d/2], float32 [..., 2] = scale, zero).
-
-    Input preparation for tests and benchmarks, as `quantize_rows_i8`: zero = min, scale =
-    (max - min) / 15, code = rint((x - zero) / scale) clamped to 0..15, element 2j in the low
-    nibble of byte j."""
-    x = rows.float()
-    mn = x.amin(dim=-1)
-    scale = (x.amax(dim=-1) - mn) / 15.0
-    safe = torch.where(scale > 0, scale, torch.ones_like(scale))
-    code = torch.where(scale.unsqueeze(-1) > 0,
-                       torch.round((x - mn.unsqueeze(-1)) / safe.unsqueeze(-1)), torch.zeros_like(x))
-    code = code.clamp_(0, 15).to(torch.uint8)
-    packed = code[..., 0::2] | (code[..., 1::2] << 4)
-    return packed, torch.stack([scale, mn], dim=-1)
 
 
 class KVCacheQ:
@@ -152,11 +122,12 @@ class KVCacheQ:
         return v.view(self.H, self.caps[b]) if self.mw == 1 else v.view(self.H, self.caps[b], 2)
 
     def fill(self, which: str, b: int, rows: torch.Tensor, t0: int = 0) -> None:
-        """Quantise fp16 ``rows [H, L, d]`` into tokens t0..t0+L-1 of sequence b."""
-        L = rows.shape[1]
-        c, s = quantize_rows_i8(rows) if self.bits == 8 else quantize_rows_u4(rows)
-        self.codes(which, b)[:, t0:t0 + L, :].copy_(c)
-        self.scales(which, b)[:, t0:t0 + L].copy_(s)
+        """Quantise fp16 ``rows [H, L, d]`` into tokens t0..t0+L-1 of sequence b (the library's
+        quantiser, the same as the append's; no length change)."""
+        rows = rows.to(device=self.device, dtype=torch.float16).contiguous()
+        assert rows.shape[0] == self.H and rows.shape[2] == self.d and t0 + rows.shape[1] <= self.caps[b]
+        rpart.fd_kv_store_rows(self.desc, b, t0, rows if which == "K" else None,
+                               rows if which == "V" else None)
 
     def set_lens(self, lens: Sequence[int]) -> None:
         """Cached tokens per sequence; a windowed cache is told the tokens seen so far, which

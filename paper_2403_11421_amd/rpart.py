@@ -56,11 +56,17 @@ def lib_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Load the built library; build it first only if no built library exists."""
+    """Load the built library.  It is built first if none exists; a library older than one of
+    its sources is rebuilt where a compiler is at hand and refused otherwise, so that a stale
+    build is never tested or timed silently."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_build.LIB):
+        _build.build()
+    elif _build.is_stale():
+        if not _build.have_compiler():
+            raise RuntimeError(f"{_build.LIB} is older than its sources and no hipcc is available to rebuild it")
         _build.build()
     lib = ctypes.CDLL(_build.LIB)
     P = ctypes.POINTER(fd_kv_desc)
@@ -96,10 +102,16 @@ def load() -> ctypes.CDLL:
     lib.fd_kv_release.argtypes = [P, _vp, ctypes.c_int32, _vp]
     lib.fd_read_status.restype = ctypes.c_int
     lib.fd_read_status.argtypes = [P, ctypes.POINTER(ctypes.c_int32), ctypes.c_int, _vp]
+    lib.fd_last_device_status.restype = ctypes.c_int
+    lib.fd_last_device_status.argtypes = [P, _vp, ctypes.POINTER(ctypes.c_int32), _vp]
+    lib.fd_kv_store_rows.restype = ctypes.c_int
+    lib.fd_kv_store_rows.argtypes = [P, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, _vp, ctypes.c_int, _vp]
     lib.fd_plan_info.restype = ctypes.c_int
     lib.fd_plan_info.argtypes = [_vp, ctypes.POINTER(ctypes.c_int32), _vp]
     Q = ctypes.POINTER(fd_kvq_desc)
     for name, args in (("fd_kvq_append", [Q, _vp, _vp, _vp]),
+                       ("fd_kvq_store_rows", [Q, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, _vp,
+                                              ctypes.c_int, _vp]),
                        ("fd_kvq_reset", [Q, _vp, ctypes.c_int32, _vp]),
                        ("fd_kvq_release", [Q, _vp, ctypes.c_int32, _vp]),
                        ("fd_rpartq_plan", [Q, _vp, ctypes.c_size_t, _vp]),
@@ -122,7 +134,8 @@ EXPORTS = ("fd_version", "fd_desc_size", "fd_strerror", "fd_workspace_bytes", "f
            "fd_read_status", "fd_plan_info", "fd_hbm_read_probe",
            "fd_kvq_append", "fd_kvq_reset", "fd_rpartq_plan", "fd_rpartq_partial", "fd_rpartq_merge",
            "fd_rpartq_decode", "fd_rpartq_step", "fd_rpart_layer_step", "fd_rpartq_layer_step",
-           "fd_kv_release", "fd_kvq_release", "fd_rpart_decode_noalloc")
+           "fd_kv_release", "fd_kvq_release", "fd_rpart_decode_noalloc", "fd_last_device_status",
+           "fd_kv_store_rows", "fd_kvq_store_rows")
 
 
 def version() -> int:
@@ -217,6 +230,29 @@ def fd_read_status(desc, clear: bool = False) -> int:
     _check(load().fd_read_status(ctypes.byref(probe), ctypes.byref(v), int(clear), _stream()),
            "fd_read_status")
     return v.value
+
+
+def fd_last_device_status(desc, workspace: torch.Tensor) -> int:
+    """Take the sticky device status (read and clear in one atomic step); fp16 or quantised cache."""
+    probe = fd_kv_desc(status=desc.status)
+    v = ctypes.c_int32(0)
+    _check(load().fd_last_device_status(ctypes.byref(probe), workspace.data_ptr(), ctypes.byref(v), _stream()),
+           "fd_last_device_status")
+    return v.value
+
+
+def fd_kv_store_rows(desc, b: int, t0: int, k_rows: Optional[torch.Tensor],
+                     v_rows: Optional[torch.Tensor], set_len: bool = False) -> None:
+    """Store token rows [H, n, d] (fp16, contiguous) at tokens t0.. of sequence b; `desc` is an
+    fd_kv_desc (bit copy) or an fd_kvq_desc (quantised as the append does)."""
+    rows = k_rows if k_rows is not None else v_rows
+    n = 0 if rows is None else int(rows.shape[1])
+    for t in (k_rows, v_rows):
+        assert t is None or (t.is_contiguous() and t.dtype == torch.float16 and t.shape[1] == n)
+    quant = isinstance(desc, fd_kvq_desc)
+    f = load().fd_kvq_store_rows if quant else load().fd_kv_store_rows
+    _check(f(ctypes.byref(desc), b, t0, n, _ptr(k_rows), _ptr(v_rows), 1 if set_len else 0, _stream()),
+           "fd_kvq_store_rows" if quant else "fd_kv_store_rows")
 
 
 def fd_plan_info(workspace: torch.Tensor) -> dict:

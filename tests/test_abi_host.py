@@ -86,6 +86,39 @@ def test_host_side_argument_checks_need_no_gpu():
     assert lib.fd_rpart_decode(ctypes.byref(d), 0x7000, 0x8000, 0x9000, 1 << 30, None) == rpart.FD_EINVAL
 
 
+def test_new_entry_points_check_their_arguments_on_the_host():
+    lib = rpart.load()
+    null = ctypes.POINTER(rpart.fd_kv_desc)()
+    v = ctypes.c_int32(0)
+    assert lib.fd_last_device_status(null, 0x1000, ctypes.byref(v), None) == rpart.FD_EINVAL
+    d = rpart.fd_kv_desc(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 2, 4, 128, 0)
+    assert lib.fd_last_device_status(ctypes.byref(d), None, ctypes.byref(v), None) == rpart.FD_EINVAL
+    assert lib.fd_last_device_status(ctypes.byref(d), 0x1010, ctypes.byref(v), None) == rpart.FD_EINVAL
+    assert lib.fd_last_device_status(ctypes.byref(d), 0x1000, None, None) == rpart.FD_EINVAL
+    assert lib.fd_kv_store_rows(null, 0, 0, 1, 0x7000, 0x8000, 0, None) == rpart.FD_EINVAL
+    for b, t0, n in ((2, 0, 1), (-1, 0, 1), (0, -1, 1), (0, 0, -1), (0, 2 ** 31 - 1, 1)):
+        assert lib.fd_kv_store_rows(ctypes.byref(d), b, t0, n, 0x7000, 0x8000, 0, None) == rpart.FD_EINVAL
+    assert lib.fd_kv_store_rows(ctypes.byref(d), 0, 0, 1, 0x7001, None, 0, None) == rpart.FD_EINVAL
+    assert lib.fd_kv_store_rows(ctypes.byref(d), 0, 5, 0, None, None, 0, None) == rpart.FD_OK   # nothing to do
+    q = rpart.fd_kvq_desc(0x1000, 0x2000, 0x3000, 0x4000, 0x5000, 0x6000, 0x7000, 0x8000, 2, 4, 128, 0, None, 0, 8)
+    assert lib.fd_kvq_store_rows(ctypes.byref(q), 2, 0, 1, 0x9000, None, 0, None) == rpart.FD_EINVAL
+    assert lib.fd_kvq_store_rows(ctypes.byref(q), 0, 0, 0, None, None, 0, None) == rpart.FD_OK
+    q.d = 64
+    assert lib.fd_kvq_store_rows(ctypes.byref(q), 0, 0, 0, None, None, 0, None) == rpart.FD_EINVAL
+
+
+def test_stale_library_is_detected_by_content():
+    from paper_2403_11421_amd import build
+    assert not build.is_stale()
+    stamp = open(build.STAMP).read()
+    try:
+        open(build.STAMP, "w").write("0" * 64 + "\n")
+        assert build.is_stale()
+    finally:
+        open(build.STAMP, "w").write(stamp)
+    assert not build.is_stale() and build.have_compiler()
+
+
 def test_binding_raises_fd_error():
     with pytest.raises(rpart.FdError) as e:
         rpart._check(rpart.FD_EWORKSPACE, "x")

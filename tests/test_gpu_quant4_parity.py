@@ -85,19 +85,19 @@ def _cfg(name, B, H, **kw):
     return W.RPartConfig(name, B, H, 128, "const", 0, 0, **kw)
 
 
-def test_fill_helper_prepares_a_valid_4bit_cache():
-    """Input preparation only (see the 8-bit test of the same name): the stored rows must be a
-    sensible 4-bit cache, dequantised values within half a step of the source."""
+def test_bulk_store_quantises_like_the_oracle():
+    """fd_kvq_store_rows on a 4-bit cache: packed codes and (scale, zero) pairs are the oracle
+    quantiser's, bit for bit, rows outside the range untouched."""
     cfg = _cfg("fill4", 2, 3)
-    case = Q4Case(cfg, [300, 77])
+    case = Q4Case(cfg, [300, 77], extra_cap=5)
     for b, L in enumerate(case.lens0):
         for which in ("K", "V"):
-            rows = W.gen_cache_block(cfg, which, b, L, W.DEFAULT_SEED, "cuda").double()
-            packed = case.cache.codes(which, b)[:, :L]
-            codes = torch.stack([packed & 15, packed >> 4], dim=-1).flatten(-2).double()
-            sz = case.cache.scales(which, b)[:, :L].double()
-            assert float(codes.max()) <= 15
-            assert bool(((codes * sz[..., 0:1] + sz[..., 1:2] - rows).abs() <= 0.51 * sz[..., 0:1]).all())
+            rows = W.gen_cache_block(cfg, which, b, L, W.DEFAULT_SEED, "cuda")
+            packed, sz = O.quantize_rows_u4(bits(rows))
+            assert np.array_equal(case.cache.codes(which, b)[:, :L].cpu().numpy(), packed)
+            assert np.array_equal(case.cache.scales(which, b)[:, :L].cpu().numpy(), sz)
+            assert bool((case.cache.codes(which, b)[:, L:] == 0).all())
+            assert bool((case.cache.scales(which, b)[:, L:] == 0).all())
 
 
 EDGE_LENS = [0, 1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513,
@@ -208,20 +208,15 @@ def test_capacity_overflow_reset_and_bad_bits():
         rpart.fd_kvq_append(bad, case.k_new, case.v_new)
 
 
-@pytest.mark.parametrize("name", ["c2_7b_uniform", "c3_7b_ragged", "c4_13b_geometric", "c5_capacity"])
-def test_full_config_sampled_parity(name):
-    cfg = W.CONFIGS[name]
-    lens = W.seq_lens(cfg)
-    n_tok = W.total_tokens_after_append(lens)
-    print(f"{name}: building 4-bit cache for {n_tok} tokens", flush=True)
-    case = Q4Case(cfg, lens, extra_cap=8)
-    case.ws = case.cache.workspace(n_tok)
-    order = np.argsort(lens, kind="stable")
-    batch = sorted({int(order[0]), int(order[-1]), int(order[len(lens) // 2]), int(order[len(lens) // 3])})
-    err, maxv = check_q4step(case, batch=batch)
-    print(f"{name}: max|err|={err:.3e} max|V|={maxv:.2f} plan={rpart.fd_plan_info(case.ws)}", flush=True)
-    assert case.cache.seq_lens.cpu().tolist() == [L + 1 for L in lens]
-    assert bool(torch.isfinite(case.out.float()).all())
+@pytest.mark.parametrize("name,n_sample", [("c2_7b_uniform", None), ("c3_7b_ragged", None),
+                                           ("c4_13b_geometric", None), ("c5_capacity", 256)])
+def test_full_config_whole_batch_parity(name, n_sample):
+    """Every sequence of configs 2-4 (256 length-stratified ones of config 5) through the oracle:
+    the oracle quantises the generator's rows itself, so the device's code bytes and row
+    parameters (written by fd_kvq_store_rows and fd_kvq_append) are compared bit for bit too."""
+    from tests.full_parity import check_full_config
+    err, maxv, done = check_full_config(name, "int4", n_sample)
+    assert done == (W.CONFIGS[name].B if n_sample is None else n_sample)
 
 
 def test_long_context_few_sequences():

@@ -78,22 +78,19 @@ def _cfg(name, B, H, **kw):
     return W.RPartConfig(name, B, H, 128, "const", 0, 0, **kw)
 
 
-def test_fill_helper_prepares_a_valid_quantised_cache():
-    """The torch helper that pre-fills caches is input preparation, not the product's quantiser
-    (torch's device division is not correctly rounded, so its scales may be 1 ulp off the
-    binary32 definition): whatever it stores IS the input, and the oracle gets a copy of it.
-    It still has to be a sensible int8 cache: dequantised rows within half a step of the source."""
+def test_bulk_store_quantises_like_the_oracle():
+    """Caches are pre-filled through fd_kvq_store_rows (prompt ingestion): the code bytes and
+    scales it stores are the oracle quantiser's, bit for bit, rows outside the range untouched."""
     cfg = _cfg("fill", 2, 3)
-    case = QCase(cfg, [300, 77])
+    case = QCase(cfg, [300, 77], extra_cap=5)
     for b, L in enumerate(case.lens0):
         for which in ("K", "V"):
-            rows = W.gen_cache_block(cfg, which, b, L, W.DEFAULT_SEED, "cuda").double()
-            codes = case.cache.codes(which, b)[:, :L].double() - 128
-            scales = case.cache.scales(which, b)[:, :L].double()
-            assert float(codes.abs().max()) <= 127
-            assert bool(((codes * scales[..., None] - rows).abs() <= 0.51 * scales[..., None]).all())
-            ref = rows.abs().amax(dim=-1) / 127
-            assert bool(((scales - ref).abs() <= ref * 2.0 ** -22).all())
+            rows = W.gen_cache_block(cfg, which, b, L, W.DEFAULT_SEED, "cuda")
+            codes, scales = O.quantize_rows_i8(bits(rows))
+            assert np.array_equal(case.cache.codes(which, b)[:, :L].cpu().numpy(), codes)
+            assert np.array_equal(case.cache.scales(which, b)[:, :L].cpu().numpy(), scales)
+            assert bool((case.cache.codes(which, b)[:, L:] == 128).all())       # as allocated
+            assert bool((case.cache.scales(which, b)[:, L:] == 0).all())
 
 
 EDGE_LENS = [0, 1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1000, 2500]
@@ -193,21 +190,15 @@ def test_invalid_arguments():
         rpart.fd_rpartq_decode(case.cache.desc, case.q, case.out, case.ws[:1024])
 
 
-@pytest.mark.parametrize("name", ["c2_7b_uniform", "c3_7b_ragged", "c4_13b_geometric", "c5_capacity"])
-def test_full_config_sampled_parity(name):
-    cfg = W.CONFIGS[name]
-    lens = W.seq_lens(cfg)
-    n_tok = W.total_tokens_after_append(lens)
-    print(f"{name}: building int8 cache for {n_tok} tokens", flush=True)
-    case = QCase(cfg, lens, extra_cap=8)
-    case.ws = case.cache.workspace(n_tok)
-    order = np.argsort(lens, kind="stable")
-    batch = sorted({int(order[0]), int(order[-1]), int(order[len(lens) // 2]), int(order[len(lens) // 3])})
-    err, maxv = check_qstep(case, batch=batch)
-    print(f"{name}: max|err|={err:.3e} max|V|={maxv:.2f} plan={rpart.fd_plan_info(case.ws)}", flush=True)
-    assert case.cache.seq_lens.cpu().tolist() == [L + 1 for L in lens]
-    out = case.out.float()
-    assert bool(torch.isfinite(out).all())
+@pytest.mark.parametrize("name,n_sample", [("c2_7b_uniform", None), ("c3_7b_ragged", None),
+                                           ("c4_13b_geometric", None), ("c5_capacity", 256)])
+def test_full_config_whole_batch_parity(name, n_sample):
+    """Every sequence of configs 2-4 (256 length-stratified ones of config 5) through the oracle:
+    the oracle quantises the generator's rows itself, so the device's code bytes and row
+    parameters (written by fd_kvq_store_rows and fd_kvq_append) are compared bit for bit too."""
+    from tests.full_parity import check_full_config
+    err, maxv, done = check_full_config(name, "int8", n_sample)
+    assert done == (W.CONFIGS[name].B if n_sample is None else n_sample)
 
 
 def test_long_context_few_sequences():
