@@ -2,8 +2,8 @@
 """Throughput of the R-Part decode step on one MI355X.
 
 A step is one pass of the whole hot path over one batch: restore the cached
-lengths, append the new k/v rows, plan the ragged split, stream K/V (split-K
-partial attention), merge.  Inputs are synthetic, seeded, resident in HBM before
+lengths, append the new k/v rows and plan the ragged split (one launch), stream
+K/V (split-K attention with the log-sum-exp merge folded in; the second launch).  Inputs are synthetic, seeded, resident in HBM before
 the timed region starts.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c2_7b_uniform]
@@ -329,10 +329,7 @@ def main() -> int:
     bytes_per_token = kv_bytes_per_token(cfg, args.kv)
     kv_bytes = bytes_per_token * n_tok
     q8 = args.kv != "fp16"
-    f_append = rpart.fd_kvq_append if q8 else rpart.fd_kv_append
-    f_plan = rpart.fd_rpartq_plan if q8 else rpart.fd_rpart_plan
     f_partial = rpart.fd_rpartq_partial if q8 else rpart.fd_rpart_partial
-    f_merge = rpart.fd_rpartq_merge if q8 else rpart.fd_rpart_merge
 
     cache, vec = build_case(cfg, lens, seed, args.chunk_tokens, kv=args.kv, capacity=args.capacity, window=args.window,
                             sinks=args.sinks)
@@ -348,17 +345,16 @@ def main() -> int:
           if k % 4 == 0 else None for k in range(args.steps)]
 
     def step(pair=None):
+        # the two launches of fd_rpart_step, issued separately so that events can bracket the second
         cache.seq_lens.copy_(lens0)                # every step is the quoted config: L cached + 1 appended
         if seen0 is not None:
             cache.seq_seen.copy_(seen0)
-        f_append(desc, vec["k_new"], vec["v_new"])
-        f_plan(desc, ws)
+        rpart.fd_kv_append_plan(desc, vec["k_new"], vec["v_new"], ws)
         if pair:
             pair[0].record()
         f_partial(desc, vec["q"], out, ws)
         if pair:
             pair[1].record()
-        f_merge(desc, out, ws)
 
     if args.copy_calibration_mib > 0:
         src = torch.ones(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda")

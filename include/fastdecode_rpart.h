@@ -132,13 +132,13 @@ int fd_kv_append(const fd_kv_desc *desc, const void *k_new, const void *v_new, v
  *   out: device fp16 [B][H][d], 16-byte aligned.
  *   workspace: device, 256-byte aligned, workspace_bytes long; contents are
  *     scratch (plan tables and split-K partial states) and need no initialisation.
- * Equivalent to fd_rpart_plan, fd_rpart_partial, fd_rpart_merge in that order.
+ * Two launches: fd_rpart_plan, then fd_rpart_partial.
  */
 int fd_rpart_decode(const fd_kv_desc *desc, const void *q, void *out,
                     void *workspace, size_t workspace_bytes, void *stream);
 
 /*
- * The three stages of fd_rpart_decode, exposed so that a harness can time them
+ * The stages of fd_rpart_decode, exposed so that a harness can time them
  * separately.  They must be enqueued in this order on one stream with the same
  * descriptor and workspace.  partial and merge check that the workspace holds a plan
  * made for the same B, H, head dimension, cache format and workspace size and for no more
@@ -147,17 +147,33 @@ int fd_rpart_decode(const fd_kv_desc *desc, const void *q, void *out,
  * other lengths gives wrong results but no access outside a sequence's block.
  *   plan:    reads seq_lens on the device, cuts every sequence into chunks and
  *            writes the work-item table into the workspace.
- *   partial: streams each chunk's K and V rows once; per (b,h,chunk) produces
- *            the running max, the sum of exponentials and the unnormalised
- *            weighted value sum; writes `out` directly for single-chunk sequences.
- *   merge:   log-sum-exp merge of a sequence's chunk states, normalisation,
- *            rounding to fp16; also writes zeros for empty sequences.
+ *   partial: the whole attention.  Streams each chunk's K and V rows once; per (b,h,chunk)
+ *            produces the running max, the sum of exponentials and the unnormalised weighted
+ *            value sum.  A sequence of one chunk is normalised and written to `out` at once.
+ *            For a split sequence the chunk states go to the workspace, and the wave that
+ *            finishes the last chunk of a (sequence, head) merges them (log-sum-exp merge,
+ *            normalisation, rounding to fp16) in chunk order: the result does not depend on
+ *            which wave that is, and no merge launch is needed.  Empty sequences get zeros.
+ *   merge:   optional.  Recomputes `out` of every split sequence from the chunk states left in
+ *            the workspace (the same arithmetic in the same order: the same bits) and writes
+ *            zeros for empty sequences.  The decode and step entry points do not launch it.
  */
 int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_bytes, void *stream);
 int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
                      void *workspace, size_t workspace_bytes, void *stream);
 int fd_rpart_merge(const fd_kv_desc *desc, void *out,
                    void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * fd_kv_append and fd_rpart_plan in ONE launch (the front half of a step): workgroup 0 plans
+ * the decode for the lengths the sequences have after the append, which it derives from the old
+ * lengths by the append's own rule, while the other workgroups append.  seq_lens (and seq_seen)
+ * are NOT updated by this launch: the new values are kept in the workspace and stored by the
+ * next fd_rpart_partial on this workspace, so fd_rpart_partial must follow on the same stream
+ * before anything else reads seq_lens.  Errors are reported as by fd_kv_append.
+ */
+int fd_kv_append_plan(const fd_kv_desc *desc, const void *k_new, const void *v_new,
+                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * fd_rpart_decode for callers that cannot allocate device memory or hand over a workspace:
@@ -180,7 +196,8 @@ int fd_rpart_merge(const fd_kv_desc *desc, void *out,
 #define FD_NOALLOC_SCRATCH_BYTES (64u << 20)
 int fd_rpart_decode_noalloc(const fd_kv_desc *desc, const void *q, void *out, void *stream);
 
-/* fd_kv_append followed by fd_rpart_decode (one R-worker step of Section 4.1). */
+/* One R-worker step of Section 4.1: append, then attend.  Two launches: fd_kv_append_plan, then
+ * fd_rpart_partial.  Same results as fd_kv_append followed by fd_rpart_decode. */
 int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, const void *v_new,
                   void *out, void *workspace, size_t workspace_bytes, void *stream);
 
@@ -285,6 +302,8 @@ typedef struct fd_kvq_desc {
  * Eq. 2 + Eq. 3 over the dequantised rows with fp32 arithmetic and an fp16 result; workspace size comes from fd_workspace_bytes(B, H, 128, n).
  */
 int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new, void *stream);
+int fd_kvq_append_plan(const fd_kvq_desc *desc, const void *k_new, const void *v_new,
+                       void *workspace, size_t workspace_bytes, void *stream);
 int fd_kvq_store_rows(const fd_kvq_desc *desc, int32_t b, int32_t t0, int32_t n, const void *k_rows,
                       const void *v_rows, int set_len, void *stream);
 int fd_kvq_reset(const fd_kvq_desc *desc, const int32_t *seq_ids, int32_t n, void *stream);

@@ -37,16 +37,20 @@ constexpr float kNegBig = -1.0e30f;    // "no token seen yet" running max (finit
 
 // header words
 enum { HDR_NITEMS = 0, HDR_CHUNK = 2, HDR_TOKENS = 3, HDR_GRID = 4, HDR_MAGIC = 5, HDR_B = 6,
-       HDR_H = 7, HDR_MAXITEMS = 8, HDR_WAVE_UNITS = 9, HDR_KIND = 10, HDR_STATUS_OUT = 16 };
+       HDR_H = 7, HDR_MAXITEMS = 8, HDR_WAVE_UNITS = 9, HDR_KIND = 10, HDR_BUMP = 11,
+       HDR_STATUS_OUT = 16 };
 // cache format a plan was made for: head dimension and bits per element (16 = fp16)
 constexpr int plan_kind(int d, int bits) { return d | (bits << 16); }
-constexpr int32_t kPlanMagic = 0x46445250;
+constexpr int32_t kPlanMagic = 0x46445251;
 
 struct WsLayout {
     size_t off_item0;     // int32[B]  first item of sequence b
     size_t off_nchunk;    // int32[B]  chunks of sequence b
+    size_t off_newlen;    // int32[B]  length of sequence b after the step's append (fused append + plan)
+    size_t off_newseen;   // int32[B]  tokens seen by sequence b after that append (windowed caches)
     size_t off_items;     // int4[max_items]  {b, t0, t1, n_chunks_of_b}, chunks of a sequence adjacent
     size_t off_order;     // int32[max_items] item indices, longest chunk first (the schedule)
+    size_t off_cnt;       // int32[max_items][H]  finished chunks of a split (sequence, head), at its first item
     size_t off_acc;       // float[max_items][H][d]  unnormalised weighted value sums (512 B records)
     size_t off_ml;        // float[max_items][H][2]  {running max, sum of exponentials}
     int64_t max_items;
@@ -55,7 +59,7 @@ struct WsLayout {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-inline size_t ws_per_item(int H, int d) { return 16 + 4 + (size_t)H * (size_t)(d + 2) * 4; }
+inline size_t ws_per_item(int H, int d) { return 16 + 4 + (size_t)H * 4 + (size_t)H * (size_t)(d + 2) * 4; }
 
 inline WsLayout ws_layout(int B, int H, int d, size_t ws_bytes)
 {
@@ -65,69 +69,119 @@ inline WsLayout ws_layout(int B, int H, int d, size_t ws_bytes)
     o = align_up(o + (size_t)B * 4, 256);
     w.off_nchunk = o;
     o = align_up(o + (size_t)B * 4, 256);
+    w.off_newlen = o;
+    o = align_up(o + (size_t)B * 4, 256);
+    w.off_newseen = o;
+    o = align_up(o + (size_t)B * 4, 256);
     w.off_items = o;
     const size_t per_item = ws_per_item(H, d);
-    const size_t slop = 4 * 256;                         // alignment of the four arrays
+    const size_t slop = 5 * 256;                         // alignment of the five arrays
     w.min_bytes = o + slop + (size_t)(B > 0 ? B : 1) * per_item;
     w.max_items = 0;
-    w.off_order = w.off_acc = w.off_ml = 0;
+    w.off_order = w.off_cnt = w.off_acc = w.off_ml = 0;
     if (ws_bytes < w.min_bytes) return w;
     w.max_items = (int64_t)((ws_bytes - o - slop) / per_item);
     if (w.max_items > (int64_t)0x3FFFFFFF) w.max_items = 0x3FFFFFFF;
     const size_t n = (size_t)w.max_items;
     w.off_order = align_up(w.off_items + n * 16, 256);
-    w.off_acc = align_up(w.off_order + n * 4, 256);
+    w.off_cnt = align_up(w.off_order + n * 4, 256);
+    w.off_acc = align_up(w.off_cnt + n * (size_t)H * 4, 256);
     w.off_ml = align_up(w.off_acc + n * (size_t)H * (size_t)d * 4, 256);
     return w;
 }
 
-// ---------------------------------------------------------------------------
-// Append (Section 4.1).  One workgroup per sequence: 2*H rows of d fp16 are
-// copied as raw 128-bit words, then one thread bumps the length.
-// ---------------------------------------------------------------------------
-// Row that the new token of sequence b goes to, and the sequence's length afterwards; -1 if
-// the append is skipped (free slot, full plain cache, inconsistent window state).  Uniform
-// over the workgroup; thread 0 reports errors.
-__device__ inline int append_row(const int32_t *seq_lens, const int32_t *seq_cap,
-                                 const int32_t *seq_seen, int n_sink, int32_t *status, int b,
-                                 int *new_len)
+// The plan as the kernels see it: pointers into the workspace.
+struct PlanView {
+    int32_t *hdr, *item0, *nchunk, *newlen, *newseen;
+    int4 *items;
+    int32_t *order, *cnt;
+    float *acc, *ml;
+    int max_items;
+};
+
+inline PlanView plan_view(void *workspace, const WsLayout &w)
 {
-    const int L = seq_lens[b];
-    const int cap = seq_cap[b];
+    char *ws = (char *)workspace;
+    PlanView v;
+    v.hdr = (int32_t *)ws;
+    v.item0 = (int32_t *)(ws + w.off_item0);
+    v.nchunk = (int32_t *)(ws + w.off_nchunk);
+    v.newlen = (int32_t *)(ws + w.off_newlen);
+    v.newseen = (int32_t *)(ws + w.off_newseen);
+    v.items = (int4 *)(ws + w.off_items);
+    v.order = (int32_t *)(ws + w.off_order);
+    v.cnt = (int32_t *)(ws + w.off_cnt);
+    v.acc = (float *)(ws + w.off_acc);
+    v.ml = (float *)(ws + w.off_ml);
+    v.max_items = (int)w.max_items;
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// Append (Section 4.1).
+// ---------------------------------------------------------------------------
+// Where the new token of a sequence goes: the row, or -1 when the append is skipped (free slot,
+// full plain cache, inconsistent window state; *err is the FD_ST_* bit to report, 0 for a free
+// slot).  *new_len / *new_seen: the length and the tokens seen after the append (unchanged when
+// it is skipped).  L = seq_lens[b], cap = seq_cap[b], p = seq_seen[b] (windowed caches only).
+__device__ inline int append_rule(int L, int cap, bool windowed, int p, int n_sink, int *new_len,
+                                  int *new_seen, int *err)
+{
+    *new_len = L;
+    *new_seen = p;
+    *err = 0;
     if (L == FD_SLOT_FREE) return -1;
-    if (!seq_seen) {
+    if (!windowed) {
         if (L < 0 || L >= cap) {
-            if (threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
+            *err = FD_ST_CAPACITY;
             return -1;
         }
         *new_len = L + 1;
         return L;
     }
     // windowed cache: a bounded buffer of n_sink fixed rows and a ring of cap - n_sink rows
-    const int p = seq_seen[b];
     if (n_sink < 0 || n_sink >= cap || p < 0 || L != (p < cap ? p : cap)) {
-        if (threadIdx.x == 0) atomicOr(status, FD_ST_WINDOW);
+        *err = FD_ST_WINDOW;
         return -1;
     }
     *new_len = p + 1 < cap ? p + 1 : cap;
+    *new_seen = p + 1;
     return p < cap ? p : n_sink + (p - n_sink) % (cap - n_sink);
 }
 
-__global__ __launch_bounds__(256) void kv_append_kernel(
-    uint4 *__restrict__ k_base, uint4 *__restrict__ v_base,
-    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
-    int32_t *__restrict__ seq_lens, int32_t *__restrict__ status,
-    const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new, int H, int d,
-    int32_t *__restrict__ seq_seen, int n_sink)
+// What the append kernels are told about the cache's bookkeeping arrays.
+struct SeqState {
+    const int64_t *seq_off;
+    const int32_t *seq_cap;
+    int32_t *seq_lens, *seq_seen, *status;
+    int n_sink;
+};
+
+// Row that the new token of sequence b goes to, -1 if the append is skipped.  Uniform over the
+// workgroup; thread 0 reports errors.
+__device__ inline int append_row(const SeqState &st, int b, int *new_len)
 {
-    const int b = blockIdx.x;
-    const int cap = seq_cap[b];
+    int new_seen, err;
+    const int row = append_rule(st.seq_lens[b], st.seq_cap[b], st.seq_seen != nullptr,
+                                st.seq_seen ? st.seq_seen[b] : 0, st.n_sink, new_len, &new_seen, &err);
+    if (err && threadIdx.x == 0) atomicOr(st.status, err);
+    return row;
+}
+
+// One workgroup per sequence: 2*H rows of d fp16 are copied as raw 128-bit words.  With `bump`
+// one thread then stores the new length; without it the lengths are left alone and take effect
+// later (the fused append + plan launch: its planner works from the old lengths).
+__device__ inline void kv_append_body(uint4 *__restrict__ k_base, uint4 *__restrict__ v_base,
+                                      const SeqState &st, const uint4 *__restrict__ k_new,
+                                      const uint4 *__restrict__ v_new, int H, int d, int b, bool bump)
+{
+    const int cap = st.seq_cap[b];
     int new_len = 0;
-    const int L = append_row(seq_lens, seq_cap, seq_seen, n_sink, status, b, &new_len);
+    const int L = append_row(st, b, &new_len);
     if (L < 0) return;
     const int vpr = d / 8;                               // 16-byte words per row
     const int n = H * vpr;
-    const int64_t blk = seq_off[b] / 8;                  // block offset in 16-byte words
+    const int64_t blk = st.seq_off[b] / 8;               // block offset in 16-byte words
     const int64_t src0 = (int64_t)b * n;
     for (int x = threadIdx.x; x < 2 * n; x += blockDim.x) {
         const int which = x >= n;
@@ -137,11 +191,20 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
         if (which) v_base[dst] = v_new[src0 + y];
         else       k_base[dst] = k_new[src0 + y];
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        seq_lens[b] = new_len;
-        if (seq_seen) seq_seen[b] += 1;
+    if (bump) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            st.seq_lens[b] = new_len;
+            if (st.seq_seen) st.seq_seen[b] += 1;
+        }
     }
+}
+
+__global__ __launch_bounds__(256) void kv_append_kernel(
+    uint4 *__restrict__ k_base, uint4 *__restrict__ v_base, SeqState st,
+    const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new, int H, int d)
+{
+    kv_append_body(k_base, v_base, st, k_new, v_new, H, d, blockIdx.x, true);
 }
 
 // value = 0 starts an empty sequence in the slot, FD_SLOT_FREE marks the slot free
@@ -217,9 +280,23 @@ __global__ void status_clear_bits_kernel(int32_t *__restrict__ status, int32_t b
 // streaming kernel deals (item, head) units to workgroups in snake order, which
 // is the longest-processing-time rule for units that are small against a
 // workgroup's share.
+//
+// The planner can run in the same launch as the step's append (workgroup 0 plans, the others
+// append): it then works from the lengths the sequences will have AFTER that append, which it
+// derives from the old lengths by the append's own rule, stores them for the streaming kernel
+// to put into seq_lens, and no kernel of that launch writes seq_lens, so nothing races.
 // ---------------------------------------------------------------------------
 constexpr int kShortSeq = 384;      // a sequence under this many tokens is latency-bound ("short")
 constexpr int kBuckets = 256;
+
+struct PlanArgs {
+    const int32_t *seq_lens, *seq_cap, *seq_seen;
+    int32_t *status;
+    int n_sink;
+    int after_append;     // plan for the lengths after one append (fused launch); else for seq_lens as it stands
+    int B, H, chunk_req, granule, grid_long, grid_short, short_below, hashed, wave_units, split, kind;
+    PlanView v;
+};
 
 __device__ inline int block_sum(int v, int *sm)
 {
@@ -258,6 +335,19 @@ __device__ inline int clamp_len(int L, int cap, int *bad)
     return L;
 }
 
+// tokens of sequence b that the plan covers
+__device__ inline int plan_len(const PlanArgs &a, int b, int *bad)
+{
+    int L = a.seq_lens[b];
+    const int cap = a.seq_cap[b];
+    if (a.after_append) {
+        int new_seen, err;
+        append_rule(L, cap, a.seq_seen != nullptr, a.seq_seen ? a.seq_seen[b] : 0, a.n_sink, &L,
+                    &new_seen, &err);
+    }
+    return clamp_len(L, cap, bad);
+}
+
 __device__ inline int length_bucket(int len, int T)
 {
     int k = (int)(((long long)(T - len) * kBuckets) / T);   // longest chunks in bucket 0
@@ -276,26 +366,28 @@ __device__ inline void chunk_span(int L, int n, int granule, int k, int *t0, int
 constexpr int kBigChunks = 16;      // a sequence cut into more chunks than this ...
 constexpr int kBigMax = 128;        // ... goes on a list of at most this many entries
 
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(
-    const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ seq_cap,
-    int32_t *__restrict__ status, int B, int H, int chunk_req, int granule, int grid_long, int grid_short,
-    int short_below, int hashed, int wave_units, int split, int kind, int max_items,
-    int32_t *__restrict__ hdr, int32_t *__restrict__ item0, int32_t *__restrict__ nchunk,
-    int4 *__restrict__ items, int32_t *__restrict__ order)
+// the whole workgroup (kPlanThreads threads) must call this
+__device__ inline void plan_body(const PlanArgs &a)
 {
     __shared__ int sm[kPlanThreads];
     __shared__ int hist[kBuckets];
     __shared__ int4 big[kBigMax];
     __shared__ int nbig, big_nmax;
+    const int B = a.B, H = a.H, granule = a.granule, max_items = a.v.max_items;
+    int32_t *__restrict__ item0 = a.v.item0;
+    int32_t *__restrict__ nchunk = a.v.nchunk;
+    int4 *__restrict__ items = a.v.items;
+    int32_t *__restrict__ order = a.v.order;
+    int32_t *__restrict__ cnt = a.v.cnt;
     const int tid = threadIdx.x;
     const int per = (B + kPlanThreads - 1) / kPlanThreads;   // sequences per thread (contiguous)
     const int b0 = tid * per;
     const int b1 = min(B, b0 + per);
 
     int bad = 0, mine = 0;
-    for (int b = b0; b < b1; ++b) mine += clamp_len(seq_lens[b], seq_cap[b], &bad);
+    for (int b = b0; b < b1; ++b) mine += plan_len(a, b, &bad);
     const int total = block_sum(mine, sm);
-    if (bad) atomicOr(status, FD_ST_BADLEN);
+    if (bad) atomicOr(a.status, FD_ST_BADLEN);
 
     // One workgroup per CU streams long sequences best (a second one costs 1-2 %); a sequence of
     // a few blocks is dominated by its fixed cost, and more workgroups per CU hide that.  Measured
@@ -307,23 +399,25 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     // workgroups at or beyond `grid` leave at once.
     int few = 0;
     for (int b = b0; b < b1; ++b) {
-        const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
-        few += L < short_below ? L : 0;
+        const int L = plan_len(a, b, &bad);
+        few += L < a.short_below ? L : 0;
     }
     few = block_sum(few, sm);
     const bool many_short = (long long)few * 10 > (long long)total;
-    const int grid = many_short ? grid_short : grid_long;
+    const int grid = many_short ? a.grid_short : a.grid_long;
     // wave_units: 0 = the workgroup's waves always share a unit, 1 = each wave takes units of its
     // own when the batch holds many short sequences, 2 = always
-    const int wave_now = wave_units == 2 || (wave_units == 1 && many_short);
+    const int wave_now = a.wave_units == 2 || (a.wave_units == 1 && many_short);
 
     int T;
-    if (chunk_req > 0) {
-        T = chunk_req;
+    if (a.chunk_req > 0) {
+        T = a.chunk_req;
     } else {
         // token-heads per worker: a workgroup, or a wave when each wave takes units of its own
+        // (a wave's share is a quarter of a workgroup's: it is cut into quarters at most, or half
+        // of a batch of a few hundred tokens per sequence would end up split)
         const long long share = (long long)total * H / ((long long)grid * (wave_now ? kWaves : 1));
-        long long t = share / split;
+        long long t = share / (wave_now && a.split > 4 ? 4 : a.split);
         T = (int)(t < 128 ? 128 : (t > (1 << 28) ? (1 << 28) : t));
     }
     T = (T + granule - 1) / granule * granule;
@@ -332,7 +426,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     for (;;) {
         int c = 0;
         for (int b = b0; b < b1; ++b) {
-            const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+            const int L = plan_len(a, b, &bad);
             c += (L + T - 1) / T;
         }
         count = block_sum(c, sm);
@@ -343,7 +437,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     // exclusive scan of per-thread item counts
     int c = 0, c_big = 0;
     for (int b = b0; b < b1; ++b) {
-        const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+        const int L = plan_len(a, b, &bad);
         const int n = (L + T - 1) / T;
         c += n;
         c_big += n > kBigChunks;
@@ -357,10 +451,19 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int first = block_exclusive_scan(c, sm);      // its barriers also publish hist = 0
     int pos = first;
     for (int b = b0; b < b1; ++b) {
-        const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+        const int L = plan_len(a, b, &bad);
         const int n = (L + T - 1) / T;
         item0[b] = pos;
         nchunk[b] = n;
+        if (a.after_append) {
+            // what the append of this launch makes of the sequence's bookkeeping; the streaming
+            // kernel stores it into seq_lens / seq_seen
+            int new_len, new_seen, err;
+            append_rule(a.seq_lens[b], a.seq_cap[b], a.seq_seen != nullptr,
+                        a.seq_seen ? a.seq_seen[b] : 0, a.n_sink, &new_len, &new_seen, &err);
+            a.v.newlen[b] = new_len;
+            a.v.newseen[b] = new_seen;
+        }
         if (use_list && n > kBigChunks) {
             big[atomicAdd(&nbig, 1)] = make_int4(b, L, n, pos);
             atomicMax(&big_nmax, n);
@@ -373,6 +476,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
                     atomicAdd(&hist[length_bucket(t1 - t0, T)], 1);
                 }
             }
+            // a split sequence's heads count their finished chunks here (see finish_split)
+            if (n > 1 && pos < max_items)
+                for (int h = 0; h < H; ++h) cnt[(int64_t)pos * H + h] = 0;
         }
         pos += n;
     }
@@ -388,6 +494,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
                 atomicAdd(&hist[length_bucket(t1 - t0, T)], 1);
             }
         }
+        if (e.w < max_items)
+            for (int h = tid; h < H; h += kPlanThreads) cnt[(int64_t)e.w * H + h] = 0;
     }
     __syncthreads();
     // bucket starts = exclusive scan of the 256 counters, then scatter
@@ -408,7 +516,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const int half = (bits + 1) / 2;
     for (int j = b0; j < b1; ++j) {
         int b = j;
-        if (hashed) {
+        if (a.hashed) {
             unsigned x = (unsigned)j;
             do {                                            // cycle-walk back into [0, B)
                 x = (x * 0x9E3779B1u) & mask;
@@ -421,7 +529,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         const int n = nchunk[b];
         const int base = item0[b];
         if (n > 0 && !(use_list && n > kBigChunks)) {
-            const int L = clamp_len(seq_lens[b], seq_cap[b], &bad);
+            const int L = plan_len(a, b, &bad);
             for (int k = 0; k < n; ++k) {
                 int t0, t1;
                 chunk_span(L, n, granule, k, &t0, &t1);
@@ -447,6 +555,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         }
     }
     if (tid == 0) {
+        int32_t *hdr = a.v.hdr;
         hdr[HDR_NITEMS] = count <= max_items ? count : 0;
         hdr[HDR_CHUNK] = T;
         hdr[HDR_TOKENS] = total;
@@ -456,8 +565,21 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
         hdr[HDR_H] = H;
         hdr[HDR_MAXITEMS] = max_items;
         hdr[HDR_WAVE_UNITS] = wave_now;
-        hdr[HDR_KIND] = kind;
+        hdr[HDR_KIND] = a.kind;
+        hdr[HDR_BUMP] = a.after_append;
     }
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_kernel(PlanArgs a) { plan_body(a); }
+
+// One launch for the front of a step: workgroup 0 plans the decode for the lengths after the
+// append, workgroups 1 .. B append (sequence blockIdx.x - 1) without touching seq_lens.
+__global__ __launch_bounds__(kPlanThreads) void kv_append_plan_kernel(
+    uint4 *__restrict__ k_base, uint4 *__restrict__ v_base, SeqState st,
+    const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new, int d, PlanArgs a)
+{
+    if (blockIdx.x == 0) plan_body(a);
+    else kv_append_body(k_base, v_base, st, k_new, v_new, a.H, d, (int)blockIdx.x - 1, false);
 }
 
 // The streaming and the merge kernels index the caller's slabs with what the plan tables say:
@@ -482,6 +604,8 @@ __device__ inline bool plan_matches(const int32_t *hdr, int B, int H, int kind, 
 // Split-K streaming attention (Eq. 2 + Eq. 3 over one chunk of one (b,h)).
 // ---------------------------------------------------------------------------
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float fvec4 __attribute__((ext_vector_type(4)));
+typedef _Float16 hvec4 __attribute__((ext_vector_type(4)));
 
 template <int CTRL>
 __device__ inline float dpp_xadd(float x)
@@ -511,19 +635,271 @@ __device__ inline half8 ld_stream(const char *p)
     return __builtin_nontemporal_load(reinterpret_cast<const half8 *>(p));
 }
 
-// One tile = this wave's share of a workgroup block.  A block is kWaves * NL
-// consecutive wave loads (1 KB each) of the K stream and of the V stream; wave w
-// takes loads w, w + kWaves, ...: the workgroup reads the block as one contiguous
-// run with its waves interleaved at 1 KB, and every wave gets the same number of
-// loads whatever the chunk length.
-template <int D, int NL>
+// Where a unit of work (one chunk of one head's stream) lives; uniform over the wave.
+struct Unit {
+    int64_t row0;            // element offset (fp16) or row index (codes) of the chunk's first row
+    int ntok;                // tokens in the chunk; 0 = no unit
+    int b, h, item, nch;     // sequence, head, item index, chunks of the sequence
+};
+
+// What a streaming kernel does before its first unit, by workgroup (blockIdx.x < active
+// workgroups, sequences dealt round-robin): a sequence without tokens gets a zero output, and
+// after a fused append + plan launch the new lengths are put into seq_lens (absolute values:
+// doing it twice changes nothing).
+template <int D>
+__device__ inline void unit_prologue(const int32_t *__restrict__ hdr, const int32_t *__restrict__ nchunk,
+                                     const int32_t *__restrict__ newlen, const int32_t *__restrict__ newseen,
+                                     int32_t *__restrict__ seq_lens, int32_t *__restrict__ seq_seen,
+                                     _Float16 *__restrict__ out, int B, int H)
+{
+    const int Wg = hdr[HDR_GRID];
+    const int bump = hdr[HDR_BUMP];
+    for (int b = blockIdx.x; b < B; b += Wg) {
+        if (bump && threadIdx.x == 0) {
+            seq_lens[b] = newlen[b];
+            if (seq_seen) seq_seen[b] = newseen[b];
+        }
+        if (nchunk[b] == 0) {
+            uint4 *o = reinterpret_cast<uint4 *>(out + (int64_t)b * H * D);
+            for (int x = threadIdx.x; x < H * (D / 8); x += blockDim.x) o[x] = make_uint4(0, 0, 0, 0);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Chunk states of split sequences travel between workgroups that may sit on different XCDs,
+// whose L2 caches are not coherent with each other.  A device-scope fence would write back and
+// invalidate a whole L2 (measured: one pair of fences per split unit cost a geometric length mix
+// 15 % and a batch of half-split sequences a factor of three).  Instead every access to a chunk
+// state or to a chunk counter is itself a device-scope access (relaxed atomics of agent scope:
+// stores go through to memory, loads come from there), and order is kept by waiting for the
+// wave's stores to complete before its counter increments are issued.
+// ---------------------------------------------------------------------------
+__device__ inline void st_agent(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float ld_agent(const float *p)
+{
+    return __hip_atomic_load(const_cast<float *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+typedef float fvec2 __attribute__((ext_vector_type(2)));
+// 128 bits of a chunk state as two 64-bit device-scope loads
+__device__ inline fvec4 ld_agent4(const fvec4 *p)
+{
+    union { unsigned long long u; fvec2 f; } lo, hi;
+    unsigned long long *q = reinterpret_cast<unsigned long long *>(const_cast<fvec4 *>(p));
+    lo.u = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    hi.u = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return fvec4{lo.f[0], lo.f[1], hi.f[0], hi.f[1]};
+}
+
+// ---------------------------------------------------------------------------
+// Log-sum-exp merge of the chunk states of one (sequence, head) by one wave.
+// States are in the base-2 exponent domain used by the streaming kernels.
+//
+// A sequence that has the device to itself is cut into over a hundred chunks per head, so the
+// wave works on many chunk states at once: maxima and sums of exponentials one chunk per lane,
+// the weighted value sums four records per load (16 lanes x 128-bit per record) with sixteen
+// records in flight, and a cross-lane sum over the four groups at the end.  The order of the
+// arithmetic is fixed, so the result does not depend on which wave runs it or when.
+// rec0 = first record (chunk 0) of this (b,h); chunk c is record rec0 + c*H.  o = out + bh*D.
+// ---------------------------------------------------------------------------
+template <int D>
+__device__ inline void merge_states(int lane, int n, int64_t rec0, int H, const float *part_acc,
+                                    const float *part_ml, _Float16 *o)
+{
+    constexpr int NV = D / 64;                        // 128-bit pieces of a record per lane
+    const int t = lane & 15, g = lane >> 4;           // piece within the record, record within the load
+    float M = kNegBig;
+    for (int c0 = 0; c0 < n; c0 += 64) {
+        const int c = c0 + lane;
+        if (c < n) M = fmaxf(M, ld_agent(&part_ml[(rec0 + (int64_t)c * H) * 2]));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    float L = 0.f;
+    fvec4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) acc[v] = fvec4{0.f, 0.f, 0.f, 0.f};
+    const int64_t step = (int64_t)H * (D / 4);         // record stride of one chunk, in 128-bit pieces
+    for (int c0 = 0; c0 < n; c0 += 64) {
+        const int c = c0 + lane;
+        float w = 0.f;
+        if (c < n) {
+            const int64_t rec = rec0 + (int64_t)c * H;
+            w = fast_exp2(ld_agent(&part_ml[rec * 2]) - M);
+            L += w * ld_agent(&part_ml[rec * 2 + 1]);
+        }
+        const int nb = min(64, n - c0);
+        const fvec4 *pa = (const fvec4 *)(part_acc + (rec0 + (int64_t)c0 * H) * D) + t;
+        for (int j0 = 0; j0 < nb; j0 += 16) {
+            fvec4 x[4][NV];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = min(j0 + u * 4 + g, nb - 1);   // past the end: a valid record, weight 0
+#pragma unroll
+                for (int v = 0; v < NV; ++v) x[u][v] = ld_agent4(pa + j * step + v * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u * 4 + g;
+                float wj = __shfl(w, j & 63);
+                wj = j < nb ? wj : 0.f;
+#pragma unroll
+                for (int v = 0; v < NV; ++v) acc[v] += wj * x[u][v];
+            }
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off);
+#pragma unroll
+    for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float a = acc[v][i];
+            a += __shfl_xor(a, 16);
+            a += __shfl_xor(a, 32);
+            acc[v][i] = a;
+        }
+    if (g == 0) {                                     // lanes of group 0 write elements v*64 + t*4 ..
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            hvec4 r;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = (_Float16)(acc[v][i] / L);
+            *(hvec4 *)(o + t * 4 + v * 64) = r;
+        }
+    }
+}
+
+// A sequence cut into few chunks (the usual case: a ragged batch splits only its longest
+// sequences, in two to four) leaves the wave-wide merge above almost idle and bound by the
+// latency of its dependent loads.  This form merges up to four (sequence, head) pairs at once,
+// one per 16-lane group, chunk after chunk in chunk order, with all loads of a pair issued
+// together.  Which form merges a pair depends only on its number of chunks (kSmallMerge), so
+// the result still does not depend on who merges it.  `active`, n, rec0, o: per 16-lane group.
+constexpr int kSmallMerge = 4;
+
+template <int D>
+__device__ inline void merge_states_small(int lane, bool active, int n, int64_t rec0, int H,
+                                          const float *part_acc, const float *part_ml, _Float16 *o)
+{
+    constexpr int NV = D / 64;
+    const int t = lane & 15;
+    float mc[kSmallMerge], lc[kSmallMerge];
+    fvec4 x[kSmallMerge][NV];
+    const int64_t step = (int64_t)H * (D / 4);
+    const fvec4 *pa = (const fvec4 *)(part_acc + rec0 * D) + t;
+#pragma unroll
+    for (int c = 0; c < kSmallMerge; ++c) {
+        const bool on = active && c < n;
+        mc[c] = on ? ld_agent(&part_ml[(rec0 + (int64_t)c * H) * 2]) : kNegBig;
+        lc[c] = on ? ld_agent(&part_ml[(rec0 + (int64_t)c * H) * 2 + 1]) : 0.f;
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+            x[c][v] = on ? ld_agent4(pa + c * step + v * 16) : fvec4{0.f, 0.f, 0.f, 0.f};
+    }
+    float M = kNegBig;
+#pragma unroll
+    for (int c = 0; c < kSmallMerge; ++c) M = fmaxf(M, mc[c]);
+    float L = 0.f;
+    fvec4 acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) acc[v] = fvec4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < kSmallMerge; ++c) {
+        const float w = (active && c < n) ? fast_exp2(mc[c] - M) : 0.f;
+        L += w * lc[c];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) acc[v] += w * x[c][v];
+    }
+    if (active) {
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            hvec4 r;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = (_Float16)(acc[v][i] / L);
+            *(hvec4 *)(o + t * 4 + v * 64) = r;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The merge is folded into the streaming kernel, so a step needs no merge launch.  A wave that
+// writes chunk states of split sequences notes them on a short list in LDS ({b, h, chunks, first
+// item}).  When it has no more units (or the list is full) it publishes them in one go: it waits
+// for its state stores to complete, then adds one to the counter of every listed (sequence,
+// head), all with a single batched atomic, so the round trip is paid once per wave and not once
+// per unit.  Whoever brings a counter to the sequence's chunk count has published, or seen
+// published, every chunk of that head: that wave merges them in chunk order and puts the counter
+// back to zero for the next launch on this plan.  Integer atomics only; the result does not
+// depend on who merges.
+// ---------------------------------------------------------------------------
+constexpr int kSplitList = 64;      // entries per publishing wave
+
+template <int D>
+__device__ __attribute__((noinline)) void publish_split(int lane, const int4 *list, int n, int H, int32_t *cnt,
+                                     const float *part_acc, const float *part_ml,
+                                     _Float16 *__restrict__ out)
+{
+    if (n == 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_waitcnt(0);                    // every chunk state store of this wave has completed
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    int4 e = make_int4(0, 0, 0, 0);
+    int last = 0;
+    if (lane < n) {
+        e = list[lane];
+        const int ticket = __hip_atomic_fetch_add(&cnt[(int64_t)e.w * H + e.y], 1, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
+        last = ticket == e.z - 1;
+    }
+    // pairs cut into few chunks: four at a time, one per 16-lane group
+    unsigned long long small = __ballot(last && e.z <= kSmallMerge);
+    unsigned long long large = __ballot(last && e.z > kSmallMerge);
+    const int grp = lane >> 4;
+    while (small) {
+        int src = -1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (small) {
+                const int bit = __ffsll((long long)small) - 1;
+                small &= small - 1;
+                if (grp == k) src = bit;
+            }
+        }
+        const int from = src < 0 ? 0 : src;
+        const int b = __shfl(e.x, from), h = __shfl(e.y, from), nch = __shfl(e.z, from);
+        const int64_t rec0 = (int64_t)__shfl(e.w, from) * H + h;
+        merge_states_small<D>(lane, src >= 0, nch, rec0, H, part_acc, part_ml, out + ((int64_t)b * H + h) * D);
+        if (src >= 0 && (lane & 15) == 0)
+            __hip_atomic_store(&cnt[rec0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    while (large) {
+        const int src = __ffsll((long long)large) - 1;
+        large &= large - 1;
+        const int b = __shfl(e.x, src), h = __shfl(e.y, src), nch = __shfl(e.z, src);
+        const int64_t rec0 = (int64_t)__shfl(e.w, src) * H + h;
+        merge_states<D>(lane, nch, rec0, H, part_acc, part_ml, out + ((int64_t)b * H + h) * D);
+        if (lane == 0) __hip_atomic_store(&cnt[rec0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// One tile = this wave's share of a block of a unit.  WPU = waves that stream a unit together:
+// kWaves (a block is kWaves * NL consecutive wave loads, 1 KB each, of the K stream and of the
+// V stream; wave w takes loads w, w + kWaves, ...: the workgroup reads the block as one
+// contiguous run with its waves interleaved at 1 KB, and every wave gets the same number of
+// loads whatever the chunk length) or 1 (the wave streams a unit of its own: NL consecutive
+// wave loads per block).
+template <int D, int NL, int WPU>
 struct Tile {
     static constexpr int LPR = D / 8;                    // lanes per row
     static constexpr int RPW = 64 / LPR;                 // rows (tokens) per wave load
-    static constexpr int STRIDE = kWaves * 1024;         // bytes between a wave's consecutive loads
-    static constexpr int TSTEP = kWaves * RPW;           // tokens between a wave's consecutive loads
-    static constexpr int BLK_TOK = NL * TSTEP;           // tokens per workgroup block
-    static constexpr int BLK_BYTES = NL * STRIDE;        // bytes of K (or V) per workgroup block
+    static constexpr int STRIDE = WPU * 1024;            // bytes between a wave's consecutive loads
+    static constexpr int TSTEP = WPU * RPW;              // tokens between a wave's consecutive loads
+    static constexpr int BLK_TOK = NL * TSTEP;           // tokens per block
+    static constexpr int BLK_BYTES = NL * STRIDE;        // bytes of K (or V) per block
     half8 k[NL], v[NL];
 
     __device__ inline void load(const char *kp, const char *vp)
@@ -534,31 +910,44 @@ struct Tile {
         for (int j = 0; j < NL; ++j) v[j] = ld_stream(vp + j * STRIDE);
     }
 
-    // ragged last block of `rem` tokens: a lane whose token (tok0 + j*TSTEP) is at or beyond
-    // `rem` re-reads token rem-1 (in bounds) and is masked in update<true>
-    __device__ inline void load_tail(const char *kp, const char *vp, int tok0, int rem)
+    // Ragged last block of `rem` tokens.  Only the wave's first nj loads hold a valid row (nj is
+    // the same for every lane of the wave): the others are neither issued nor computed, so a
+    // rest of a few tokens costs a few tokens' work.  Within a load, a lane whose token
+    // (tok0 + j*TSTEP) is at or beyond `rem` re-reads token rem-1 (in bounds) and is masked.
+    __device__ static inline int tail_loads(int wave_tok0, int rem)
+    {
+        const int n = (rem - wave_tok0 + TSTEP - 1) / TSTEP;
+        return n < 0 ? 0 : (n > NL ? NL : n);
+    }
+    __device__ inline void load_tail(const char *kp, const char *vp, int tok0, int rem, int nj)
     {
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            const int t = j * TSTEP + tok0;
-            const int back = t < rem ? 0 : (t - (rem - 1)) * (D * 2);
-            k[j] = ld_stream(kp + j * STRIDE - back);
-            v[j] = ld_stream(vp + j * STRIDE - back);
+            if (j < nj) {
+                const int t = j * TSTEP + tok0;
+                const int back = t < rem ? 0 : (t - (rem - 1)) * (D * 2);
+                k[j] = ld_stream(kp + j * STRIDE - back);
+                v[j] = ld_stream(vp + j * STRIDE - back);
+            }
         }
     }
 
+    // MASKED: the ragged last block (tok0, rem, nj as for load_tail); otherwise all NL loads count
     template <bool MASKED>
     __device__ inline void update(const float (&q)[8], float &m, float &l, float (&acc)[8],
-                                  int tok0, int rem) const
+                                  int tok0, int rem, int nj) const
     {
         float s[NL];
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            float a = 0.f;
+            float a = kNegBig;
+            if (!MASKED || j < nj) {
+                a = 0.f;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) a = __builtin_fmaf((float)k[j][i], q[i], a);
-            a = row_sum<LPR>(a);
-            if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
+                for (int i = 0; i < 8; ++i) a = __builtin_fmaf((float)k[j][i], q[i], a);
+                a = row_sum<LPR>(a);
+                if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
+            }
             s[j] = a;
         }
         float tm = s[0];
@@ -571,55 +960,77 @@ struct Tile {
         for (int i = 0; i < 8; ++i) acc[i] *= corr;
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            float p = fast_exp2(s[j] - mn);
-            if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
-            l += p;
+            if (!MASKED || j < nj) {
+                float p = fast_exp2(s[j] - mn);
+                if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
+                l += p;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(p, (float)v[j][i], acc[i]);
+                for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(p, (float)v[j][i], acc[i]);
+            }
         }
         m = mn;
     }
 };
 
-// Where a unit of work (one chunk of one head's stream) lives; uniform over the workgroup.
-struct Unit {
-    int64_t row0;            // element offset of the chunk's first row in the K / V slab
-    int ntok;                // tokens in the chunk; 0 = no unit
-    int b, h, item, nch;     // sequence, head, item index, chunks of the sequence
+// Everything the fp16 streaming kernel is given.
+struct PartialArgs {
+    const char *k_base, *v_base;
+    const int64_t *seq_off;
+    const int32_t *seq_cap;
+    int32_t *seq_lens, *seq_seen, *status;
+    const _Float16 *q;
+    _Float16 *out;
+    int B, H;
+    float qscale;
+    PlanView v;
 };
 
-template <int D, int NL>
-__global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
-    const char *__restrict__ k_base, const char *__restrict__ v_base,
-    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
-    const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
-    const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
-    const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
-    float qscale, int B, int max_items, int32_t *__restrict__ status)
+template <int D, int NL, int WPU>
+__device__ __forceinline__ void rpart_body(const PartialArgs &a)
 {
-    using T = Tile<D, NL>;
+    using T = Tile<D, NL, WPU>;
     constexpr int LPR = T::LPR;
     // two sets, used by alternate units: one barrier per unit is then enough (a wave cannot
     // overwrite a set before every wave has passed the barrier of the unit in between)
     __shared__ float sm_acc2[2][kWaves][D];
     __shared__ float sm_m2[2][kWaves], sm_l2[2][kWaves];
+    __shared__ int4 sm_split[kWaves][kSplitList];        // chunk states written but not yet published
     int set = 0;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const char *__restrict__ k_base = a.k_base;
+    const char *__restrict__ v_base = a.v_base;
+    const int64_t *__restrict__ seq_off = a.seq_off;
+    const int32_t *__restrict__ seq_cap = a.seq_cap;
+    const _Float16 *__restrict__ q = a.q;
+    _Float16 *__restrict__ out = a.out;
+    const int32_t *__restrict__ hdr = a.v.hdr;
+    const int4 *__restrict__ items = a.v.items;
+    const int32_t *__restrict__ order = a.v.order;
+    float *part_acc = a.v.acc;
+    float *part_ml = a.v.ml;
+    const int H = a.H;
+
+    const int lane = threadIdx.x & 63;
+    // the wave's number is the same in all its lanes: kept in a scalar register, so that everything
+    // derived from it (the unit, its addresses, the loop counts) is scalar as well
+    const int wave_id = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int wave = WPU == 1 ? 0 : wave_id;                     // position among the unit's waves
+    const int tid = wave * 64 + lane;                            // thread index among them
     const int row = lane / LPR;
     const int col = lane % LPR;
-    if (!plan_matches(hdr, B, H, plan_kind(D, 16), max_items, (int)gridDim.x, status)) return;
     const int n_units = hdr[HDR_NITEMS] * H;
-    const int W = hdr[HDR_GRID], g = blockIdx.x;          // active workgroups, chosen by the planner
+    // workers (workgroups, or single waves) that the planner's grid amounts to, and this one
+    const int W = hdr[HDR_GRID] * (kWaves / WPU);
+    const int g = WPU == 1 ? (int)(blockIdx.x * kWaves) + wave_id : (int)blockIdx.x;
     if (g >= W) return;
+    int4 *split_list = sm_split[wave_id];
+    int n_split = 0;
 
-    // Static snake schedule over units in longest-first order: in round k this workgroup
+    // Static snake schedule over units in longest-first order: in round k this worker
     // owns unit k*W + g (even k) or k*W + W-1-g (odd k), which balances the token totals.
-    // The workgroups walk their rounds from kPhases different starting points, so that at
+    // The workers walk their rounds from kPhases different starting points, so that at
     // any moment long and short units are in flight together: short units are dominated by
-    // latency, and letting every workgroup reach them at once would leave HBM idle (+3 % on
+    // latency, and letting every worker reach them at once would leave HBM idle (+3 % on
     // exponentially distributed lengths).  More phases spread the reads over more of the
     // cache at once, which costs about 1 % on uniform lengths; four keeps both.
     const int n_rounds = (int)(((long long)n_units + W - 1) / W);
@@ -653,7 +1064,11 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
     int j = 0;
     Unit cur = fetch(0);
     if (cur.ntok == 0 && n_rounds > 1) cur = fetch(++j);
-    while (cur.ntok > 0) {
+    // The units are walked in stretches: a stretch ends when the wave has no more units or its list
+    // of unpublished chunk states is full; the states are then published (the call sits outside
+    // the unit loop, so that it does not constrain the registers of the streaming code).
+    for (;;) {
+    while (cur.ntok > 0 && n_split < kSplitList) {
         // the next unit's descriptor (three dependent scalar loads) is fetched while this
         // unit streams
         Unit nxt = fetch(++j);
@@ -667,7 +1082,7 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
         {
             const half8 qh = *reinterpret_cast<const half8 *>(q + ((int64_t)b * H + h) * D + col * 8);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) qf[i] = (float)qh[i] * qscale;
+            for (int i = 0; i < 8; ++i) qf[i] = (float)qh[i] * a.qscale;
         }
 
         float m = kNegBig, l = 0.f, acc[8];
@@ -675,7 +1090,7 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
         for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
         const int ntok = cur.ntok;
-        const int n_blk = ntok / T::BLK_TOK;              // full workgroup blocks
+        const int n_blk = ntok / T::BLK_TOK;              // full blocks
         const int rem = ntok - n_blk * T::BLK_TOK;        // tokens of the ragged last block
 
         // ping-pong register buffers: the next block's loads are in flight while the current
@@ -690,11 +1105,11 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
             while (i + 2 < n_blk) {
                 Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES);
                 sched_fence();
-                A.template update<false>(qf, m, l, acc, 0, 0);
+                A.template update<false>(qf, m, l, acc, 0, 0, 0);
                 sched_fence();
                 A.load(kt + 2 * T::BLK_BYTES, vt + 2 * T::BLK_BYTES);
                 sched_fence();
-                Bf.template update<false>(qf, m, l, acc, 0, 0);
+                Bf.template update<false>(qf, m, l, acc, 0, 0, 0);
                 sched_fence();
                 kt += 2 * T::BLK_BYTES;
                 vt += 2 * T::BLK_BYTES;
@@ -703,19 +1118,20 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
             if (i + 1 < n_blk) {
                 Bf.load(kt + T::BLK_BYTES, vt + T::BLK_BYTES);
                 sched_fence();
-                A.template update<false>(qf, m, l, acc, 0, 0);
+                A.template update<false>(qf, m, l, acc, 0, 0, 0);
                 sched_fence();
-                Bf.template update<false>(qf, m, l, acc, 0, 0);
+                Bf.template update<false>(qf, m, l, acc, 0, 0, 0);
             } else {
-                A.template update<false>(qf, m, l, acc, 0, 0);
+                A.template update<false>(qf, m, l, acc, 0, 0, 0);
             }
         }
         if (rem > 0) {
-            const int tok0 = wave * T::RPW + row;
-            if (wave * T::RPW < rem) {                    // this wave has at least one valid row
+            const int nj = T::tail_loads(wave * T::RPW, rem);
+            if (nj > 0) {                                 // this wave has at least one valid row
+                const int tok0 = wave * T::RPW + row;
                 const int64_t o = (int64_t)n_blk * T::BLK_BYTES;
-                A.load_tail(kp + o, vp + o, tok0, rem);
-                A.template update<true>(qf, m, l, acc, tok0, rem);
+                A.load_tail(kp + o, vp + o, tok0, rem, nj);
+                A.template update<true>(qf, m, l, acc, tok0, rem, nj);
             }
         }
 
@@ -725,150 +1141,157 @@ __global__ __launch_bounds__(kThreads) void rpart_partial_kernel(
             const float mo = __shfl_xor(m, off);
             const float lo = __shfl_xor(l, off);
             const float M = fmaxf(m, mo);
-            const float a = fast_exp2(m - M), c = fast_exp2(mo - M);
-            l = l * a + lo * c;
+            const float wa = fast_exp2(m - M), wc = fast_exp2(mo - M);
+            l = l * wa + lo * wc;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = acc[i] * a + __shfl_xor(acc[i], off) * c;
+            for (int i = 0; i < 8; ++i) acc[i] = acc[i] * wa + __shfl_xor(acc[i], off) * wc;
             m = M;
         }
-        float (&sm_acc)[kWaves][D] = sm_acc2[set];
-        float (&sm_m)[kWaves] = sm_m2[set];
-        float (&sm_l)[kWaves] = sm_l2[set];
-        set ^= 1;
-        if (lane < LPR) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) sm_acc[wave][lane * 8 + i] = acc[i];
-        }
-        if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; }
-        __syncthreads();
-
-        // combine the waves; write the final output or this chunk's partial state.  Stores
-        // are non-temporal: they are never re-read by this kernel, and plain stores were
+        // Stores are non-temporal: they are never re-read by this unit, and plain stores were
         // measured to cost the read stream about three times as much bandwidth.
-        if (tid < D) {
-            float M = sm_m[0];
-#pragma unroll
-            for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
-            float L = 0.f, o = 0.f;
-#pragma unroll
-            for (int w = 0; w < kWaves; ++w) {
-                const float a = fast_exp2(sm_m[w] - M);
-                L += a * sm_l[w];
-                o += a * sm_acc[w][tid];
-            }
+        if constexpr (WPU == 1) {
+            // the wave owns the unit: every lane holds the state of all rows for its 8 columns;
+            // the lanes of row 0 write them
             if (cur.nch == 1) {
-                __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
+                if (lane < LPR) {
+                    half8 o8;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) o8[i] = (_Float16)(acc[i] / l);
+                    __builtin_nontemporal_store(o8, reinterpret_cast<half8 *>(out + ((int64_t)b * H + h) * D + lane * 8));
+                }
             } else {
                 const int64_t rec = (int64_t)cur.item * H + h;
-                __builtin_nontemporal_store(o, &part_acc[rec * D + tid]);
-                if (tid == 0) {
-                    __builtin_nontemporal_store(M, &part_ml[rec * 2]);
-                    __builtin_nontemporal_store(L, &part_ml[rec * 2 + 1]);
+                if (lane < LPR) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) st_agent(&part_acc[rec * D + lane * 8 + i], acc[i]);
+                    if (lane == 0) {
+                        st_agent(&part_ml[rec * 2], m);
+                        st_agent(&part_ml[rec * 2 + 1], l);
+                    }
                 }
+                if (lane == 0) split_list[n_split] = make_int4(b, h, cur.nch, a.v.item0[b]);
+                ++n_split;
             }
+        } else {
+            float (&sm_acc)[kWaves][D] = sm_acc2[set];
+            float (&sm_m)[kWaves] = sm_m2[set];
+            float (&sm_l)[kWaves] = sm_l2[set];
+            set ^= 1;
+            if (lane < LPR) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) sm_acc[wave][lane * 8 + i] = acc[i];
+            }
+            if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; }
+            __syncthreads();
+
+            // combine the waves; write the final output, or this chunk's state
+            if (cur.nch == 1) {
+                if (tid < D) {
+                    float M = sm_m[0];
+#pragma unroll
+                    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
+                    float L = 0.f, o = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) {
+                        const float wa = fast_exp2(sm_m[w] - M);
+                        L += wa * sm_l[w];
+                        o += wa * sm_acc[w][tid];
+                    }
+                    __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
+                }
+            } else if (wave == 0) {
+                // one wave writes the whole state (element lane, and lane + 64) and will publish it
+                float M = sm_m[0];
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
+                float L = 0.f, wgt[kWaves];
+#pragma unroll
+                for (int w = 0; w < kWaves; ++w) {
+                    wgt[w] = fast_exp2(sm_m[w] - M);
+                    L += wgt[w] * sm_l[w];
+                }
+                const int64_t rec = (int64_t)cur.item * H + h;
+#pragma unroll
+                for (int e = lane; e < D; e += 64) {
+                    float o = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) o += wgt[w] * sm_acc[w][e];
+                    st_agent(&part_acc[rec * D + e], o);
+                }
+                if (lane == 0) {
+                    st_agent(&part_ml[rec * 2], M);
+                    st_agent(&part_ml[rec * 2 + 1], L);
+                }
+                if (lane == 0) split_list[n_split] = make_int4(b, h, cur.nch, a.v.item0[b]);
+            }
+            // counted by every wave of the workgroup (they all leave the stretch together)
+            if (cur.nch != 1) ++n_split;
         }
         cur = nxt;                     // no second barrier: the next unit uses the other LDS set
     }
+    // the chunk states written in this stretch are published, and merged where this wave is the
+    // last to publish a chunk of a (sequence, head)
+    if (WPU == 1 || wave == 0)
+        publish_split<D>(lane, split_list, n_split, H, a.v.cnt, part_acc, part_ml, out);
+    n_split = 0;
+    if (cur.ntok == 0) break;
+    }
+}
+
+// Whether each wave of the fp16 streaming kernel takes units of its own when the batch holds
+// many short sequences (the planner's wave_units argument).  Measured against workgroup units
+// with two workgroups per CU: 256 tokens per sequence -1.1 %, lengths uniform in 1..1024 -1.0 %
+// (streaming kernel time), so it stays off: the fp16 unit streams four times the bytes of a 4-bit
+// one against the same fixed cost, and two resident workgroups already hide that cost.
+constexpr int kWaveUnitsFp16 = 0;
+
+// One kernel, two bodies: the planner decides per launch whether a workgroup's four waves share
+// a unit or take one each (short sequences: a unit's fixed cost, the epilogue with its barrier
+// and cross-wave combine, is then spread over four times as many blocks per wave).
+template <int D, int NL>
+__global__ __launch_bounds__(kThreads) void rpart_partial_kernel(PartialArgs a)
+{
+    const int32_t *hdr = a.v.hdr;
+    if (!plan_matches(hdr, a.B, a.H, plan_kind(D, 16), a.v.max_items, (int)gridDim.x, a.status)) return;
+    if ((int)blockIdx.x >= hdr[HDR_GRID]) return;
+    unit_prologue<D>(hdr, a.v.nchunk, a.v.newlen, a.v.newseen, a.seq_lens, a.seq_seen, a.out, a.B, a.H);
+    if constexpr (kWaveUnitsFp16 != 0) {
+        if (hdr[HDR_WAVE_UNITS]) {
+            rpart_body<D, NL, 1>(a);
+            return;
+        }
+    }
+    rpart_body<D, NL, kWaves>(a);
 }
 
 // ---------------------------------------------------------------------------
-// Log-sum-exp merge of a sequence's chunk states; one wave per (b,h).
-// States are in the base-2 exponent domain used by the streaming kernel.
-//
-// A sequence that has the device to itself is cut into over a hundred chunks per head, so the
-// wave works on many chunk states at once: maxima and sums of exponentials one chunk per lane,
-// the weighted value sums four records per load (16 lanes x 128-bit per record) with sixteen
-// records in flight, and a cross-lane sum over the four groups at the end.
+// Stand-alone merge, one wave per (b,h): recomputes `out` of every split sequence from the chunk
+// states in the workspace, in the same order as the streaming kernel's own merge (same bits),
+// and writes zeros for empty sequences.  The decode entry points do not launch it.
 // ---------------------------------------------------------------------------
-typedef float fvec4 __attribute__((ext_vector_type(4)));
-typedef _Float16 hvec4 __attribute__((ext_vector_type(4)));
-
 template <int D>
-__global__ __launch_bounds__(256) void rpart_merge_kernel(
-    const int32_t *__restrict__ item0, const int32_t *__restrict__ nchunk,
-    const float *__restrict__ part_acc, const float *__restrict__ part_ml,
-    _Float16 *__restrict__ out, int B, int H, const int32_t *__restrict__ hdr, int kind,
-    int max_items, int32_t *__restrict__ status)
+__global__ __launch_bounds__(256) void rpart_merge_kernel(PlanView v, _Float16 *__restrict__ out, int B,
+                                                          int H, int kind, int32_t *__restrict__ status)
 {
-    constexpr int NV = D / 64;                        // 128-bit pieces of a record per lane
-    if (!plan_matches(hdr, B, H, kind, max_items, 0, status)) return;
+    if (!plan_matches(v.hdr, B, H, kind, v.max_items, 0, status)) return;
     const int lane = threadIdx.x & 63;
-    const int t = lane & 15, g = lane >> 4;           // piece within the record, record within the load
     const int64_t bh = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (bh >= (int64_t)B * H) return;
     const int b = (int)(bh / H);
     const int h = (int)(bh - (int64_t)b * H);
-    const int n = nchunk[b];
+    const int n = v.nchunk[b];
     if (n == 1) return;                               // written by the streaming kernel
-    _Float16 *o = out + bh * D + t * 4;               // lanes of group 0 write elements v*64 + t*4 ..
+    _Float16 *o = out + bh * D;
     if (n == 0) {
-        if (g == 0) {
+        if (lane < 16) {
 #pragma unroll
-            for (int v = 0; v < NV; ++v) *(hvec4 *)(o + v * 64) = hvec4{0, 0, 0, 0};
+            for (int p = 0; p < D / 64; ++p) *(hvec4 *)(o + lane * 4 + p * 64) = hvec4{0, 0, 0, 0};
         }
         return;
     }
-    const int64_t rec0 = (int64_t)item0[b] * H + h;   // chunk c of this (b,h) is record rec0 + c*H
-    float M = kNegBig;
-    for (int c0 = 0; c0 < n; c0 += 64) {
-        const int c = c0 + lane;
-        if (c < n) M = fmaxf(M, part_ml[(rec0 + (int64_t)c * H) * 2]);
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-    float L = 0.f;
-    fvec4 acc[NV];
-#pragma unroll
-    for (int v = 0; v < NV; ++v) acc[v] = fvec4{0.f, 0.f, 0.f, 0.f};
-    const int64_t step = (int64_t)H * (D / 4);         // record stride of one chunk, in 128-bit pieces
-    for (int c0 = 0; c0 < n; c0 += 64) {
-        const int c = c0 + lane;
-        float w = 0.f;
-        if (c < n) {
-            const int64_t rec = rec0 + (int64_t)c * H;
-            w = fast_exp2(part_ml[rec * 2] - M);
-            L += w * part_ml[rec * 2 + 1];
-        }
-        const int nb = min(64, n - c0);
-        const fvec4 *pa = (const fvec4 *)(part_acc + (rec0 + (int64_t)c0 * H) * D) + t;
-        for (int j0 = 0; j0 < nb; j0 += 16) {
-            fvec4 x[4][NV];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int j = min(j0 + u * 4 + g, nb - 1);   // past the end: a valid record, weight 0
-#pragma unroll
-                for (int v = 0; v < NV; ++v) x[u][v] = pa[j * step + v * 16];
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int j = j0 + u * 4 + g;
-                float wj = __shfl(w, j & 63);
-                wj = j < nb ? wj : 0.f;
-#pragma unroll
-                for (int v = 0; v < NV; ++v) acc[v] += wj * x[u][v];
-            }
-        }
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off);
-#pragma unroll
-    for (int v = 0; v < NV; ++v)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float a = acc[v][i];
-            a += __shfl_xor(a, 16);
-            a += __shfl_xor(a, 32);
-            acc[v][i] = a;
-        }
-    if (g == 0) {
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            hvec4 r;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = (_Float16)(acc[v][i] / L);
-            *(hvec4 *)(o + v * 64) = r;
-        }
-    }
+    const int64_t rec0 = (int64_t)v.item0[b] * H + h;
+    if (n <= kSmallMerge) merge_states_small<D>(lane, lane < 16, n, rec0, H, v.acc, v.ml, o);
+    else merge_states<D>(lane, n, rec0, H, v.acc, v.ml, o);
 }
 
 // ---------------------------------------------------------------------------
@@ -925,8 +1348,6 @@ int check_ws(const fd_kv_desc *d, const void *ws, size_t ws_bytes, WsLayout *w)
     return FD_OK;
 }
 
-// tokens per workgroup block of the streaming kernel = chunk granule of the planner
-int block_tokens(int d) { return kWaves * kTileLoads * (d == 128 ? 4 : 8); }
 // chunk boundaries are multiples of this many tokens (one wave load of rows)
 int chunk_granule(int d) { return d == 128 ? 32 : 64; }
 
@@ -962,6 +1383,82 @@ void *scratch_address()
     }
     __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
     return p;
+}
+
+SeqState seq_state(const fd_kv_desc *d)
+{
+    SeqState st;
+    st.seq_off = d->seq_off;
+    st.seq_cap = d->seq_cap;
+    st.seq_lens = d->seq_lens;
+    st.seq_seen = d->seq_seen;
+    st.status = d->status;
+    st.n_sink = d->n_sink;
+    return st;
+}
+
+
+PlanArgs plan_args(const fd_kv_desc *d, void *workspace, const WsLayout &w, int grid, int after_append)
+{
+    PlanArgs a;
+    a.seq_lens = d->seq_lens;
+    a.seq_cap = d->seq_cap;
+    a.seq_seen = d->seq_seen;
+    a.status = d->status;
+    a.n_sink = d->n_sink;
+    a.after_append = after_append;
+    a.B = d->B;
+    a.H = d->H;
+    a.chunk_req = d->chunk_tokens;
+    a.granule = chunk_granule(d->d);
+    a.grid_long = grid;
+    a.grid_short = 2 * grid;
+    a.short_below = kShortSeq;
+    a.hashed = 0;
+    a.wave_units = kWaveUnitsFp16;
+    a.split = 16;
+    a.kind = plan_kind(d->d, 16);
+    a.v = plan_view(workspace, w);
+    return a;
+}
+
+// the streaming launch; every argument has been checked
+int launch_partial(const fd_kv_desc *desc, const void *q, void *out, void *workspace,
+                   const WsLayout &w, int grid, void *stream)
+{
+    PartialArgs a;
+    a.k_base = (const char *)desc->k_base;
+    a.v_base = (const char *)desc->v_base;
+    a.seq_off = desc->seq_off;
+    a.seq_cap = desc->seq_cap;
+    a.seq_lens = desc->seq_lens;
+    a.seq_seen = desc->seq_seen;
+    a.status = desc->status;
+    a.q = (const _Float16 *)q;
+    a.out = (_Float16 *)out;
+    a.B = desc->B;
+    a.H = desc->H;
+    // scores are kept in the base-2 exponent domain: exp(x) = 2^(x * log2 e)
+    a.qscale = (float)(1.4426950408889634 / (desc->d == 128 ? 11.313708498984761 : 8.0));
+    a.v = plan_view(workspace, w);
+    if (desc->d == 128)
+        hipLaunchKernelGGL((rpart_partial_kernel<128, kTileLoads>), dim3(2 * grid), dim3(kThreads), 0,
+                           (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL((rpart_partial_kernel<64, kTileLoads>), dim3(2 * grid), dim3(kThreads), 0,
+                           (hipStream_t)stream, a);
+    return launched();
+}
+
+// host checks shared by the entry points that take q, out and a workspace
+int check_decode_args(const fd_kv_desc *desc, const void *q, const void *out, const void *workspace,
+                      size_t workspace_bytes, WsLayout *w)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
+    return check_ws(desc, workspace, workspace_bytes, w);
 }
 
 } // namespace
@@ -1003,9 +1500,27 @@ int fd_kv_append(const fd_kv_desc *desc, const void *k_new, const void *v_new, v
     if (desc->B == 0) return FD_OK;
     if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
     hipLaunchKernelGGL(kv_append_kernel, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
-                       (uint4 *)desc->k_base, (uint4 *)desc->v_base, desc->seq_off, desc->seq_cap,
-                       desc->seq_lens, desc->status, (const uint4 *)k_new, (const uint4 *)v_new,
-                       desc->H, desc->d, desc->seq_seen, desc->n_sink);
+                       (uint4 *)desc->k_base, (uint4 *)desc->v_base, seq_state(desc),
+                       (const uint4 *)k_new, (const uint4 *)v_new, desc->H, desc->d);
+    return launched();
+}
+
+int fd_kv_append_plan(const fd_kv_desc *desc, const void *k_new, const void *v_new,
+                      void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_desc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
+    WsLayout w;
+    rc = check_ws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    hipLaunchKernelGGL(kv_append_plan_kernel, dim3(desc->B + 1), dim3(kPlanThreads), 0,
+                       (hipStream_t)stream, (uint4 *)desc->k_base, (uint4 *)desc->v_base,
+                       seq_state(desc), (const uint4 *)k_new, (const uint4 *)v_new, desc->d,
+                       plan_args(desc, workspace, w, grid, 1));
     return launched();
 }
 
@@ -1044,49 +1559,20 @@ int fd_rpart_plan(const fd_kv_desc *desc, void *workspace, size_t workspace_byte
     if (rc != FD_OK) return rc;
     const int grid = persistent_grid();
     if (grid <= 0) return FD_EHIP;
-    char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
-                       desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, chunk_granule(desc->d), grid, 2 * grid, kShortSeq, 0, 0,
-                       16 /* split */, plan_kind(desc->d, 16),
-                       (int)w.max_items, (int32_t *)ws,
-                       (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
-                       (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
+                       plan_args(desc, workspace, w, grid, 0));
     return launched();
 }
 
 int fd_rpart_partial(const fd_kv_desc *desc, const void *q, void *out,
                      void *workspace, size_t workspace_bytes, void *stream)
 {
-    int rc = check_desc(desc);
-    if (rc != FD_OK) return rc;
-    if (desc->B == 0) return FD_OK;
-    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
     WsLayout w;
-    rc = check_ws(desc, workspace, workspace_bytes, &w);
-    if (rc != FD_OK) return rc;
+    int rc = check_decode_args(desc, q, out, workspace, workspace_bytes, &w);
+    if (rc != FD_OK || desc->B == 0) return rc;
     const int grid = persistent_grid();
     if (grid <= 0) return FD_EHIP;
-    char *ws = (char *)workspace;
-    // scores are kept in the base-2 exponent domain: exp(x) = 2^(x * log2 e)
-    const float qscale = (float)(1.4426950408889634 / (desc->d == 128 ? 11.313708498984761 : 8.0));
-    if (desc->d == 128)
-        hipLaunchKernelGGL((rpart_partial_kernel<128, kTileLoads>), dim3(2 * grid), dim3(kThreads), 0,
-                           (hipStream_t)stream, (const char *)desc->k_base,
-                           (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
-                           (const _Float16 *)q, (_Float16 *)out, desc->H, (const int32_t *)ws,
-                           (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
-                           (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale, desc->B,
-                           (int)w.max_items, desc->status);
-    else
-        hipLaunchKernelGGL((rpart_partial_kernel<64, kTileLoads>), dim3(2 * grid), dim3(kThreads), 0,
-                           (hipStream_t)stream, (const char *)desc->k_base,
-                           (const char *)desc->v_base, desc->seq_off, desc->seq_cap,
-                           (const _Float16 *)q, (_Float16 *)out, desc->H, (const int32_t *)ws,
-                           (const int4 *)(ws + w.off_items), (const int32_t *)(ws + w.off_order),
-                           (float *)(ws + w.off_acc), (float *)(ws + w.off_ml), qscale, desc->B,
-                           (int)w.max_items, desc->status);
-    return launched();
+    return launch_partial(desc, q, out, workspace, w, grid, stream);
 }
 
 int fd_rpart_merge(const fd_kv_desc *desc, void *out,
@@ -1099,21 +1585,15 @@ int fd_rpart_merge(const fd_kv_desc *desc, void *out,
     WsLayout w;
     rc = check_ws(desc, workspace, workspace_bytes, &w);
     if (rc != FD_OK) return rc;
-    char *ws = (char *)workspace;
     const int64_t bh = (int64_t)desc->B * desc->H;
     const dim3 grid((unsigned)((bh + 3) / 4));
+    const PlanView v = plan_view(workspace, w);
     if (desc->d == 128)
-        hipLaunchKernelGGL(rpart_merge_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream,
-                           (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
-                           (const float *)(ws + w.off_acc), (const float *)(ws + w.off_ml),
-                           (_Float16 *)out, desc->B, desc->H, (const int32_t *)ws,
-                           plan_kind(128, 16), (int)w.max_items, desc->status);
+        hipLaunchKernelGGL(rpart_merge_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream, v,
+                           (_Float16 *)out, desc->B, desc->H, plan_kind(128, 16), desc->status);
     else
-        hipLaunchKernelGGL(rpart_merge_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream,
-                           (const int32_t *)(ws + w.off_item0), (const int32_t *)(ws + w.off_nchunk),
-                           (const float *)(ws + w.off_acc), (const float *)(ws + w.off_ml),
-                           (_Float16 *)out, desc->B, desc->H, (const int32_t *)ws,
-                           plan_kind(64, 16), (int)w.max_items, desc->status);
+        hipLaunchKernelGGL(rpart_merge_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream, v,
+                           (_Float16 *)out, desc->B, desc->H, plan_kind(64, 16), desc->status);
     return launched();
 }
 
@@ -1121,18 +1601,16 @@ int fd_rpart_decode(const fd_kv_desc *desc, const void *q, void *out,
                     void *workspace, size_t workspace_bytes, void *stream)
 {
     // validate everything before the first launch so that a failing call enqueues nothing
-    int rc = check_desc(desc);
-    if (rc != FD_OK) return rc;
-    if (desc->B == 0) return FD_OK;
-    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
     WsLayout w;
-    rc = check_ws(desc, workspace, workspace_bytes, &w);
+    int rc = check_decode_args(desc, q, out, workspace, workspace_bytes, &w);
+    if (rc != FD_OK || desc->B == 0) return rc;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
+                       plan_args(desc, workspace, w, grid, 0));
+    rc = launched();
     if (rc != FD_OK) return rc;
-    rc = fd_rpart_plan(desc, workspace, workspace_bytes, stream);
-    if (rc != FD_OK) return rc;
-    rc = fd_rpart_partial(desc, q, out, workspace, workspace_bytes, stream);
-    if (rc != FD_OK) return rc;
-    return fd_rpart_merge(desc, out, workspace, workspace_bytes, stream);
+    return launch_partial(desc, q, out, workspace, w, grid, stream);
 }
 
 int fd_rpart_decode_noalloc(const fd_kv_desc *desc, const void *q, void *out, void *stream)
@@ -1146,50 +1624,51 @@ int fd_rpart_decode_noalloc(const fd_kv_desc *desc, const void *q, void *out, vo
     if (w.max_items < desc->B) return FD_ETOOBIG;
     void *ws = scratch_address();
     if (!ws) return FD_EHIP;
-    // nothing in the array has to start at zero: the planner rewrites the header and every
-    // table entry the other kernels read, and chunk states are written before they are merged
+    // nothing in the array has to start at zero: the planner rewrites the header, every table
+    // entry and every counter the other kernels read, and chunk states are written before they
+    // are merged
     return fd_rpart_decode(desc, q, out, ws, FD_NOALLOC_SCRATCH_BYTES, stream);
+}
+
+// append + plan in one launch, then the streaming kernel: two launches per step
+static int step_fused(const fd_kv_desc *desc, const void *q, const void *k_new, const void *v_new,
+                      void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    WsLayout w;
+    int rc = check_decode_args(desc, q, out, workspace, workspace_bytes, &w);
+    if (rc != FD_OK || desc->B == 0) return rc;
+    if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    hipLaunchKernelGGL(kv_append_plan_kernel, dim3(desc->B + 1), dim3(kPlanThreads), 0,
+                       (hipStream_t)stream, (uint4 *)desc->k_base, (uint4 *)desc->v_base,
+                       seq_state(desc), (const uint4 *)k_new, (const uint4 *)v_new, desc->d,
+                       plan_args(desc, workspace, w, grid, 1));
+    rc = launched();
+    if (rc != FD_OK) return rc;
+    return launch_partial(desc, q, out, workspace, w, grid, stream);
 }
 
 int fd_rpart_step(const fd_kv_desc *desc, const void *q, const void *k_new, const void *v_new,
                   void *out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    int rc = check_desc(desc);
-    if (rc != FD_OK) return rc;
-    if (desc->B == 0) return FD_OK;
-    if (!q || !out || !k_new || !v_new || !aligned(q, 16) || !aligned(out, 16) ||
-        !aligned(k_new, 16) || !aligned(v_new, 16))
-        return FD_EINVAL;
-    WsLayout w;
-    rc = check_ws(desc, workspace, workspace_bytes, &w);
-    if (rc != FD_OK) return rc;
-    rc = fd_kv_append(desc, k_new, v_new, stream);
-    if (rc != FD_OK) return rc;
-    return fd_rpart_decode(desc, q, out, workspace, workspace_bytes, stream);
+    return step_fused(desc, q, k_new, v_new, out, workspace, workspace_bytes, stream);
 }
 
 int fd_rpart_layer_step(const fd_kv_desc *layer, const void *q, const void *k_new,
                         const void *v_new, void *out, void *workspace, size_t workspace_bytes,
                         int replan, void *stream)
 {
-    int rc = check_desc(layer);
-    if (rc != FD_OK) return rc;
-    if (layer->B == 0) return FD_OK;
-    if (!q || !out || !k_new || !v_new || !aligned(q, 16) || !aligned(out, 16) ||
-        !aligned(k_new, 16) || !aligned(v_new, 16))
-        return FD_EINVAL;
+    if (replan) return step_fused(layer, q, k_new, v_new, out, workspace, workspace_bytes, stream);
     WsLayout w;
-    rc = check_ws(layer, workspace, workspace_bytes, &w);
-    if (rc != FD_OK) return rc;
+    int rc = check_decode_args(layer, q, out, workspace, workspace_bytes, &w);
+    if (rc != FD_OK || layer->B == 0) return rc;
+    if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
     rc = fd_kv_append(layer, k_new, v_new, stream);
     if (rc != FD_OK) return rc;
-    if (replan) {
-        rc = fd_rpart_plan(layer, workspace, workspace_bytes, stream);
-        if (rc != FD_OK) return rc;
-    }
-    rc = fd_rpart_partial(layer, q, out, workspace, workspace_bytes, stream);
-    if (rc != FD_OK) return rc;
-    return fd_rpart_merge(layer, out, workspace, workspace_bytes, stream);
+    return launch_partial(layer, q, out, workspace, w, grid, stream);
 }
 
 int fd_hbm_read_probe(const void *buf, size_t bytes, int32_t *sink, size_t *bytes_read, void *stream)

@@ -113,41 +113,64 @@ __device__ inline void load_row_f32(const _Float16 *src, float (&f)[8])
 }
 
 // ---------------------------------------------------------------------------
-// Quantising append.  One workgroup per sequence, 16 rows in flight per pass.
+// Quantising append.  One workgroup per sequence, one row per 16 lanes per pass.  `bump` as in
+// the fp16 append: without it the lengths take effect later (fused append + plan launch).
 // ---------------------------------------------------------------------------
+struct QSlabs {
+    uint8_t *k_codes, *v_codes;
+    float *k_meta, *v_meta;
+};
+
 template <int BITS>
-__global__ __launch_bounds__(256) void kvq_append_kernel(
-    uint8_t *__restrict__ k_codes, uint8_t *__restrict__ v_codes,
-    float *__restrict__ k_meta, float *__restrict__ v_meta,
-    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
-    int32_t *__restrict__ seq_lens, int32_t *__restrict__ status,
-    const _Float16 *__restrict__ k_new, const _Float16 *__restrict__ v_new, int H,
-    int32_t *__restrict__ seq_seen, int n_sink)
+__device__ inline void kvq_append_body(const QSlabs &c, const SeqState &st,
+                                       const _Float16 *__restrict__ k_new,
+                                       const _Float16 *__restrict__ v_new, int H, int b, bool bump)
 {
     using F = QFmt<BITS>;
     constexpr int D = F::D;
-    const int b = blockIdx.x;
-    const int cap = seq_cap[b];
+    const int cap = st.seq_cap[b];
     int new_len = 0;
-    const int L = append_row(seq_lens, seq_cap, seq_seen, n_sink, status, b, &new_len);
+    const int L = append_row(st, b, &new_len);
     if (L < 0) return;
     const int sub = threadIdx.x & 15;          // position inside the 16-lane group of a row
     const int group = threadIdx.x >> 4;
-    const int64_t off = seq_off[b];
-    for (int r = group; r < 2 * H; r += 16) {
+    const int groups = blockDim.x >> 4;
+    const int64_t off = st.seq_off[b];
+    for (int r = group; r < 2 * H; r += groups) {
         const int which = r >= H;
         const int h = which ? r - H : r;
         float f[8];
         load_row_f32((which ? v_new : k_new) + ((int64_t)b * H + h) * D + sub * 8, f);
         const int64_t row = (int64_t)h * cap + L;
-        quantize_row_store<BITS>(f, sub, (which ? v_codes : k_codes) + off + row * F::RB,
-                                 (which ? v_meta : k_meta) + (off / F::RB + row) * F::MW);
+        quantize_row_store<BITS>(f, sub, (which ? c.v_codes : c.k_codes) + off + row * F::RB,
+                                 (which ? c.v_meta : c.k_meta) + (off / F::RB + row) * F::MW);
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        seq_lens[b] = new_len;
-        if (seq_seen) seq_seen[b] += 1;
+    if (bump) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            st.seq_lens[b] = new_len;
+            if (st.seq_seen) st.seq_seen[b] += 1;
+        }
     }
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void kvq_append_kernel(QSlabs c, SeqState st,
+                                                         const _Float16 *__restrict__ k_new,
+                                                         const _Float16 *__restrict__ v_new, int H)
+{
+    kvq_append_body<BITS>(c, st, k_new, v_new, H, blockIdx.x, true);
+}
+
+// front of a step in one launch: workgroup 0 plans for the lengths after the append, the
+// others append without touching seq_lens (see kv_append_plan_kernel)
+template <int BITS>
+__global__ __launch_bounds__(kPlanThreads) void kvq_append_plan_kernel(
+    QSlabs c, SeqState st, const _Float16 *__restrict__ k_new, const _Float16 *__restrict__ v_new,
+    PlanArgs a)
+{
+    if (blockIdx.x == 0) plan_body(a);
+    else kvq_append_body<BITS>(c, st, k_new, v_new, a.H, (int)blockIdx.x - 1, false);
 }
 
 // Bulk store of n consecutive token rows of one sequence (prompt ingestion): the same quantiser
@@ -564,25 +587,49 @@ __device__ inline int64_t uniform64(int64_t x)
     return (int64_t)(((unsigned long long)hi << 32) | lo);
 }
 
+// Everything the streaming kernel over codes is given.
+struct PartialQArgs {
+    const char *k_codes, *v_codes;
+    const float *k_meta, *v_meta;
+    const int64_t *seq_off;
+    const int32_t *seq_cap;
+    int32_t *seq_lens, *seq_seen, *status;
+    const _Float16 *q;
+    _Float16 *out;
+    int B, H;
+    float qscale;
+    PlanView v;
+};
+
 template <int BITS, int WPU>
-__device__ __forceinline__ void rpartq_body(
-    const char *__restrict__ k_codes, const char *__restrict__ v_codes,
-    const float *__restrict__ k_meta, const float *__restrict__ v_meta,
-    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
-    const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
-    const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
-    const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
-    float qscale)
+__device__ __forceinline__ void rpartq_body(const PartialQArgs &a)
 {
+    const char *__restrict__ k_codes = a.k_codes;
+    const char *__restrict__ v_codes = a.v_codes;
+    const float *__restrict__ k_meta = a.k_meta;
+    const float *__restrict__ v_meta = a.v_meta;
+    const int64_t *__restrict__ seq_off = a.seq_off;
+    const int32_t *__restrict__ seq_cap = a.seq_cap;
+    const _Float16 *__restrict__ q = a.q;
+    _Float16 *__restrict__ out = a.out;
+    const int32_t *__restrict__ hdr = a.v.hdr;
+    const int4 *__restrict__ items = a.v.items;
+    const int32_t *__restrict__ order = a.v.order;
+    float *part_acc = a.v.acc;
+    float *part_ml = a.v.ml;
+    const int H = a.H;
+    const float qscale = a.qscale;
     using T = TileQ<BITS, q_tile_loads<BITS>(), WPU>;
     constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL, RB = T::RB, MW = T::MW;
     // two sets, used by alternate units, so that one barrier per unit is enough
     __shared__ float sm_acc2[2][kWaves][D];
     __shared__ float sm_m2[2][kWaves], sm_l2[2][kWaves], sm_aux2[2][kWaves];
+    __shared__ int4 sm_split[kWaves][kSplitList];        // chunk states written but not yet published
     int set = 0;
 
     const int lane = threadIdx.x & 63;
-    const int wave = WPU == 1 ? 0 : (int)(threadIdx.x >> 6);     // position among the unit's waves
+    const int wave_id = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // scalar
+    const int wave = WPU == 1 ? 0 : wave_id;                     // position among the unit's waves
     const int tid = wave * 64 + lane;                            // thread index among them
     const int row = lane / LPR;
     const int col = lane % LPR;
@@ -590,8 +637,10 @@ __device__ __forceinline__ void rpartq_body(
     const int n_units = hdr[HDR_NITEMS] * H;
     // workers (workgroups, or single waves) that the planner's grid amounts to, and this one
     const int W = hdr[HDR_GRID] * (kWaves / WPU);
-    const int g = WPU == 1 ? (int)(blockIdx.x * kWaves + (threadIdx.x >> 6)) : (int)blockIdx.x;
+    const int g = WPU == 1 ? (int)(blockIdx.x * kWaves) + wave_id : (int)blockIdx.x;
     if (g >= W) return;
+    int4 *split_list = sm_split[wave_id];
+    int n_split = 0;
 
     // same static schedule as the fp16 kernel
     const int n_rounds = (int)(((long long)n_units + W - 1) / W);
@@ -628,7 +677,11 @@ __device__ __forceinline__ void rpartq_body(
     int j = 0;
     Unit cur = fetch(0);
     if (cur.ntok == 0 && n_rounds > 1) cur = fetch(++j);
-    while (cur.ntok > 0) {
+    // The units are walked in stretches: a stretch ends when the wave has no more units or its list
+    // of unpublished chunk states is full; the states are then published (the call sits outside
+    // the unit loop, so that it does not constrain the registers of the streaming code).
+    for (;;) {
+    while (cur.ntok > 0 && n_split < kSplitList) {
         Unit nxt = fetch(++j);
         if (nxt.ntok == 0 && j < n_rounds) nxt = fetch(++j);
 
@@ -791,13 +844,16 @@ __device__ __forceinline__ void rpartq_body(
                 } else {
                     const int64_t rec = (int64_t)cur.item * H + h;
 #pragma unroll
-                    for (int i = 0; i < EPL; ++i)
-                        __builtin_nontemporal_store(acc[i] + aux, &part_acc[rec * D + lane * EPL + i]);
+                    for (int i = 0; i < EPL; ++i) st_agent(&part_acc[rec * D + lane * EPL + i], acc[i] + aux);
                     if (lane == 0) {
-                        __builtin_nontemporal_store(m, &part_ml[rec * 2]);
-                        __builtin_nontemporal_store(l, &part_ml[rec * 2 + 1]);
+                        st_agent(&part_ml[rec * 2], m);
+                        st_agent(&part_ml[rec * 2 + 1], l);
                     }
                 }
+            }
+            if (cur.nch != 1) {
+                if (lane == 0) split_list[n_split] = make_int4(b, h, cur.nch, a.v.item0[b]);
+                ++n_split;
             }
         } else {
             float (&sm_acc)[kWaves][D] = sm_acc2[set];
@@ -812,32 +868,59 @@ __device__ __forceinline__ void rpartq_body(
             if (lane == 0) { sm_m[wave] = m; sm_l[wave] = l; sm_aux[wave] = aux; }
             __syncthreads();
 
-            if (tid < D) {
+            if (cur.nch == 1) {
+                if (tid < D) {
+                    float M = sm_m[0];
+#pragma unroll
+                    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
+                    float L = 0.f, X = 0.f, o = 0.f;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) {
+                        const float wa = fast_exp2(sm_m[w] - M);
+                        L += wa * sm_l[w];
+                        X += wa * sm_aux[w];
+                        o += wa * sm_acc[w][tid];
+                    }
+                    o += X;                                      // the weighted zero points
+                    __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
+                }
+            } else if (wave == 0) {
+                // one wave writes the whole chunk state, publishes it and counts the chunk
                 float M = sm_m[0];
 #pragma unroll
                 for (int w = 1; w < kWaves; ++w) M = fmaxf(M, sm_m[w]);
-                float L = 0.f, X = 0.f, o = 0.f;
+                float L = 0.f, X = 0.f, wgt[kWaves];
 #pragma unroll
                 for (int w = 0; w < kWaves; ++w) {
-                    const float a = fast_exp2(sm_m[w] - M);
-                    L += a * sm_l[w];
-                    X += a * sm_aux[w];
-                    o += a * sm_acc[w][tid];
+                    wgt[w] = fast_exp2(sm_m[w] - M);
+                    L += wgt[w] * sm_l[w];
+                    X += wgt[w] * sm_aux[w];
                 }
-                o += X;                                          // the weighted zero points
-                if (cur.nch == 1) {
-                    __builtin_nontemporal_store((_Float16)(o / L), &out[((int64_t)b * H + h) * D + tid]);
-                } else {
-                    const int64_t rec = (int64_t)cur.item * H + h;
-                    __builtin_nontemporal_store(o, &part_acc[rec * D + tid]);
-                    if (tid == 0) {
-                        __builtin_nontemporal_store(M, &part_ml[rec * 2]);
-                        __builtin_nontemporal_store(L, &part_ml[rec * 2 + 1]);
-                    }
+                const int64_t rec = (int64_t)cur.item * H + h;
+#pragma unroll
+                for (int e = lane; e < D; e += 64) {
+                    float o = X;
+#pragma unroll
+                    for (int w = 0; w < kWaves; ++w) o += wgt[w] * sm_acc[w][e];
+                    st_agent(&part_acc[rec * D + e], o);
                 }
+                if (lane == 0) {
+                    st_agent(&part_ml[rec * 2], M);
+                    st_agent(&part_ml[rec * 2 + 1], L);
+                }
+                if (lane == 0) split_list[n_split] = make_int4(b, h, cur.nch, a.v.item0[b]);
             }
+            // counted by every wave of the workgroup (they all leave the stretch together)
+            if (cur.nch != 1) ++n_split;
         }
         cur = nxt;                     // no second barrier: the next unit uses the other LDS set
+    }
+    // the chunk states written in this stretch are published, and merged where this wave is the
+    // last to publish a chunk of a (sequence, head)
+    if (WPU == 1 || wave == 0)
+        publish_split<D>(lane, split_list, n_split, H, a.v.cnt, part_acc, part_ml, out);
+    n_split = 0;
+    if (cur.ntok == 0) break;
     }
 }
 
@@ -847,25 +930,19 @@ __device__ __forceinline__ void rpartq_body(
 template <int BITS>
 __global__ __launch_bounds__(kThreads)
 __attribute__((amdgpu_waves_per_eu(q_wg_short<BITS>(), q_wg_short<BITS>())))
-void rpartq_partial_kernel(
-    const char *__restrict__ k_codes, const char *__restrict__ v_codes,
-    const float *__restrict__ k_meta, const float *__restrict__ v_meta,
-    const int64_t *__restrict__ seq_off, const int32_t *__restrict__ seq_cap,
-    const _Float16 *__restrict__ q, _Float16 *__restrict__ out, int H,
-    const int32_t *__restrict__ hdr, const int4 *__restrict__ items,
-    const int32_t *__restrict__ order, float *__restrict__ part_acc, float *__restrict__ part_ml,
-    float qscale, int B, int max_items, int32_t *__restrict__ status)
+void rpartq_partial_kernel(PartialQArgs a)
 {
-    if (!plan_matches(hdr, B, H, plan_kind(128, BITS), max_items, (int)gridDim.x, status)) return;
+    const int32_t *hdr = a.v.hdr;
+    if (!plan_matches(hdr, a.B, a.H, plan_kind(128, BITS), a.v.max_items, (int)gridDim.x, a.status)) return;
+    if ((int)blockIdx.x >= hdr[HDR_GRID]) return;
+    unit_prologue<128>(hdr, a.v.nchunk, a.v.newlen, a.v.newseen, a.seq_lens, a.seq_seen, a.out, a.B, a.H);
     if constexpr (q_wave_units<BITS>() != 0) {
         if (hdr[HDR_WAVE_UNITS]) {
-            rpartq_body<BITS, 1>(k_codes, v_codes, k_meta, v_meta, seq_off, seq_cap, q, out, H, hdr,
-                                 items, order, part_acc, part_ml, qscale);
+            rpartq_body<BITS, 1>(a);
             return;
         }
     }
-    rpartq_body<BITS, kWaves>(k_codes, v_codes, k_meta, v_meta, seq_off, seq_cap, q, out, H, hdr,
-                              items, order, part_acc, part_ml, qscale);
+    rpartq_body<BITS, kWaves>(a);
 }
 
 // ---------------------------------------------------------------------------
@@ -897,6 +974,106 @@ int check_qws(const fd_kvq_desc *d, const void *ws, size_t ws_bytes, WsLayout *w
     return FD_OK;
 }
 
+QSlabs q_slabs(const fd_kvq_desc *d)
+{
+    QSlabs c;
+    c.k_codes = (uint8_t *)d->k_codes;
+    c.v_codes = (uint8_t *)d->v_codes;
+    c.k_meta = d->k_scale;
+    c.v_meta = d->v_scale;
+    return c;
+}
+
+SeqState q_seq_state(const fd_kvq_desc *d)
+{
+    SeqState st;
+    st.seq_off = d->seq_off;
+    st.seq_cap = d->seq_cap;
+    st.seq_lens = d->seq_lens;
+    st.seq_seen = d->seq_seen;
+    st.status = d->status;
+    st.n_sink = d->n_sink;
+    return st;
+}
+
+PlanArgs q_plan_args(const fd_kvq_desc *d, void *workspace, const WsLayout &w, int grid, int after_append)
+{
+    const bool four = d->bits == 4;
+    PlanArgs a;
+    a.seq_lens = d->seq_lens;
+    a.seq_cap = d->seq_cap;
+    a.seq_seen = d->seq_seen;
+    a.status = d->status;
+    a.n_sink = d->n_sink;
+    a.after_append = after_append;
+    a.B = d->B;
+    a.H = d->H;
+    a.chunk_req = d->chunk_tokens;
+    a.granule = 64;
+    a.grid_long = (four ? q_wg_long<4>() : q_wg_long<8>()) * grid;
+    a.grid_short = (four ? q_wg_short<4>() : q_wg_short<8>()) * grid;
+    a.short_below = kShortSeq;
+    a.hashed = 1;
+    a.wave_units = four ? q_wave_units<4>() : q_wave_units<8>();
+    a.split = kQSplit;
+    a.kind = plan_kind(128, four ? 4 : 8);
+    a.v = plan_view(workspace, w);
+    return a;
+}
+
+int launch_qpartial(const fd_kvq_desc *desc, const void *q, void *out, void *workspace,
+                    const WsLayout &w, int grid, void *stream)
+{
+    PartialQArgs a;
+    a.k_codes = (const char *)desc->k_codes;
+    a.v_codes = (const char *)desc->v_codes;
+    a.k_meta = desc->k_scale;
+    a.v_meta = desc->v_scale;
+    a.seq_off = desc->seq_off;
+    a.seq_cap = desc->seq_cap;
+    a.seq_lens = desc->seq_lens;
+    a.seq_seen = desc->seq_seen;
+    a.status = desc->status;
+    a.q = (const _Float16 *)q;
+    a.out = (_Float16 *)out;
+    a.B = desc->B;
+    a.H = desc->H;
+    a.qscale = (float)(1.4426950408889634 / 11.313708498984761);
+    a.v = plan_view(workspace, w);
+    if (desc->bits == 4)
+        hipLaunchKernelGGL(rpartq_partial_kernel<4>, dim3(q_wg_short<4>() * grid), dim3(kThreads), 0,
+                           (hipStream_t)stream, a);
+    else
+        hipLaunchKernelGGL(rpartq_partial_kernel<8>, dim3(q_wg_short<8>() * grid), dim3(kThreads), 0,
+                           (hipStream_t)stream, a);
+    return launched();
+}
+
+int check_qdecode_args(const fd_kvq_desc *desc, const void *q, const void *out, const void *workspace,
+                       size_t workspace_bytes, WsLayout *w)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
+    return check_qws(desc, workspace, workspace_bytes, w);
+}
+
+int launch_qfront(const fd_kvq_desc *desc, const void *k_new, const void *v_new, void *workspace,
+                  const WsLayout &w, int grid, void *stream)
+{
+    const PlanArgs pa = q_plan_args(desc, workspace, w, grid, 1);
+    if (desc->bits == 4)
+        hipLaunchKernelGGL(kvq_append_plan_kernel<4>, dim3(desc->B + 1), dim3(kPlanThreads), 0,
+                           (hipStream_t)stream, q_slabs(desc), q_seq_state(desc),
+                           (const _Float16 *)k_new, (const _Float16 *)v_new, pa);
+    else
+        hipLaunchKernelGGL(kvq_append_plan_kernel<8>, dim3(desc->B + 1), dim3(kPlanThreads), 0,
+                           (hipStream_t)stream, q_slabs(desc), q_seq_state(desc),
+                           (const _Float16 *)k_new, (const _Float16 *)v_new, pa);
+    return launched();
+}
+
 } // namespace
 
 extern "C" {
@@ -909,17 +1086,28 @@ int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new,
     if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
     if (desc->bits == 4)
         hipLaunchKernelGGL(kvq_append_kernel<4>, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
-                           (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
-                           desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens,
-                           desc->status, (const _Float16 *)k_new, (const _Float16 *)v_new, desc->H,
-                           desc->seq_seen, desc->n_sink);
+                           q_slabs(desc), q_seq_state(desc), (const _Float16 *)k_new,
+                           (const _Float16 *)v_new, desc->H);
     else
         hipLaunchKernelGGL(kvq_append_kernel<8>, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
-                           (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
-                           desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens,
-                           desc->status, (const _Float16 *)k_new, (const _Float16 *)v_new, desc->H,
-                           desc->seq_seen, desc->n_sink);
+                           q_slabs(desc), q_seq_state(desc), (const _Float16 *)k_new,
+                           (const _Float16 *)v_new, desc->H);
     return launched();
+}
+
+int fd_kvq_append_plan(const fd_kvq_desc *desc, const void *k_new, const void *v_new,
+                       void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc = check_qdesc(desc);
+    if (rc != FD_OK) return rc;
+    if (desc->B == 0) return FD_OK;
+    if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
+    WsLayout w;
+    rc = check_qws(desc, workspace, workspace_bytes, &w);
+    if (rc != FD_OK) return rc;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    return launch_qfront(desc, k_new, v_new, workspace, w, grid, stream);
 }
 
 int fd_kvq_store_rows(const fd_kvq_desc *desc, int32_t b, int32_t t0, int32_t n, const void *k_rows,
@@ -982,50 +1170,20 @@ int fd_rpartq_plan(const fd_kvq_desc *desc, void *workspace, size_t workspace_by
     if (rc != FD_OK) return rc;
     const int grid = persistent_grid();
     if (grid <= 0) return FD_EHIP;
-    char *ws = (char *)workspace;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
-                       desc->seq_lens, desc->seq_cap, desc->status, desc->B, desc->H,
-                       desc->chunk_tokens, 64,
-                       (desc->bits == 4 ? q_wg_long<4>() : q_wg_long<8>()) * grid,
-                       (desc->bits == 4 ? q_wg_short<4>() : q_wg_short<8>()) * grid, kShortSeq, 1,
-                       desc->bits == 4 ? q_wave_units<4>() : q_wave_units<8>(), kQSplit,
-                       plan_kind(128, desc->bits == 4 ? 4 : 8), (int)w.max_items, (int32_t *)ws,
-                       (int32_t *)(ws + w.off_item0), (int32_t *)(ws + w.off_nchunk),
-                       (int4 *)(ws + w.off_items), (int32_t *)(ws + w.off_order));
+                       q_plan_args(desc, workspace, w, grid, 0));
     return launched();
 }
 
 int fd_rpartq_partial(const fd_kvq_desc *desc, const void *q, void *out,
                       void *workspace, size_t workspace_bytes, void *stream)
 {
-    int rc = check_qdesc(desc);
-    if (rc != FD_OK) return rc;
-    if (desc->B == 0) return FD_OK;
-    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
     WsLayout w;
-    rc = check_qws(desc, workspace, workspace_bytes, &w);
-    if (rc != FD_OK) return rc;
+    int rc = check_qdecode_args(desc, q, out, workspace, workspace_bytes, &w);
+    if (rc != FD_OK || desc->B == 0) return rc;
     const int grid = persistent_grid();
     if (grid <= 0) return FD_EHIP;
-    char *ws = (char *)workspace;
-    const float qscale = (float)(1.4426950408889634 / 11.313708498984761);
-    if (desc->bits == 4)
-        hipLaunchKernelGGL(rpartq_partial_kernel<4>, dim3(q_wg_short<4>() * grid), dim3(kThreads), 0,
-                           (hipStream_t)stream, (const char *)desc->k_codes,
-                           (const char *)desc->v_codes, desc->k_scale, desc->v_scale, desc->seq_off,
-                           desc->seq_cap, (const _Float16 *)q, (_Float16 *)out, desc->H,
-                           (const int32_t *)ws, (const int4 *)(ws + w.off_items),
-                           (const int32_t *)(ws + w.off_order), (float *)(ws + w.off_acc),
-                           (float *)(ws + w.off_ml), qscale, desc->B, (int)w.max_items, desc->status);
-    else
-        hipLaunchKernelGGL(rpartq_partial_kernel<8>, dim3(q_wg_short<8>() * grid), dim3(kThreads), 0,
-                           (hipStream_t)stream, (const char *)desc->k_codes,
-                           (const char *)desc->v_codes, desc->k_scale, desc->v_scale, desc->seq_off,
-                           desc->seq_cap, (const _Float16 *)q, (_Float16 *)out, desc->H,
-                           (const int32_t *)ws, (const int4 *)(ws + w.off_items),
-                           (const int32_t *)(ws + w.off_order), (float *)(ws + w.off_acc),
-                           (float *)(ws + w.off_ml), qscale, desc->B, (int)w.max_items, desc->status);
-    return launched();
+    return launch_qpartial(desc, q, out, workspace, w, grid, stream);
 }
 
 int fd_rpartq_merge(const fd_kvq_desc *desc, void *out,
@@ -1038,73 +1196,62 @@ int fd_rpartq_merge(const fd_kvq_desc *desc, void *out,
     WsLayout w;
     rc = check_qws(desc, workspace, workspace_bytes, &w);
     if (rc != FD_OK) return rc;
-    char *ws = (char *)workspace;
     const int64_t bh = (int64_t)desc->B * desc->H;
     hipLaunchKernelGGL(rpart_merge_kernel<128>, dim3((unsigned)((bh + 3) / 4)), dim3(256), 0,
-                       (hipStream_t)stream, (const int32_t *)(ws + w.off_item0),
-                       (const int32_t *)(ws + w.off_nchunk), (const float *)(ws + w.off_acc),
-                       (const float *)(ws + w.off_ml), (_Float16 *)out, desc->B, desc->H,
-                       (const int32_t *)ws, plan_kind(128, desc->bits == 4 ? 4 : 8),
-                       (int)w.max_items, desc->status);
+                       (hipStream_t)stream, plan_view(workspace, w), (_Float16 *)out, desc->B, desc->H,
+                       plan_kind(128, desc->bits == 4 ? 4 : 8), desc->status);
     return launched();
 }
 
 int fd_rpartq_decode(const fd_kvq_desc *desc, const void *q, void *out,
                      void *workspace, size_t workspace_bytes, void *stream)
 {
-    int rc = check_qdesc(desc);
-    if (rc != FD_OK) return rc;
-    if (desc->B == 0) return FD_OK;
-    if (!q || !out || !aligned(q, 16) || !aligned(out, 16)) return FD_EINVAL;
     WsLayout w;
-    rc = check_qws(desc, workspace, workspace_bytes, &w);
+    int rc = check_qdecode_args(desc, q, out, workspace, workspace_bytes, &w);
+    if (rc != FD_OK || desc->B == 0) return rc;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanThreads), 0, (hipStream_t)stream,
+                       q_plan_args(desc, workspace, w, grid, 0));
+    rc = launched();
     if (rc != FD_OK) return rc;
-    rc = fd_rpartq_plan(desc, workspace, workspace_bytes, stream);
+    return launch_qpartial(desc, q, out, workspace, w, grid, stream);
+}
+
+static int qstep_fused(const fd_kvq_desc *desc, const void *q, const void *k_new, const void *v_new,
+                       void *out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    WsLayout w;
+    int rc = check_qdecode_args(desc, q, out, workspace, workspace_bytes, &w);
+    if (rc != FD_OK || desc->B == 0) return rc;
+    if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
+    rc = launch_qfront(desc, k_new, v_new, workspace, w, grid, stream);
     if (rc != FD_OK) return rc;
-    rc = fd_rpartq_partial(desc, q, out, workspace, workspace_bytes, stream);
-    if (rc != FD_OK) return rc;
-    return fd_rpartq_merge(desc, out, workspace, workspace_bytes, stream);
+    return launch_qpartial(desc, q, out, workspace, w, grid, stream);
 }
 
 int fd_rpartq_step(const fd_kvq_desc *desc, const void *q, const void *k_new, const void *v_new,
                    void *out, void *workspace, size_t workspace_bytes, void *stream)
 {
-    int rc = check_qdesc(desc);
-    if (rc != FD_OK) return rc;
-    if (desc->B == 0) return FD_OK;
-    if (!q || !out || !k_new || !v_new || !aligned(q, 16) || !aligned(out, 16) ||
-        !aligned(k_new, 16) || !aligned(v_new, 16))
-        return FD_EINVAL;
-    WsLayout w;
-    rc = check_qws(desc, workspace, workspace_bytes, &w);
-    if (rc != FD_OK) return rc;
-    rc = fd_kvq_append(desc, k_new, v_new, stream);
-    if (rc != FD_OK) return rc;
-    return fd_rpartq_decode(desc, q, out, workspace, workspace_bytes, stream);
+    return qstep_fused(desc, q, k_new, v_new, out, workspace, workspace_bytes, stream);
 }
 
 int fd_rpartq_layer_step(const fd_kvq_desc *layer, const void *q, const void *k_new,
                          const void *v_new, void *out, void *workspace, size_t workspace_bytes,
                          int replan, void *stream)
 {
-    int rc = check_qdesc(layer);
-    if (rc != FD_OK) return rc;
-    if (layer->B == 0) return FD_OK;
-    if (!q || !out || !k_new || !v_new || !aligned(q, 16) || !aligned(out, 16) ||
-        !aligned(k_new, 16) || !aligned(v_new, 16))
-        return FD_EINVAL;
+    if (replan) return qstep_fused(layer, q, k_new, v_new, out, workspace, workspace_bytes, stream);
     WsLayout w;
-    rc = check_qws(layer, workspace, workspace_bytes, &w);
-    if (rc != FD_OK) return rc;
+    int rc = check_qdecode_args(layer, q, out, workspace, workspace_bytes, &w);
+    if (rc != FD_OK || layer->B == 0) return rc;
+    if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
+    const int grid = persistent_grid();
+    if (grid <= 0) return FD_EHIP;
     rc = fd_kvq_append(layer, k_new, v_new, stream);
     if (rc != FD_OK) return rc;
-    if (replan) {
-        rc = fd_rpartq_plan(layer, workspace, workspace_bytes, stream);
-        if (rc != FD_OK) return rc;
-    }
-    rc = fd_rpartq_partial(layer, q, out, workspace, workspace_bytes, stream);
-    if (rc != FD_OK) return rc;
-    return fd_rpartq_merge(layer, out, workspace, workspace_bytes, stream);
+    return launch_qpartial(layer, q, out, workspace, w, grid, stream);
 }
 
 } // extern "C"

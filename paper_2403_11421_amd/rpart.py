@@ -84,6 +84,8 @@ def load() -> ctypes.CDLL:
     lib.fd_kv_append.argtypes = [P, _vp, _vp, _vp]
     lib.fd_rpart_decode.restype = ctypes.c_int
     lib.fd_rpart_decode.argtypes = [P, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+    lib.fd_kv_append_plan.restype = ctypes.c_int
+    lib.fd_kv_append_plan.argtypes = [P, _vp, _vp, _vp, ctypes.c_size_t, _vp]
     lib.fd_rpart_decode_noalloc.restype = ctypes.c_int
     lib.fd_rpart_decode_noalloc.argtypes = [P, _vp, _vp, _vp]
     lib.fd_rpart_plan.restype = ctypes.c_int
@@ -112,6 +114,7 @@ def load() -> ctypes.CDLL:
     for name, args in (("fd_kvq_append", [Q, _vp, _vp, _vp]),
                        ("fd_kvq_store_rows", [Q, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, _vp, _vp,
                                               ctypes.c_int, _vp]),
+                       ("fd_kvq_append_plan", [Q, _vp, _vp, _vp, ctypes.c_size_t, _vp]),
                        ("fd_kvq_reset", [Q, _vp, ctypes.c_int32, _vp]),
                        ("fd_kvq_release", [Q, _vp, ctypes.c_int32, _vp]),
                        ("fd_rpartq_plan", [Q, _vp, ctypes.c_size_t, _vp]),
@@ -135,7 +138,7 @@ EXPORTS = ("fd_version", "fd_desc_size", "fd_strerror", "fd_workspace_bytes", "f
            "fd_kvq_append", "fd_kvq_reset", "fd_rpartq_plan", "fd_rpartq_partial", "fd_rpartq_merge",
            "fd_rpartq_decode", "fd_rpartq_step", "fd_rpart_layer_step", "fd_rpartq_layer_step",
            "fd_kv_release", "fd_kvq_release", "fd_rpart_decode_noalloc", "fd_last_device_status",
-           "fd_kv_store_rows", "fd_kvq_store_rows")
+           "fd_kv_store_rows", "fd_kvq_store_rows", "fd_kv_append_plan", "fd_kvq_append_plan")
 
 
 def version() -> int:
@@ -170,6 +173,16 @@ def _ws(ws: torch.Tensor):
 def fd_kv_append(desc: fd_kv_desc, k_new: torch.Tensor, v_new: torch.Tensor) -> None:
     _check(load().fd_kv_append(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), _stream()),
            "fd_kv_append")
+
+
+def fd_kv_append_plan(desc, k_new: torch.Tensor, v_new: torch.Tensor, workspace: torch.Tensor) -> None:
+    """Append and plan in one launch (front half of a step); `desc` is an fd_kv_desc or an
+    fd_kvq_desc.  The streaming call on the same workspace must follow."""
+    p, n = _ws(workspace)
+    quant = isinstance(desc, fd_kvq_desc)
+    f = load().fd_kvq_append_plan if quant else load().fd_kv_append_plan
+    _check(f(ctypes.byref(desc), _ptr(k_new), _ptr(v_new), p, n, _stream()),
+           "fd_kvq_append_plan" if quant else "fd_kv_append_plan")
 
 
 def fd_rpart_decode(desc: fd_kv_desc, q: torch.Tensor, out: torch.Tensor,

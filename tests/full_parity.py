@@ -1,5 +1,6 @@
 """Whole-batch parity of a full-size config against the oracle, in the launch configuration
-bench.py times (staged calls, library-chosen chunking, workspace sized for the step's tokens).
+bench.py times (append + plan launch, streaming launch, library-chosen chunking, workspace
+sized for the step's tokens).
 
 Every oracle input comes from the seeded generator, never from the device cache: for each
 sequence the cached rows are regenerated, copied to the host, (for a quantised cache) quantised
@@ -68,18 +69,13 @@ class FullCase:
         self.ws = self.cache.workspace(self.n_tok)              # as bench.py sizes it
 
     def step(self):
-        """The calls bench.py times, in its order."""
+        """The calls bench.py times, in its order: the two launches of a step."""
         d = self.cache.desc
+        rpart.fd_kv_append_plan(d, self.k_new, self.v_new, self.ws)
         if self.kv == "fp16":
-            rpart.fd_kv_append(d, self.k_new, self.v_new)
-            rpart.fd_rpart_plan(d, self.ws)
             rpart.fd_rpart_partial(d, self.q, self.out, self.ws)
-            rpart.fd_rpart_merge(d, self.out, self.ws)
         else:
-            rpart.fd_kvq_append(d, self.k_new, self.v_new)
-            rpart.fd_rpartq_plan(d, self.ws)
             rpart.fd_rpartq_partial(d, self.q, self.out, self.ws)
-            rpart.fd_rpartq_merge(d, self.out, self.ws)
         torch.cuda.synchronize()
         assert rpart.fd_read_status(d) == 0
         self.plan = rpart.fd_plan_info(self.ws)

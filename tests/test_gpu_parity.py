@@ -319,3 +319,67 @@ def test_random_length_mixes(seed):
     chunk = int(rng.choice([0, 64, 96, 160, 512, 1000]))
     case = DeviceCase(_cfg("rand%d" % seed, len(lens), 2, 128), lens, seed=50 + seed, chunk_tokens=chunk)
     check_step(case)
+
+
+def test_folded_merge_standalone_merge_and_repeated_streaming_on_one_plan():
+    """The streaming kernel merges a split sequence itself (the wave that finishes the last chunk
+    of a head does it).  The stand-alone merge recomputes the same outputs from the chunk states,
+    bit for bit; running the streaming kernel again on the same plan gives the same bits again
+    (the per-head chunk counters are back at zero after every launch)."""
+    cfg = _cfg("fold", 6, 5, 128)
+    lens = [0, 700, 33, 3001, 64, 1500]
+    case = DeviceCase(cfg, lens, seed=61, chunk_tokens=128)
+    case.cache.seq_lens[0] = rpart.FD_SLOT_FREE               # stays empty through the append
+    rpart.fd_kv_append(case.cache.desc, case.k_new, case.v_new)
+    rpart.fd_rpart_plan(case.cache.desc, case.ws)
+    rpart.fd_rpart_partial(case.cache.desc, case.q, case.out, case.ws)
+    torch.cuda.synchronize()
+    first = case.out.clone()
+    finite, zero0 = bool(torch.isfinite(first.float()).all()), bool((first[0] == 0).all())
+    assert finite and zero0
+    again = torch.full_like(first, float("nan"))
+    for _ in range(3):
+        rpart.fd_rpart_partial(case.cache.desc, case.q, again, case.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16), first.view(torch.int16))
+    alone = torch.full_like(first, float("nan"))
+    rpart.fd_rpart_merge(case.cache.desc, alone, case.ws)
+    torch.cuda.synchronize()
+    split, single = [1, 3, 5], [2, 4]                          # 701, 3002, 1501 tokens; 34 and 65
+    for b in split + [0]:                                      # split sequences and the empty one
+        assert torch.equal(alone[b].view(torch.int16), first[b].view(torch.int16))
+    for b in single:                                           # not the stand-alone merge's business
+        untouched = bool(torch.isnan(alone[b].float()).all())
+        assert untouched
+    assert rpart.fd_read_status(case.cache.desc) == 0
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_two_launch_step_equals_append_then_decode(d):
+    """fd_rpart_step (append + plan in one launch, lengths stored by the streaming kernel) against
+    fd_kv_append followed by fd_rpart_decode: same cache bits, same lengths, same output bits,
+    also with a full cache (append refused), a free slot and an empty sequence in the batch."""
+    cfg = _cfg("fused", 7, 3, d)
+    lens = [5, 0, 300, 129, 2000, 64, 17]
+    a = DeviceCase(cfg, lens, seed=71, extra_cap=1)
+    b = DeviceCase(cfg, lens, seed=71, extra_cap=1)
+    for case in (a, b):
+        case.cache.seq_lens[3] = rpart.FD_SLOT_FREE                       # a free slot
+    rpart.fd_rpart_step(a.cache.desc, a.q, a.k_new, a.v_new, a.out, a.ws)
+    rpart.fd_kv_append(b.cache.desc, b.k_new, b.v_new)
+    rpart.fd_rpart_decode(b.cache.desc, b.q, b.out, b.ws)
+    torch.cuda.synchronize()
+    want_lens = [6, 1, 301, rpart.FD_SLOT_FREE, 2001, 65, 18]
+    assert a.cache.seq_lens.cpu().tolist() == want_lens == b.cache.seq_lens.cpu().tolist()
+    assert torch.equal(a.cache.k.view(torch.int16), b.cache.k.view(torch.int16))
+    assert torch.equal(a.cache.v.view(torch.int16), b.cache.v.view(torch.int16))
+    assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
+    assert bool((a.out[3] == 0).all())
+    # a second step: every cache is full now (capacity L + 1), nothing may change but the output
+    k_before = a.cache.k.clone()
+    rpart.fd_rpart_step(a.cache.desc, a.q, a.k_new, a.v_new, a.out, a.ws)
+    torch.cuda.synchronize()
+    assert rpart.fd_last_device_status(a.cache.desc, a.ws) == rpart.FD_ST_CAPACITY
+    assert a.cache.seq_lens.cpu().tolist() == want_lens
+    assert torch.equal(a.cache.k, k_before)
+    assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
