@@ -349,6 +349,16 @@ int fd_rpartq_layer_step(const fd_kvq_desc *layer, const void *q, const void *k_
  */
 int fd_hbm_read_probe(const void *buf, size_t bytes, int32_t *sink, size_t *bytes_read, void *stream);
 
+/*
+ * Measurement aid, not part of the R-Part: fill `buf` (device, 4-byte aligned, `bytes` a
+ * multiple of 4) with a seeded bit pattern whose 16-bit halves are finite fp16 values of
+ * magnitude 0.25 .. 1 (and whose 32-bit words are finite floats), so that a harness can give a
+ * cache contents without running any kernel of its own: counter-collection runs of the
+ * profiler have crashed inside the tensor framework's kernel dispatches, and HBM traffic does
+ * not depend on the values.
+ */
+int fd_fill_pattern(void *buf, size_t bytes, uint32_t seed, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

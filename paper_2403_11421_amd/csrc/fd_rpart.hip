@@ -1318,6 +1318,25 @@ __global__ __launch_bounds__(256) void hbm_read_probe_kernel(const uint4v *__res
     if (acc == 0x9E3779B9u) sink[0] = (int32_t)acc;     // keeps the loads alive
 }
 
+// Measurement aid: fill a buffer with a seeded bit pattern whose 16-bit halves are finite fp16
+// values of magnitude 0.25 .. 1 (read as float32 the words are finite too), without any help
+// from the framework that owns the memory.
+__global__ __launch_bounds__(256) void fill_pattern_kernel(uint32_t *__restrict__ p, size_t n_words,
+                                                           uint32_t seed)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_words; i += stride) {
+        uint32_t x = (uint32_t)i * 0x9E3779B1u + (uint32_t)(i >> 32) + seed;
+        x ^= x >> 15;
+        x *= 0x85EBCA6Bu;
+        x ^= x >> 13;
+        // per half: sign, exponent field 13 or 14, ten mantissa bits
+        const uint32_t lo = (x & 0x83FFu) | ((13u + ((x >> 10) & 1u)) << 10);
+        const uint32_t hi = ((x >> 16) & 0x83FFu) | ((13u + ((x >> 26) & 1u)) << 10);
+        p[i] = lo | (hi << 16);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
@@ -1682,6 +1701,17 @@ int fd_hbm_read_probe(const void *buf, size_t bytes, int32_t *sink, size_t *byte
     if (iters == 0) return FD_EINVAL;
     hipLaunchKernelGGL(hbm_read_probe_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream,
                        (const uint4v *)buf, iters, sink);
+    return launched();
+}
+
+int fd_fill_pattern(void *buf, size_t bytes, uint32_t seed, void *stream)
+{
+    if (!buf || !aligned(buf, 4) || bytes % 4 != 0) return FD_EINVAL;
+    if (bytes == 0) return FD_OK;
+    const int cus = persistent_grid();
+    if (cus <= 0) return FD_EHIP;
+    hipLaunchKernelGGL(fill_pattern_kernel, dim3(cus * 8), dim3(256), 0, (hipStream_t)stream,
+                       (uint32_t *)buf, bytes / 4, seed);
     return launched();
 }
 

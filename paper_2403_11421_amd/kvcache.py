@@ -16,9 +16,11 @@ from . import rpart
 
 class KVCache:
     def __init__(self, B: int, H: int, d: int, capacities: Sequence[int], device="cuda",
-                 chunk_tokens: int = 0, n_sink: Optional[int] = None):
+                 chunk_tokens: int = 0, n_sink: Optional[int] = None, zero_fill: bool = True):
         """n_sink = None: plain cache.  n_sink >= 0: windowed cache, sequence b keeps its first
-        n_sink tokens and its last capacities[b] - n_sink tokens."""
+        n_sink tokens and its last capacities[b] - n_sink tokens.  zero_fill = False leaves the
+        slabs as allocated (the caller fills them); the small arrays are then set up by copies
+        from the host, so that constructing the cache dispatches no kernel."""
         assert len(capacities) == B and d in (64, 128)
         self.B, self.H, self.d = B, H, d
         self.device = torch.device(device)
@@ -30,13 +32,14 @@ class KVCache:
             o = (o + 127) // 128 * 128               # 256-byte aligned blocks
         self.total_elems = max(o, 128)
         self.offs = offs
-        self.k = torch.zeros(self.total_elems, dtype=torch.float16, device=self.device)
-        self.v = torch.zeros(self.total_elems, dtype=torch.float16, device=self.device)
-        self.seq_off = torch.tensor(offs, dtype=torch.int64, device=self.device)
-        self.seq_cap = torch.tensor(self.caps, dtype=torch.int32, device=self.device)
-        self.seq_lens = torch.zeros(B, dtype=torch.int32, device=self.device)
-        self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
-        self.seq_seen = None if n_sink is None else torch.zeros(B, dtype=torch.int32, device=self.device)
+        alloc = torch.zeros if zero_fill else torch.empty
+        self.k = alloc(self.total_elems, dtype=torch.float16, device=self.device)
+        self.v = alloc(self.total_elems, dtype=torch.float16, device=self.device)
+        self.seq_off = torch.tensor(offs, dtype=torch.int64).to(self.device)
+        self.seq_cap = torch.tensor(self.caps, dtype=torch.int32).to(self.device)
+        self.seq_lens = torch.zeros(B, dtype=torch.int32).to(self.device)
+        self.status = torch.zeros(1, dtype=torch.int32).to(self.device)
+        self.seq_seen = None if n_sink is None else torch.zeros(B, dtype=torch.int32).to(self.device)
         self.desc = rpart.fd_kv_desc(
             self.k.data_ptr(), self.v.data_ptr(), self.seq_off.data_ptr(), self.seq_cap.data_ptr(),
             self.seq_lens.data_ptr(), self.status.data_ptr(), B, H, d, chunk_tokens,
@@ -44,6 +47,10 @@ class KVCache:
 
     def set_chunk_tokens(self, t: int) -> None:
         self.desc.chunk_tokens = int(t)
+
+    def slabs(self):
+        """The large allocations (for bulk copies or fills)."""
+        return [self.k, self.v]
 
     def block(self, which: str, b: int) -> torch.Tensor:
         """View ``[H, cap_b, d]`` of sequence b's K or V block."""
@@ -76,7 +83,8 @@ class KVCacheQ:
     """Quantised KV-cache of one layer in the layout of ``fd_kvq_desc`` (d = 128, 8 or 4 bits)."""
 
     def __init__(self, B: int, H: int, d: int, capacities: Sequence[int], device="cuda",
-                 chunk_tokens: int = 0, n_sink: Optional[int] = None, bits: int = 8):
+                 chunk_tokens: int = 0, n_sink: Optional[int] = None, bits: int = 8,
+                 zero_fill: bool = True):
         assert len(capacities) == B and d == 128 and bits in (8, 4)
         self.B, self.H, self.d, self.bits = B, H, d, bits
         self.rb = d * bits // 8                         # bytes of codes per row
@@ -91,22 +99,32 @@ class KVCacheQ:
         self.offs = offs
         self.total_bytes = max(o, 256)
         fill = 128 if bits == 8 else 0
-        self.k_codes = torch.full((self.total_bytes,), fill, dtype=torch.uint8, device=self.device)
-        self.v_codes = torch.full((self.total_bytes,), fill, dtype=torch.uint8, device=self.device)
         n_meta = self.total_bytes // self.rb * self.mw
-        self.k_scale = torch.zeros(n_meta, dtype=torch.float32, device=self.device)
-        self.v_scale = torch.zeros(n_meta, dtype=torch.float32, device=self.device)
-        self.seq_off = torch.tensor(offs, dtype=torch.int64, device=self.device)
-        self.seq_cap = torch.tensor(self.caps, dtype=torch.int32, device=self.device)
-        self.seq_lens = torch.zeros(B, dtype=torch.int32, device=self.device)
-        self.status = torch.zeros(1, dtype=torch.int32, device=self.device)
-        self.seq_seen = None if n_sink is None else torch.zeros(B, dtype=torch.int32, device=self.device)
+        if zero_fill:
+            self.k_codes = torch.full((self.total_bytes,), fill, dtype=torch.uint8, device=self.device)
+            self.v_codes = torch.full((self.total_bytes,), fill, dtype=torch.uint8, device=self.device)
+            self.k_scale = torch.zeros(n_meta, dtype=torch.float32, device=self.device)
+            self.v_scale = torch.zeros(n_meta, dtype=torch.float32, device=self.device)
+        else:
+            self.k_codes = torch.empty(self.total_bytes, dtype=torch.uint8, device=self.device)
+            self.v_codes = torch.empty(self.total_bytes, dtype=torch.uint8, device=self.device)
+            self.k_scale = torch.empty(n_meta, dtype=torch.float32, device=self.device)
+            self.v_scale = torch.empty(n_meta, dtype=torch.float32, device=self.device)
+        self.seq_off = torch.tensor(offs, dtype=torch.int64).to(self.device)
+        self.seq_cap = torch.tensor(self.caps, dtype=torch.int32).to(self.device)
+        self.seq_lens = torch.zeros(B, dtype=torch.int32).to(self.device)
+        self.status = torch.zeros(1, dtype=torch.int32).to(self.device)
+        self.seq_seen = None if n_sink is None else torch.zeros(B, dtype=torch.int32).to(self.device)
         self.desc = rpart.fd_kvq_desc(
             self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_scale.data_ptr(),
             self.v_scale.data_ptr(), self.seq_off.data_ptr(), self.seq_cap.data_ptr(),
             self.seq_lens.data_ptr(), self.status.data_ptr(), B, H, d, chunk_tokens,
             None if n_sink is None else self.seq_seen.data_ptr(), 0 if n_sink is None else n_sink,
             bits)
+
+    def slabs(self):
+        """The large allocations (for bulk copies or fills)."""
+        return [self.k_codes, self.v_codes, self.k_scale, self.v_scale]
 
     def codes(self, which: str, b: int) -> torch.Tensor:
         """View ``[H, cap_b, rb]`` (uint8) of sequence b's K or V code bytes."""

@@ -126,6 +126,8 @@ def load() -> ctypes.CDLL:
                                                  ctypes.c_int, _vp])):
         getattr(lib, name).restype = ctypes.c_int
         getattr(lib, name).argtypes = args
+    lib.fd_fill_pattern.restype = ctypes.c_int
+    lib.fd_fill_pattern.argtypes = [_vp, ctypes.c_size_t, ctypes.c_uint32, _vp]
     lib.fd_hbm_read_probe.restype = ctypes.c_int
     lib.fd_hbm_read_probe.argtypes = [_vp, ctypes.c_size_t, _vp, ctypes.POINTER(ctypes.c_size_t), _vp]
     _lib = lib
@@ -138,7 +140,7 @@ EXPORTS = ("fd_version", "fd_desc_size", "fd_strerror", "fd_workspace_bytes", "f
            "fd_kvq_append", "fd_kvq_reset", "fd_rpartq_plan", "fd_rpartq_partial", "fd_rpartq_merge",
            "fd_rpartq_decode", "fd_rpartq_step", "fd_rpart_layer_step", "fd_rpartq_layer_step",
            "fd_kv_release", "fd_kvq_release", "fd_rpart_decode_noalloc", "fd_last_device_status",
-           "fd_kv_store_rows", "fd_kvq_store_rows", "fd_kv_append_plan", "fd_kvq_append_plan")
+           "fd_kv_store_rows", "fd_kvq_store_rows", "fd_kv_append_plan", "fd_kvq_append_plan", "fd_fill_pattern")
 
 
 def version() -> int:
@@ -281,6 +283,12 @@ def fd_hbm_read_probe(buf: torch.Tensor, sink: torch.Tensor) -> int:
                                     sink.data_ptr(), ctypes.byref(n), _stream()),
            "fd_hbm_read_probe")
     return int(n.value)
+
+
+def fd_fill_pattern(buf: torch.Tensor, seed: int) -> None:
+    """Fill a device tensor with the library's seeded bit pattern (no torch kernel involved)."""
+    _check(load().fd_fill_pattern(buf.data_ptr(), buf.numel() * buf.element_size(), seed & 0xFFFFFFFF,
+                                  _stream()), "fd_fill_pattern")
 
 
 # ---------------------------------------------------------------------------
