@@ -269,14 +269,14 @@ int fd_plan_info(const void *workspace, int32_t info[4], void *stream);
  *       code_i = rint((x_i - zero) / scale) in 0..15, element 2j in the low nibble of
  *       byte j, element 2j+1 in the high one; value = code * scale + zero; a constant
  *       row gets scale 0 and codes 0.  Two floats (scale, zero) per row in k_scale.
- * The query needs no transformation for these schemes.  d must be 128.
+ * The query needs no transformation for these schemes.  d is 128 or 64.
  *
  * With rb = d * bits / 8 bytes of codes per row, byte i of the K row of sequence b,
  * head h, token t is
  *     k_codes[ seq_off[b] + ((int64)h * seq_cap[b] + t) * rb + i ]
  * and its parameters start at float index
  *     (seq_off[b] / rb + (int64)h * seq_cap[b] + t) * (bits == 4 ? 2 : 1)   of k_scale;
- * likewise for V.  seq_off[b] must be a multiple of 128; blocks must not overlap.
+ * likewise for V.  seq_off[b] must be a multiple of 128 bytes; blocks must not overlap.
  * k_scale and v_scale must be 8-byte aligned.
  */
 typedef struct fd_kvq_desc {
@@ -288,7 +288,7 @@ typedef struct fd_kvq_desc {
     const int32_t *seq_cap;       /* device int32[B]: capacity of sequence b in tokens          */
     int32_t       *seq_lens;      /* device int32[B]: cached tokens; written by append / reset  */
     int32_t       *status;        /* device int32[1]: sticky FD_ST_* bits; caller zeroes it     */
-    int32_t        B, H, d;       /* sequences, heads, head dimension (128)                      */
+    int32_t        B, H, d;       /* sequences, heads, head dimension (128 or 64)               */
     int32_t        chunk_tokens;  /* split-K chunk length in tokens; 0 = chosen on the device   */
     int32_t       *seq_seen;      /* device int32[B] or NULL: windowed cache, as in fd_kv_desc  */
     int32_t        n_sink;        /* windowed cache: leading tokens that are never replaced     */
@@ -299,7 +299,8 @@ typedef struct fd_kvq_desc {
  * Same contracts as the fp16 entry points of the same names without the "q":
  * fd_kvq_append quantises k_new[b], v_new[b] (device fp16 [B][H][d]) into row
  * seq_lens[b] and bumps the length (FD_ST_CAPACITY when full); fd_rpartq_decode is
- * Eq. 2 + Eq. 3 over the dequantised rows with fp32 arithmetic and an fp16 result; workspace size comes from fd_workspace_bytes(B, H, 128, n).
+ * Eq. 2 + Eq. 3 over the dequantised rows with fp32 arithmetic and an fp16 result; workspace
+ * size comes from fd_workspace_bytes(B, H, d, n).
  */
 int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new, void *stream);
 int fd_kvq_append_plan(const fd_kvq_desc *desc, const void *k_new, const void *v_new,

@@ -188,8 +188,13 @@ __device__ inline void kv_append_body(uint4 *__restrict__ k_base, uint4 *__restr
         const int y = which ? x - n : x;
         const int h = y / vpr, c = y - h * vpr;
         const int64_t dst = blk + ((int64_t)h * cap + L) * vpr + c;
-        if (which) v_base[dst] = v_new[src0 + y];
-        else       k_base[dst] = k_new[src0 + y];
+        // written through, not left dirty in this XCD's L2: the streaming kernel that follows
+        // reads the row from another XCD as a rule, and fetching a line out of a remote L2 was
+        // measured at about half a microsecond per unit, exposed at the end of the unit
+        typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
+        const uint4 val = which ? v_new[src0 + y] : k_new[src0 + y];
+        u32x4v *out4 = reinterpret_cast<u32x4v *>((which ? v_base : k_base) + dst);
+        __builtin_nontemporal_store(u32x4v{val.x, val.y, val.z, val.w}, out4);
     }
     if (bump) {
         __syncthreads();

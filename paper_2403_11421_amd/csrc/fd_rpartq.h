@@ -7,7 +7,7 @@
 // Formats (the paper leaves the quantiser to the user), one set of parameters per token and
 // head, everything evaluated in IEEE binary32 so that the stored bytes are reproducible:
 //   8 bit: symmetric.  scale = max|x| / 127, code = rint(x / scale), byte = code + 128;
-//          value = (byte - 128) * scale.  A row of d = 128 values: 128 B + a 4 B scale.
+//          value = (byte - 128) * scale.  A row of d values: d bytes + a 4 B scale.
 //   4 bit: asymmetric. zero = min x, scale = (max x - min x) / 15,
 //          code = rint((x - zero) / scale) in 0..15, element 2j in the low nibble of byte j;
 //          value = code * scale + zero.  A row: 64 B + an 8 B (scale, zero) pair.
@@ -34,39 +34,42 @@ __device__ inline float dpp_xmin(float x)
     return fminf(x, __int_as_float(y));
 }
 
-// geometry of a quantised row of 128 elements
-template <int BITS>
+// geometry of a quantised row of D elements (D = 128 or 64)
+template <int BITS, int D_>
 struct QFmt {
     static_assert(BITS == 8 || BITS == 4, "8- or 4-bit codes");
-    static constexpr int D = 128;
+    static_assert(D_ == 128 || D_ == 64, "head dimension 128 or 64");
+    static constexpr int D = D_;
     static constexpr int RB = D * BITS / 8;              // bytes of codes per row
     static constexpr int MW = BITS == 8 ? 1 : 2;         // floats of parameters per row
-    static constexpr int LB = RB / 8;                    // bytes of a row one lane loads (8 lanes per row)
+    static constexpr int LPR = D / 16;                   // lanes per row when streaming: 16 elements per lane
+    static constexpr int LB = RB / LPR;                  // bytes of a row one lane loads: 16 (8 bit) or 8 (4 bit)
     static constexpr int NW = LB / 4;                    // 32-bit words per lane load
+    static constexpr int QL = D / 8;                     // lanes per row when quantising: 8 values per lane
 };
 template <int BITS> struct CodeVec;
 template <> struct CodeVec<8> { typedef u32x4 type; };
 template <> struct CodeVec<4> { typedef u32x2 type; };
 
 // ---------------------------------------------------------------------------
-// Row quantiser.  A row (128 fp16) is handled by 16 consecutive lanes with 8 values each:
+// Row quantiser.  A row (D fp16) is handled by D / 8 consecutive lanes with 8 values each:
 // `sub` is the lane's position among them, f its values, dst the row's first code byte,
 // meta the row's parameters.  Every step is a correctly rounded binary32 operation, so the
 // stored bytes are those of the definition evaluated in IEEE binary32.
 // ---------------------------------------------------------------------------
-template <int BITS>
+template <int BITS, int D>
 __device__ inline void quantize_row_store(const float (&f)[8], int sub, uint8_t *dst, float *meta)
 {
-    using F = QFmt<BITS>;
-    dst += sub * (F::RB / 16);                                // this lane's 8 codes
+    using F = QFmt<BITS, D>;
+    dst += sub * (F::RB / F::QL);                             // this lane's 8 codes
     if (BITS == 8) {
         float amax = 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(f[i]));
-        amax = dpp_xmax<0xB1>(amax);           // max over the 16 lanes of the row
+        amax = dpp_xmax<0xB1>(amax);           // max over the 16 (or 8) lanes of the row
         amax = dpp_xmax<0x4E>(amax);
         amax = dpp_xmax<0x141>(amax);
-        amax = dpp_xmax<0x140>(amax);
+        if (F::QL == 16) amax = dpp_xmax<0x140>(amax);
         const float scale = __fdiv_rn(amax, 127.0f);
         unsigned lo = 0, hi = 0;
 #pragma unroll
@@ -76,8 +79,10 @@ __device__ inline void quantize_row_store(const float (&f)[8], int sub, uint8_t 
             if (i < 4) lo |= u << (8 * i);
             else       hi |= u << (8 * (i - 4));
         }
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
-        if (sub == 0) meta[0] = scale;
+        // non-temporal stores: written through instead of left dirty in this XCD's L2, from which
+        // the streaming kernel that follows would have to fetch them across XCDs
+        __builtin_nontemporal_store(u32x2{lo, hi}, reinterpret_cast<u32x2 *>(dst));
+        if (sub == 0) __builtin_nontemporal_store(scale, meta);
     } else {
         float mn = f[0], mx = f[0];
 #pragma unroll
@@ -88,7 +93,7 @@ __device__ inline void quantize_row_store(const float (&f)[8], int sub, uint8_t 
         mn = dpp_xmin<0xB1>(mn);  mx = dpp_xmax<0xB1>(mx);
         mn = dpp_xmin<0x4E>(mn);  mx = dpp_xmax<0x4E>(mx);
         mn = dpp_xmin<0x141>(mn); mx = dpp_xmax<0x141>(mx);
-        mn = dpp_xmin<0x140>(mn); mx = dpp_xmax<0x140>(mx);
+        if (F::QL == 16) { mn = dpp_xmin<0x140>(mn); mx = dpp_xmax<0x140>(mx); }
         const float scale = __fdiv_rn(__fsub_rn(mx, mn), 15.0f);
         unsigned w = 0;
 #pragma unroll
@@ -97,11 +102,8 @@ __device__ inline void quantize_row_store(const float (&f)[8], int sub, uint8_t 
             c = fminf(fmaxf(c, 0.f), 15.f);
             w |= (unsigned)(int)c << (4 * i);
         }
-        *reinterpret_cast<unsigned *>(dst) = w;
-        if (sub == 0) {
-            meta[0] = scale;
-            meta[1] = mn;
-        }
+        __builtin_nontemporal_store(w, reinterpret_cast<unsigned *>(dst));
+        if (sub == 0) __builtin_nontemporal_store(f32x2{scale, mn}, reinterpret_cast<f32x2 *>(meta));
     }
 }
 
@@ -121,20 +123,19 @@ struct QSlabs {
     float *k_meta, *v_meta;
 };
 
-template <int BITS>
+template <int BITS, int D>
 __device__ inline void kvq_append_body(const QSlabs &c, const SeqState &st,
                                        const _Float16 *__restrict__ k_new,
                                        const _Float16 *__restrict__ v_new, int H, int b, bool bump)
 {
-    using F = QFmt<BITS>;
-    constexpr int D = F::D;
+    using F = QFmt<BITS, D>;
     const int cap = st.seq_cap[b];
     int new_len = 0;
     const int L = append_row(st, b, &new_len);
     if (L < 0) return;
-    const int sub = threadIdx.x & 15;          // position inside the 16-lane group of a row
-    const int group = threadIdx.x >> 4;
-    const int groups = blockDim.x >> 4;
+    const int sub = threadIdx.x % F::QL;       // position inside the lane group of a row
+    const int group = threadIdx.x / F::QL;
+    const int groups = blockDim.x / F::QL;
     const int64_t off = st.seq_off[b];
     for (int r = group; r < 2 * H; r += groups) {
         const int which = r >= H;
@@ -142,8 +143,8 @@ __device__ inline void kvq_append_body(const QSlabs &c, const SeqState &st,
         float f[8];
         load_row_f32((which ? v_new : k_new) + ((int64_t)b * H + h) * D + sub * 8, f);
         const int64_t row = (int64_t)h * cap + L;
-        quantize_row_store<BITS>(f, sub, (which ? c.v_codes : c.k_codes) + off + row * F::RB,
-                                 (which ? c.v_meta : c.k_meta) + (off / F::RB + row) * F::MW);
+        quantize_row_store<BITS, D>(f, sub, (which ? c.v_codes : c.k_codes) + off + row * F::RB,
+                                    (which ? c.v_meta : c.k_meta) + (off / F::RB + row) * F::MW);
     }
     if (bump) {
         __syncthreads();
@@ -154,28 +155,29 @@ __device__ inline void kvq_append_body(const QSlabs &c, const SeqState &st,
     }
 }
 
-template <int BITS>
+template <int BITS, int D>
 __global__ __launch_bounds__(256) void kvq_append_kernel(QSlabs c, SeqState st,
                                                          const _Float16 *__restrict__ k_new,
                                                          const _Float16 *__restrict__ v_new, int H)
 {
-    kvq_append_body<BITS>(c, st, k_new, v_new, H, blockIdx.x, true);
+    kvq_append_body<BITS, D>(c, st, k_new, v_new, H, blockIdx.x, true);
 }
 
 // front of a step in one launch: workgroup 0 plans for the lengths after the append, the
 // others append without touching seq_lens (see kv_append_plan_kernel)
-template <int BITS>
+template <int BITS, int D>
 __global__ __launch_bounds__(kPlanThreads) void kvq_append_plan_kernel(
     QSlabs c, SeqState st, const _Float16 *__restrict__ k_new, const _Float16 *__restrict__ v_new,
     PlanArgs a)
 {
     if (blockIdx.x == 0) plan_body(a);
-    else kvq_append_body<BITS>(c, st, k_new, v_new, a.H, (int)blockIdx.x - 1, false);
+    else kvq_append_body<BITS, D>(c, st, k_new, v_new, a.H, (int)blockIdx.x - 1, false);
 }
 
 // Bulk store of n consecutive token rows of one sequence (prompt ingestion): the same quantiser
-// as the append, rows given as fp16 [H][n][128].  grid.x covers the H * n rows, 16 per workgroup.
-template <int BITS>
+// as the append, rows given as fp16 [H][n][D].  grid.x covers the H * n rows, 256 / (D / 8) per
+// workgroup.
+template <int BITS, int D>
 __global__ __launch_bounds__(256) void kvq_store_rows_kernel(
     uint8_t *__restrict__ k_codes, uint8_t *__restrict__ v_codes,
     float *__restrict__ k_meta, float *__restrict__ v_meta,
@@ -184,15 +186,14 @@ __global__ __launch_bounds__(256) void kvq_store_rows_kernel(
     const _Float16 *__restrict__ k_rows, const _Float16 *__restrict__ v_rows, int H, int b, int t0,
     int n, int set_len)
 {
-    using F = QFmt<BITS>;
-    constexpr int D = F::D;
+    using F = QFmt<BITS, D>;
     const int cap = seq_cap[b];
     if (t0 + n > cap) {                                      // uniform over the grid: nothing is written
         if (blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, FD_ST_CAPACITY);
         return;
     }
-    const int sub = threadIdx.x & 15;
-    const int64_t r = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);   // row index in [H][n]
+    const int sub = threadIdx.x % F::QL;
+    const int64_t r = (int64_t)blockIdx.x * (256 / F::QL) + threadIdx.x / F::QL;   // row index in [H][n]
     const int64_t off = seq_off[b];
     if (r < (int64_t)H * n) {
         const int h = (int)(r / n), j = (int)(r - (int64_t)h * n);
@@ -200,11 +201,11 @@ __global__ __launch_bounds__(256) void kvq_store_rows_kernel(
         float f[8];
         if (k_rows) {
             load_row_f32(k_rows + r * D + sub * 8, f);
-            quantize_row_store<BITS>(f, sub, k_codes + off + row * F::RB, k_meta + (off / F::RB + row) * F::MW);
+            quantize_row_store<BITS, D>(f, sub, k_codes + off + row * F::RB, k_meta + (off / F::RB + row) * F::MW);
         }
         if (v_rows) {
             load_row_f32(v_rows + r * D + sub * 8, f);
-            quantize_row_store<BITS>(f, sub, v_codes + off + row * F::RB, v_meta + (off / F::RB + row) * F::MW);
+            quantize_row_store<BITS, D>(f, sub, v_codes + off + row * F::RB, v_meta + (off / F::RB + row) * F::MW);
         }
     }
     if (set_len && blockIdx.x == 0 && threadIdx.x == 0) {
@@ -214,11 +215,12 @@ __global__ __launch_bounds__(256) void kvq_store_rows_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Streaming kernel over codes, d = 128.  A row is 8 lanes x 16 elements (16 B of 8-bit or 8 B
-// of 4-bit codes per lane), a wave load covers 8 tokens (1 KB or 512 B); a workgroup block is
-// 4 waves x NL loads = 32 NL tokens.  The 8 NL tokens of a wave's tile map onto its first 8 NL
-// lanes for the row parameters: each lane loads those of "its" token (the other lanes repeat
-// them) and the values are handed to the lanes that need them with a cross-lane read.
+// Streaming kernel over codes.  A lane always holds 16 elements of a row (16 B of 8-bit or 8 B of
+// 4-bit codes), so a row is 8 lanes at d = 128 and 4 lanes at d = 64, and a wave load covers
+// RPW = 8 or 16 tokens (1 KB of 8-bit, 512 B of 4-bit codes either way); a workgroup block is
+// 4 waves x NL loads = 4 NL RPW tokens.  The NL RPW tokens of a wave's tile map onto its first
+// NL RPW lanes for the row parameters: each lane loads those of "its" token (the other lanes
+// repeat them) and the values are handed to the lanes that need them with a cross-lane read.
 //
 // Dequantisation is folded into the arithmetic.  With value = u * scale + zero (8 bit: u is
 // the stored byte and zero = -128 * scale):
@@ -307,18 +309,18 @@ template <int BITS> constexpr int q_wave_units() { return BITS == 4 ? 1 : 0; }
 
 // WPU = waves that share a unit: kWaves (the workgroup streams one (sequence, head) together,
 // wave w the w-th quarter of every block) or 1 (every wave streams a unit of its own).
-template <int BITS, int NL_, int WPU>
+template <int BITS, int D_, int NL_, int WPU>
 struct TileQ {
-    using F = QFmt<BITS>;
+    using F = QFmt<BITS, D_>;
     static constexpr int D = F::D;
     static constexpr int NL = NL_;
     static constexpr int RB = F::RB;
     static constexpr int MW = F::MW;
     static constexpr int LB = F::LB;
     static constexpr int NW = F::NW;
-    static constexpr int LPR = 8;                        // lanes per row
-    static constexpr int RPW = 8;                        // rows (tokens) per wave load
-    static constexpr int EPL = D / LPR;                  // elements per lane
+    static constexpr int LPR = F::LPR;                   // lanes per row: 8 (D = 128) or 4 (D = 64)
+    static constexpr int RPW = 64 / LPR;                 // rows (tokens) per wave load: 8 or 16
+    static constexpr int EPL = D / LPR;                  // elements per lane: 16
     // A wave's NL loads of a block are consecutive: it owns NL * RPW consecutive tokens, so the
     // row parameters it needs are one contiguous 64 B (8 bit) or 256 B (4 bit) run and no other
     // wave asks for a part of the same run.  (With the waves interleaved load by load, a wave's
@@ -601,7 +603,7 @@ struct PartialQArgs {
     PlanView v;
 };
 
-template <int BITS, int WPU>
+template <int BITS, int D_, int WPU>
 __device__ __forceinline__ void rpartq_body(const PartialQArgs &a)
 {
     const char *__restrict__ k_codes = a.k_codes;
@@ -619,7 +621,7 @@ __device__ __forceinline__ void rpartq_body(const PartialQArgs &a)
     float *part_ml = a.v.ml;
     const int H = a.H;
     const float qscale = a.qscale;
-    using T = TileQ<BITS, q_tile_loads<BITS>(), WPU>;
+    using T = TileQ<BITS, D_, q_tile_loads<BITS>(), WPU>;
     constexpr int D = T::D, LPR = T::LPR, EPL = T::EPL, RB = T::RB, MW = T::MW;
     // two sets, used by alternate units, so that one barrier per unit is enough
     __shared__ float sm_acc2[2][kWaves][D];
@@ -793,7 +795,7 @@ __device__ __forceinline__ void rpartq_body(const PartialQArgs &a)
         // rest of a few tokens then costs a few tokens' arithmetic, not a whole block's (uniform
         // 2048-token batches leave exactly one token, the one just appended).
         {
-            using T1 = TileQ<BITS, 1, WPU>;
+            using T1 = TileQ<BITS, D_, 1, WPU>;
             const unsigned mo1 = (unsigned)(T1::own_token(lane, wave) * MW);
             const unsigned co1 = T1::lane_offset(lane, wave);
             const int tok1 = T1::first_token(wave) + row;
@@ -927,22 +929,22 @@ __device__ __forceinline__ void rpartq_body(const PartialQArgs &a)
 // One kernel, two bodies: the planner decides per launch whether a workgroup's four waves share
 // a unit or take one each (short sequences: a unit's fixed cost, the epilogue with its barrier
 // and cross-wave combine, is then spread over four times as many blocks per wave).
-template <int BITS>
+template <int BITS, int D>
 __global__ __launch_bounds__(kThreads)
 __attribute__((amdgpu_waves_per_eu(q_wg_short<BITS>(), q_wg_short<BITS>())))
 void rpartq_partial_kernel(PartialQArgs a)
 {
     const int32_t *hdr = a.v.hdr;
-    if (!plan_matches(hdr, a.B, a.H, plan_kind(128, BITS), a.v.max_items, (int)gridDim.x, a.status)) return;
+    if (!plan_matches(hdr, a.B, a.H, plan_kind(D, BITS), a.v.max_items, (int)gridDim.x, a.status)) return;
     if ((int)blockIdx.x >= hdr[HDR_GRID]) return;
-    unit_prologue<128>(hdr, a.v.nchunk, a.v.newlen, a.v.newseen, a.seq_lens, a.seq_seen, a.out, a.B, a.H);
+    unit_prologue<D>(hdr, a.v.nchunk, a.v.newlen, a.v.newseen, a.seq_lens, a.seq_seen, a.out, a.B, a.H);
     if constexpr (q_wave_units<BITS>() != 0) {
         if (hdr[HDR_WAVE_UNITS]) {
-            rpartq_body<BITS, 1>(a);
+            rpartq_body<BITS, D, 1>(a);
             return;
         }
     }
-    rpartq_body<BITS, kWaves>(a);
+    rpartq_body<BITS, D, kWaves>(a);
 }
 
 // ---------------------------------------------------------------------------
@@ -951,7 +953,7 @@ void rpartq_partial_kernel(PartialQArgs a)
 int check_qdesc(const fd_kvq_desc *d)
 {
     if (!d) return FD_EINVAL;
-    if (d->B < 0 || d->H <= 0 || d->d != 128) return FD_EINVAL;
+    if (d->B < 0 || d->H <= 0 || (d->d != 128 && d->d != 64)) return FD_EINVAL;
     if (d->chunk_tokens < 0) return FD_EINVAL;
     if (d->bits != 0 && d->bits != 8 && d->bits != 4) return FD_EINVAL;
     if (d->B == 0) return FD_OK;
@@ -973,6 +975,16 @@ int check_qws(const fd_kvq_desc *d, const void *ws, size_t ws_bytes, WsLayout *w
     if (w->max_items < d->B) return FD_EWORKSPACE;
     return FD_OK;
 }
+
+// instantiate a launch for the descriptor's bit width and head dimension
+#define FD_Q_DISPATCH(desc, LAUNCH)                                    \
+    do {                                                               \
+        if ((desc)->bits == 4) {                                       \
+            if ((desc)->d == 64) { LAUNCH(4, 64); } else { LAUNCH(4, 128); } \
+        } else {                                                       \
+            if ((desc)->d == 64) { LAUNCH(8, 64); } else { LAUNCH(8, 128); } \
+        }                                                              \
+    } while (0)
 
 QSlabs q_slabs(const fd_kvq_desc *d)
 {
@@ -1016,7 +1028,7 @@ PlanArgs q_plan_args(const fd_kvq_desc *d, void *workspace, const WsLayout &w, i
     a.hashed = 1;
     a.wave_units = four ? q_wave_units<4>() : q_wave_units<8>();
     a.split = kQSplit;
-    a.kind = plan_kind(128, four ? 4 : 8);
+    a.kind = plan_kind(d->d, four ? 4 : 8);
     a.v = plan_view(workspace, w);
     return a;
 }
@@ -1038,14 +1050,13 @@ int launch_qpartial(const fd_kvq_desc *desc, const void *q, void *out, void *wor
     a.out = (_Float16 *)out;
     a.B = desc->B;
     a.H = desc->H;
-    a.qscale = (float)(1.4426950408889634 / 11.313708498984761);
+    a.qscale = (float)(1.4426950408889634 / (desc->d == 128 ? 11.313708498984761 : 8.0));
     a.v = plan_view(workspace, w);
-    if (desc->bits == 4)
-        hipLaunchKernelGGL(rpartq_partial_kernel<4>, dim3(q_wg_short<4>() * grid), dim3(kThreads), 0,
-                           (hipStream_t)stream, a);
-    else
-        hipLaunchKernelGGL(rpartq_partial_kernel<8>, dim3(q_wg_short<8>() * grid), dim3(kThreads), 0,
-                           (hipStream_t)stream, a);
+#define FD_LAUNCH(BITS, D)                                                                              \
+    hipLaunchKernelGGL((rpartq_partial_kernel<BITS, D>), dim3(q_wg_short<BITS>() * grid), dim3(kThreads), 0, \
+                       (hipStream_t)stream, a)
+    FD_Q_DISPATCH(desc, FD_LAUNCH);
+#undef FD_LAUNCH
     return launched();
 }
 
@@ -1063,14 +1074,12 @@ int launch_qfront(const fd_kvq_desc *desc, const void *k_new, const void *v_new,
                   const WsLayout &w, int grid, void *stream)
 {
     const PlanArgs pa = q_plan_args(desc, workspace, w, grid, 1);
-    if (desc->bits == 4)
-        hipLaunchKernelGGL(kvq_append_plan_kernel<4>, dim3(desc->B + 1), dim3(kPlanThreads), 0,
-                           (hipStream_t)stream, q_slabs(desc), q_seq_state(desc),
-                           (const _Float16 *)k_new, (const _Float16 *)v_new, pa);
-    else
-        hipLaunchKernelGGL(kvq_append_plan_kernel<8>, dim3(desc->B + 1), dim3(kPlanThreads), 0,
-                           (hipStream_t)stream, q_slabs(desc), q_seq_state(desc),
-                           (const _Float16 *)k_new, (const _Float16 *)v_new, pa);
+#define FD_LAUNCH(BITS, D)                                                                              \
+    hipLaunchKernelGGL((kvq_append_plan_kernel<BITS, D>), dim3(desc->B + 1), dim3(kPlanThreads), 0,     \
+                       (hipStream_t)stream, q_slabs(desc), q_seq_state(desc), (const _Float16 *)k_new,  \
+                       (const _Float16 *)v_new, pa)
+    FD_Q_DISPATCH(desc, FD_LAUNCH);
+#undef FD_LAUNCH
     return launched();
 }
 
@@ -1084,14 +1093,12 @@ int fd_kvq_append(const fd_kvq_desc *desc, const void *k_new, const void *v_new,
     if (rc != FD_OK) return rc;
     if (desc->B == 0) return FD_OK;
     if (!k_new || !v_new || !aligned(k_new, 16) || !aligned(v_new, 16)) return FD_EINVAL;
-    if (desc->bits == 4)
-        hipLaunchKernelGGL(kvq_append_kernel<4>, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
-                           q_slabs(desc), q_seq_state(desc), (const _Float16 *)k_new,
-                           (const _Float16 *)v_new, desc->H);
-    else
-        hipLaunchKernelGGL(kvq_append_kernel<8>, dim3(desc->B), dim3(256), 0, (hipStream_t)stream,
-                           q_slabs(desc), q_seq_state(desc), (const _Float16 *)k_new,
-                           (const _Float16 *)v_new, desc->H);
+#define FD_LAUNCH(BITS, D)                                                                              \
+    hipLaunchKernelGGL((kvq_append_kernel<BITS, D>), dim3(desc->B), dim3(256), 0, (hipStream_t)stream,  \
+                       q_slabs(desc), q_seq_state(desc), (const _Float16 *)k_new,                       \
+                       (const _Float16 *)v_new, desc->H)
+    FD_Q_DISPATCH(desc, FD_LAUNCH);
+#undef FD_LAUNCH
     return launched();
 }
 
@@ -1119,19 +1126,15 @@ int fd_kvq_store_rows(const fd_kvq_desc *desc, int32_t b, int32_t t0, int32_t n,
     if ((k_rows && !aligned(k_rows, 16)) || (v_rows && !aligned(v_rows, 16))) return FD_EINVAL;
     if (n == 0 && !set_len) return FD_OK;
     const int64_t rows = (int64_t)desc->H * n;
-    const unsigned grid = (unsigned)((rows + 15) / 16 > 0 ? (rows + 15) / 16 : 1);
-    if (desc->bits == 4)
-        hipLaunchKernelGGL(kvq_store_rows_kernel<4>, dim3(grid), dim3(256), 0, (hipStream_t)stream,
-                           (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
-                           desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens, desc->seq_seen,
-                           desc->status, (const _Float16 *)k_rows, (const _Float16 *)v_rows, desc->H,
-                           b, t0, n, set_len);
-    else
-        hipLaunchKernelGGL(kvq_store_rows_kernel<8>, dim3(grid), dim3(256), 0, (hipStream_t)stream,
-                           (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale,
-                           desc->v_scale, desc->seq_off, desc->seq_cap, desc->seq_lens, desc->seq_seen,
-                           desc->status, (const _Float16 *)k_rows, (const _Float16 *)v_rows, desc->H,
-                           b, t0, n, set_len);
+    const int per_wg = 256 / (desc->d / 8);                   // rows a workgroup handles
+    const unsigned grid = (unsigned)(rows > 0 ? (rows + per_wg - 1) / per_wg : 1);
+#define FD_LAUNCH(BITS, D)                                                                              \
+    hipLaunchKernelGGL((kvq_store_rows_kernel<BITS, D>), dim3(grid), dim3(256), 0, (hipStream_t)stream, \
+                       (uint8_t *)desc->k_codes, (uint8_t *)desc->v_codes, desc->k_scale, desc->v_scale, \
+                       desc->seq_off, desc->seq_cap, desc->seq_lens, desc->seq_seen, desc->status,      \
+                       (const _Float16 *)k_rows, (const _Float16 *)v_rows, desc->H, b, t0, n, set_len)
+    FD_Q_DISPATCH(desc, FD_LAUNCH);
+#undef FD_LAUNCH
     return launched();
 }
 
@@ -1197,9 +1200,14 @@ int fd_rpartq_merge(const fd_kvq_desc *desc, void *out,
     rc = check_qws(desc, workspace, workspace_bytes, &w);
     if (rc != FD_OK) return rc;
     const int64_t bh = (int64_t)desc->B * desc->H;
-    hipLaunchKernelGGL(rpart_merge_kernel<128>, dim3((unsigned)((bh + 3) / 4)), dim3(256), 0,
-                       (hipStream_t)stream, plan_view(workspace, w), (_Float16 *)out, desc->B, desc->H,
-                       plan_kind(128, desc->bits == 4 ? 4 : 8), desc->status);
+    const dim3 grid((unsigned)((bh + 3) / 4));
+    const int kind = plan_kind(desc->d, desc->bits == 4 ? 4 : 8);
+    if (desc->d == 128)
+        hipLaunchKernelGGL(rpart_merge_kernel<128>, grid, dim3(256), 0, (hipStream_t)stream,
+                           plan_view(workspace, w), (_Float16 *)out, desc->B, desc->H, kind, desc->status);
+    else
+        hipLaunchKernelGGL(rpart_merge_kernel<64>, grid, dim3(256), 0, (hipStream_t)stream,
+                           plan_view(workspace, w), (_Float16 *)out, desc->B, desc->H, kind, desc->status);
     return launched();
 }
 

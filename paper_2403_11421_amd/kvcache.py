@@ -80,12 +80,12 @@ class KVCache:
 
 
 class KVCacheQ:
-    """Quantised KV-cache of one layer in the layout of ``fd_kvq_desc`` (d = 128, 8 or 4 bits)."""
+    """Quantised KV-cache of one layer in the layout of ``fd_kvq_desc`` (d = 128 or 64, 8 or 4 bits)."""
 
     def __init__(self, B: int, H: int, d: int, capacities: Sequence[int], device="cuda",
                  chunk_tokens: int = 0, n_sink: Optional[int] = None, bits: int = 8,
                  zero_fill: bool = True):
-        assert len(capacities) == B and d == 128 and bits in (8, 4)
+        assert len(capacities) == B and d in (64, 128) and bits in (8, 4)
         self.B, self.H, self.d, self.bits = B, H, d, bits
         self.rb = d * bits // 8                         # bytes of codes per row
         self.mw = 1 if bits == 8 else 2                 # floats of parameters per row

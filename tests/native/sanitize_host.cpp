@@ -145,7 +145,7 @@ static void entry_point_argument_checks()
     CHECK(fd_kvq_store_rows(&q, 3, 0, 1, P(0x9000), nullptr, 0, nullptr) == FD_EINVAL);
     q.bits = 5;
     CHECK(fd_kvq_reset(&q, nullptr, 0, nullptr) == FD_EINVAL);
-    q.bits = 8; q.d = 64;
+    q.bits = 8; q.d = 96;
     CHECK(fd_rpartq_plan(&q, P(0xB000), 1u << 30, nullptr) == FD_EINVAL);
 
     CHECK(fd_workspace_bytes(256, 32, 128, 0) > 0 && fd_workspace_bytes(256, 32, 96, 0) == 0);

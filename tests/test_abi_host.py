@@ -104,6 +104,8 @@ def test_new_entry_points_check_their_arguments_on_the_host():
     assert lib.fd_kvq_store_rows(ctypes.byref(q), 2, 0, 1, 0x9000, None, 0, None) == rpart.FD_EINVAL
     assert lib.fd_kvq_store_rows(ctypes.byref(q), 0, 0, 0, None, None, 0, None) == rpart.FD_OK
     q.d = 64
+    assert lib.fd_kvq_store_rows(ctypes.byref(q), 0, 0, 0, None, None, 0, None) == rpart.FD_OK
+    q.d = 96
     assert lib.fd_kvq_store_rows(ctypes.byref(q), 0, 0, 0, None, None, 0, None) == rpart.FD_EINVAL
 
 

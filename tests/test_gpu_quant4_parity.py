@@ -81,8 +81,8 @@ def check_q4step(case, batch=None, use_step=False):
     return err, maxv
 
 
-def _cfg(name, B, H, **kw):
-    return W.RPartConfig(name, B, H, 128, "const", 0, 0, **kw)
+def _cfg(name, B, H, d=128, **kw):
+    return W.RPartConfig(name, B, H, d, "const", 0, 0, **kw)
 
 
 def test_bulk_store_quantises_like_the_oracle():
@@ -104,9 +104,10 @@ EDGE_LENS = [0, 1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 
              1000, 2500]
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("chunk", [0, 64, 256, 1024, 4096])
-def test_edge_lengths_all_chunk_sizes(chunk):
-    cfg = _cfg("q4edges", len(EDGE_LENS), 3)
+def test_edge_lengths_all_chunk_sizes(chunk, d):
+    cfg = _cfg("q4edges", len(EDGE_LENS), 3, d)
     case = Q4Case(cfg, EDGE_LENS, seed=21, chunk_tokens=chunk)
     check_q4step(case)
     assert rpart.fd_plan_info(case.ws)["total_tokens"] == sum(EDGE_LENS) + len(EDGE_LENS)
@@ -135,8 +136,9 @@ def test_more_sequences_than_planner_threads():
     assert rpart.fd_plan_info(case.ws)["total_tokens"] == sum(lens) + len(lens)
 
 
-def test_step_entry_point_many_heads_and_peaked_keys():
-    cfg = W.RPartConfig("q4step", 6, 40, 128, "const", 0, 0, peaked_keys=True)
+@pytest.mark.parametrize("d", [128, 64])
+def test_step_entry_point_many_heads_and_peaked_keys(d):
+    cfg = W.RPartConfig("q4step", 6, 40, d, "const", 0, 0, peaked_keys=True)
     case = Q4Case(cfg, [300, 17, 2049, 64, 999, 4100], seed=5)
     check_q4step(case, use_step=True)
 
@@ -243,5 +245,18 @@ def test_random_length_mixes(seed):
                                               np.where(kinds == 2, rng.integers(200, 901, 14),
                                                        rng.integers(1000, 3001, 14))))]
     chunk = int(rng.choice([0, 64, 96, 160, 512, 1000]))
-    case = Q4Case(_cfg("rand%d" % seed, len(lens), 2), lens, seed=50 + seed, chunk_tokens=chunk)
+    case = Q4Case(_cfg("rand%d" % seed, len(lens), 2, 64 if seed % 2 else 128), lens, seed=50 + seed,
+                  chunk_tokens=chunk)
+    check_q4step(case)
+
+
+def test_config1_shape_with_a_4bit_cache_and_short_batch_modes_at_d64():
+    """Config 1's shape (B=4, H=8, d=64, 128 cached tokens + 1) on the 4-bit cache, and a batch
+    of short sequences at d = 64 (each wave takes units of its own there)."""
+    cfg = W.CONFIGS["c1_tiny"]
+    case = Q4Case(cfg, W.seq_lens(cfg))
+    err, maxv = check_q4step(case, use_step=True)
+    print(f"c1_tiny/int4: max|err|={err:.3e} bound={TOL * maxv:.3e}", flush=True)
+    lens = [(37 * i) % 300 for i in range(40)]
+    case = Q4Case(_cfg("q4short64", len(lens), 5, 64), lens, seed=3)
     check_q4step(case)

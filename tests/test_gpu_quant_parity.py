@@ -74,8 +74,8 @@ def check_qstep(case, batch=None, use_step=False):
     return err, maxv
 
 
-def _cfg(name, B, H, **kw):
-    return W.RPartConfig(name, B, H, 128, "const", 0, 0, **kw)
+def _cfg(name, B, H, d=128, **kw):
+    return W.RPartConfig(name, B, H, d, "const", 0, 0, **kw)
 
 
 def test_bulk_store_quantises_like_the_oracle():
@@ -96,9 +96,10 @@ def test_bulk_store_quantises_like_the_oracle():
 EDGE_LENS = [0, 1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1000, 2500]
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("chunk", [0, 64, 256, 1024, 4096])
-def test_edge_lengths_all_chunk_sizes(chunk):
-    cfg = _cfg("qedges", len(EDGE_LENS), 3)
+def test_edge_lengths_all_chunk_sizes(chunk, d):
+    cfg = _cfg("qedges", len(EDGE_LENS), 3, d)
     case = QCase(cfg, EDGE_LENS, seed=21, chunk_tokens=chunk)
     check_qstep(case)
     info = rpart.fd_plan_info(case.ws)
@@ -116,8 +117,9 @@ def test_more_sequences_than_planner_threads():
     assert rpart.fd_plan_info(case.ws)["total_tokens"] == sum(lens) + len(lens)
 
 
-def test_step_entry_point_many_heads_and_peaked_keys():
-    cfg = W.RPartConfig("qstep", 6, 40, 128, "const", 0, 0, peaked_keys=True)
+@pytest.mark.parametrize("d", [128, 64])
+def test_step_entry_point_many_heads_and_peaked_keys(d):
+    cfg = W.RPartConfig("qstep", 6, 40, d, "const", 0, 0, peaked_keys=True)
     case = QCase(cfg, [300, 17, 2049, 64, 999, 4100], seed=5)
     check_qstep(case, use_step=True)
 
@@ -181,7 +183,7 @@ def test_invalid_arguments():
     cfg = _cfg("qinval", 2, 2)
     case = QCase(cfg, [5, 6])
     bad = rpart.fd_kvq_desc.from_buffer_copy(case.cache.desc)
-    bad.d = 64
+    bad.d = 96
     with pytest.raises(rpart.FdError):
         rpart.fd_kvq_append(bad, case.k_new, case.v_new)
     with pytest.raises(rpart.FdError):
@@ -214,6 +216,14 @@ def test_long_context_few_sequences():
     assert plan["items"] > 16
 
 
+def test_config1_shape_with_a_quantised_cache():
+    """Config 1's shape (B=4, H=8, d=64, 128 cached tokens + 1) on the 8-bit cache."""
+    cfg = W.CONFIGS["c1_tiny"]
+    case = QCase(cfg, W.seq_lens(cfg))
+    err, maxv = check_qstep(case, use_step=True)
+    print(f"c1_tiny/int8: max|err|={err:.3e} bound={TOL * maxv:.3e}", flush=True)
+
+
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
 def test_random_length_mixes(seed):
     """Random ragged batches (empty, a few tokens, a few blocks, a few thousand tokens) under a
@@ -225,5 +235,6 @@ def test_random_length_mixes(seed):
                                               np.where(kinds == 2, rng.integers(200, 901, 14),
                                                        rng.integers(1000, 3001, 14))))]
     chunk = int(rng.choice([0, 64, 96, 160, 512, 1000]))
-    case = QCase(_cfg("rand%d" % seed, len(lens), 2), lens, seed=50 + seed, chunk_tokens=chunk)
+    case = QCase(_cfg("rand%d" % seed, len(lens), 2, 64 if seed % 2 else 128), lens, seed=50 + seed,
+                 chunk_tokens=chunk)
     check_qstep(case)

@@ -59,9 +59,10 @@ def test_fp16_store_rows_copies_bits_and_leaves_the_rest_alone(d):
             rpart.fd_kv_store_rows(cache.desc, bad[0], bad[1], k_rows, v_rows)
 
 
+@pytest.mark.parametrize("d", [128, 64])
 @pytest.mark.parametrize("nbits", [8, 4])
-def test_quantised_store_rows_matches_the_oracle_quantiser(nbits):
-    H, d, n = 5, 128, 19
+def test_quantised_store_rows_matches_the_oracle_quantiser(nbits, d):
+    H, n = 5, 19
     cache = KVCacheQ(3, H, d, [64, 30, 19], bits=nbits)
     quantise = O.quantize_rows_i8 if nbits == 8 else O.quantize_rows_u4
     k_rows, v_rows = _special_rows(H, n, d, 3), _special_rows(H, n, d, 4)
