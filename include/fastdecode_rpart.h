@@ -271,13 +271,16 @@ int fd_plan_info(const void *workspace, int32_t info[4], void *stream);
  *       row gets scale 0 and codes 0.  Two floats (scale, zero) per row in k_scale.
  * The query needs no transformation for these schemes.  d is 128 or 64.
  *
- * With rb = d * bits / 8 bytes of codes per row, byte i of the K row of sequence b,
- * head h, token t is
- *     k_codes[ seq_off[b] + ((int64)h * seq_cap[b] + t) * rb + i ]
- * and its parameters start at float index
- *     (seq_off[b] / rb + (int64)h * seq_cap[b] + t) * (bits == 4 ? 2 : 1)   of k_scale;
- * likewise for V.  seq_off[b] must be a multiple of 128 bytes; blocks must not overlap.
- * k_scale and v_scale must be 8-byte aligned.
+ * With rb = d * bits / 8 bytes of codes per row, the K row of sequence b, head h, token t is
+ * row r = h * rows_b + t of the sequence's block, where rows_b = seq_cap[b] (8 bit) or
+ * seq_cap[b] rounded up to even (4 bit).  Byte i of that row is
+ *     8 bit:  k_codes[ seq_off[b] + r * rb + i ]
+ *     4 bit:  k_codes[ seq_off[b] + (r / 2) * 2 rb + (i / 8) * 16 + (r % 2) * 8 + i % 8 ]
+ * (4-bit rows lie in pairs whose 8-byte pieces alternate, so that one 16-byte load brings the
+ * same 16 elements of two consecutive tokens), and its parameters start at float index
+ *     (seq_off[b] / rb + r) * (bits == 4 ? 2 : 1)   of k_scale;
+ * likewise for V.  A block holds H * rows_b rows; seq_off[b] must be a multiple of 128 bytes;
+ * blocks must not overlap.  k_scale and v_scale must be 8-byte aligned.
  */
 typedef struct fd_kvq_desc {
     void          *k_codes;       /* device, byte slab of K codes                               */

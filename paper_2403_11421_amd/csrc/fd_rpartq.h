@@ -52,16 +52,37 @@ template <> struct CodeVec<8> { typedef u32x4 type; };
 template <> struct CodeVec<4> { typedef u32x2 type; };
 
 // ---------------------------------------------------------------------------
+// Where a row's codes live.  A sequence's block holds, for each head, head_rows(capacity) rows.
+// 8 bit: the rows follow one another.  4 bit: the rows lie in pairs (rows 2p and 2p+1 of a
+// head) whose 8-byte pieces alternate: piece c of row 2p at byte 16 c of the pair, piece c of
+// row 2p+1 at 16 c + 8.  The streaming kernel then reads both rows' 16 elements with one 16-byte
+// load per lane.  A head's rows are padded to an even count so that every head starts a pair;
+// the row parameters keep one entry per row, with the same padding.
+// ---------------------------------------------------------------------------
+template <int BITS> __host__ __device__ inline int head_rows(int cap) { return BITS == 4 ? (cap + 1) & ~1 : cap; }
+
+// byte offset, inside the block, of byte o of row `row` (row counted over the block's heads)
+template <int BITS, int D>
+__device__ inline int64_t code_byte(int64_t row, int o)
+{
+    constexpr int RB = QFmt<BITS, D>::RB;
+    if (BITS == 8) return row * RB + o;
+    return (row >> 1) * (2 * RB) + (o >> 3) * 16 + (int)(row & 1) * 8 + (o & 7);
+}
+
+// ---------------------------------------------------------------------------
 // Row quantiser.  A row (D fp16) is handled by D / 8 consecutive lanes with 8 values each:
-// `sub` is the lane's position among them, f its values, dst the row's first code byte,
-// meta the row's parameters.  Every step is a correctly rounded binary32 operation, so the
-// stored bytes are those of the definition evaluated in IEEE binary32.
+// `sub` is the lane's position among them, f its values, block the first code byte of the
+// sequence's block, row the row's index in it, meta the row's parameters.  Every step is a
+// correctly rounded binary32 operation, so the stored bytes are those of the definition
+// evaluated in IEEE binary32.
 // ---------------------------------------------------------------------------
 template <int BITS, int D>
-__device__ inline void quantize_row_store(const float (&f)[8], int sub, uint8_t *dst, float *meta)
+__device__ inline void quantize_row_store(const float (&f)[8], int sub, uint8_t *block, int64_t row,
+                                          float *meta)
 {
     using F = QFmt<BITS, D>;
-    dst += sub * (F::RB / F::QL);                             // this lane's 8 codes
+    uint8_t *dst = block + code_byte<BITS, D>(row, sub * (F::RB / F::QL));   // this lane's 8 codes
     if (BITS == 8) {
         float amax = 0.f;
 #pragma unroll
@@ -142,8 +163,8 @@ __device__ inline void kvq_append_body(const QSlabs &c, const SeqState &st,
         const int h = which ? r - H : r;
         float f[8];
         load_row_f32((which ? v_new : k_new) + ((int64_t)b * H + h) * D + sub * 8, f);
-        const int64_t row = (int64_t)h * cap + L;
-        quantize_row_store<BITS, D>(f, sub, (which ? c.v_codes : c.k_codes) + off + row * F::RB,
+        const int64_t row = (int64_t)h * head_rows<BITS>(cap) + L;
+        quantize_row_store<BITS, D>(f, sub, (which ? c.v_codes : c.k_codes) + off, row,
                                     (which ? c.v_meta : c.k_meta) + (off / F::RB + row) * F::MW);
     }
     if (bump) {
@@ -197,15 +218,15 @@ __global__ __launch_bounds__(256) void kvq_store_rows_kernel(
     const int64_t off = seq_off[b];
     if (r < (int64_t)H * n) {
         const int h = (int)(r / n), j = (int)(r - (int64_t)h * n);
-        const int64_t row = (int64_t)h * cap + t0 + j;
+        const int64_t row = (int64_t)h * head_rows<BITS>(cap) + t0 + j;
         float f[8];
         if (k_rows) {
             load_row_f32(k_rows + r * D + sub * 8, f);
-            quantize_row_store<BITS, D>(f, sub, k_codes + off + row * F::RB, k_meta + (off / F::RB + row) * F::MW);
+            quantize_row_store<BITS, D>(f, sub, k_codes + off, row, k_meta + (off / F::RB + row) * F::MW);
         }
         if (v_rows) {
             load_row_f32(v_rows + r * D + sub * 8, f);
-            quantize_row_store<BITS, D>(f, sub, v_codes + off + row * F::RB, v_meta + (off / F::RB + row) * F::MW);
+            quantize_row_store<BITS, D>(f, sub, v_codes + off, row, v_meta + (off / F::RB + row) * F::MW);
         }
     }
     if (set_len && blockIdx.x == 0 && threadIdx.x == 0) {
@@ -325,8 +346,16 @@ struct TileQ {
     // row parameters it needs are one contiguous 64 B (8 bit) or 256 B (4 bit) run and no other
     // wave asks for a part of the same run.  (With the waves interleaved load by load, a wave's
     // parameters came in 32 B / 64 B pieces of memory lines that its neighbours fetched again.)
-    static constexpr int STRIDE = 64 * LB;               // bytes between a wave's consecutive loads
-    static constexpr int TSTEP = RPW;                    // tokens between a wave's consecutive loads
+    //
+    // 4-bit rows lie in memory in pairs (see pair_byte): a lane's 16-byte load brings its 8 bytes
+    // of an even row and of the odd row after it.  The arithmetic still sees NL "loads" of RPW
+    // rows (slot j = half j % 2 of memory load j / 2), so only the loads and the slot -> token
+    // map know about pairs.  Against 8-byte loads of plain rows this halves the requests that
+    // the vector memory pipeline tracks per byte: its queue was full 43 % of the time and HBM
+    // was not (no credit stalls), +4 % at 2048 tokens per sequence, +6 % on the geometric mix.
+    static constexpr bool PAIRED = BITS == 4;
+    static_assert(!PAIRED || NL % 2 == 0, "4-bit tiles are made of row pairs");
+    static constexpr int STRIDE = 64 * LB * (PAIRED ? 2 : 1);   // bytes between a wave's consecutive memory loads
     static constexpr int BLK_TOK = NL * WPU * RPW;       // tokens per workgroup block
     static constexpr int BLK_BYTES = NL * WPU * 64 * LB; // bytes of K (or V) codes per block
     static_assert(NL * RPW <= 64, "one lane per token of the tile for the row parameters");
@@ -339,11 +368,37 @@ struct TileQ {
     {
         return first_token(wave) + lane % (NL * RPW);
     }
-    // first token (inside a block) of the wave's run, and the byte offset of a lane's part of load 0
+    // first token (inside a block) of the wave's run, and the byte offset of a lane's part of
+    // memory load 0
     __device__ static inline int first_token(int wave) { return wave * NL * RPW; }
     __device__ static inline unsigned lane_offset(int lane, int wave)
     {
-        return (unsigned)((wave * NL * 64 + lane) * LB);
+        return PAIRED ? (unsigned)((wave * (NL / 2) * 64 + lane) * 16) : (unsigned)((wave * NL * 64 + lane) * LB);
+    }
+    // token (inside the wave's run) that slot j holds for the lanes of row `row`
+    __device__ static inline int slot_token(int j, int row)
+    {
+        return PAIRED ? 2 * ((j / 2) * RPW + row) + (j & 1) : j * RPW + row;
+    }
+    // memory loads of the K (or V) codes of one tile into the slots
+    __device__ inline void load_codes(CV (&dst)[NL], Rsrc r, unsigned co)
+    {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) load_slot(dst, j, r, co);
+    }
+    // the load that fills slot j, issued when the arithmetic is done with the slot: for a pair
+    // that is after its odd half (the even half's registers are written by the same load)
+    __device__ inline void load_slot(CV (&dst)[NL], int j, Rsrc r, unsigned co)
+    {
+        if constexpr (PAIRED) {
+            if (j & 1) {
+                const u32x4 t = ld_buf<u32x4>(r, co, (j / 2) * STRIDE);
+                dst[j - 1] = CV{t[0], t[1]};
+                dst[j] = CV{t[2], t[3]};
+            }
+        } else {
+            dst[j] = ld_buf<CV>(r, co, j * STRIDE);
+        }
     }
 
     // mo4 = byte offset of this lane's token in the parameter stream
@@ -375,33 +430,47 @@ struct TileQ {
     __device__ inline void load(const char *kb, const char *vb, const float *kmb, const float *vmb,
                                 unsigned co, unsigned mo)
     {
-        const Rsrc rk = stream_rsrc(kb), rv = stream_rsrc(vb);
         load_kmeta(kmb, mo * 4u);
-#pragma unroll
-        for (int j = 0; j < NL; ++j) k[j] = ld_buf<CV>(rk, co, j * STRIDE);
+        load_codes(k, stream_rsrc(kb), co);
         load_vmeta(vmb, mo * 4u);
-#pragma unroll
-        for (int j = 0; j < NL; ++j) v[j] = ld_buf<CV>(rv, co, j * STRIDE);
+        load_codes(v, stream_rsrc(vb), co);
     }
 
     // ragged last block of `rem` >= 1 tokens: lanes whose token is at or beyond `rem` re-read
-    // token rem-1 (in bounds) and are masked in update<true, ...>
+    // the row (the pair) of token rem-1 (in bounds) and are masked in update<true, ...>.  `row` is
+    // the lane's row, wtok the first token of the wave's run, own the token whose parameters the
+    // lane loads.  The odd row of the last pair may lie beyond `rem`: it is inside the block
+    // (a head's rows are padded to an even count) and masked like the others.
     __device__ inline void load_tail(const char *kb, const char *vb, const float *kmb,
-                                     const float *vmb, unsigned co, unsigned mo, int tok0, int own,
-                                     int rem)
+                                     const float *vmb, unsigned co, unsigned mo, int row, int wtok,
+                                     int own, int rem)
     {
         const int sback = own > rem - 1 ? own - (rem - 1) : 0;
         const unsigned mt = mo - (unsigned)(sback * MW);           // token min(own, rem-1) >= 0
         load_kmeta(kmb, mt * 4u);
         load_vmeta(vmb, mt * 4u);
         const Rsrc rk = stream_rsrc(kb), rv = stream_rsrc(vb);
+        if constexpr (PAIRED) {
 #pragma unroll
-        for (int j = 0; j < NL; ++j) {
-            const int over = j * TSTEP + tok0 - (rem - 1);
-            const int back = over > 0 ? over * RB : 0;
-            const unsigned ct = co + (unsigned)(j * STRIDE) - (unsigned)back;   // row min(., rem-1) >= 0
-            k[j] = ld_buf<CV>(rk, ct, 0);
-            v[j] = ld_buf<CV>(rv, ct, 0);
+            for (int jp = 0; jp < NL / 2; ++jp) {
+                const int over = (wtok + slot_token(2 * jp, row)) / 2 - (rem - 1) / 2;   // pairs beyond the last one
+                const int back = over > 0 ? over * 2 * RB : 0;
+                const unsigned ct = co + (unsigned)(jp * STRIDE) - (unsigned)back;
+                const u32x4 a = ld_buf<u32x4>(rk, ct, 0), b = ld_buf<u32x4>(rv, ct, 0);
+                k[2 * jp] = CV{a[0], a[1]};
+                k[2 * jp + 1] = CV{a[2], a[3]};
+                v[2 * jp] = CV{b[0], b[1]};
+                v[2 * jp + 1] = CV{b[2], b[3]};
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NL; ++j) {
+                const int over = wtok + slot_token(j, row) - (rem - 1);
+                const int back = over > 0 ? over * RB : 0;
+                const unsigned ct = co + (unsigned)(j * STRIDE) - (unsigned)back;   // row min(., rem-1) >= 0
+                k[j] = ld_buf<CV>(rk, ct, 0);
+                v[j] = ld_buf<CV>(rv, ct, 0);
+            }
         }
     }
 
@@ -500,7 +569,7 @@ struct TileQ {
     // blocks of loads per wave stay in flight during the arithmetic as well.
     template <bool MASKED, bool REFILL>
     __device__ inline void update(const f16x2 (&qh)[EPL / 2], float kmul, float qs, float &m,
-                                  float &l, float &aux, float (&acc)[EPL], int row, int tok0,
+                                  float &l, float &aux, float (&acc)[EPL], int row, int wtok,
                                   int rem, unsigned co = 0, unsigned mo = 0,
                                   const char *kp2 = nullptr, const char *vp2 = nullptr,
                                   const float *kmp2 = nullptr, const float *vmp2 = nullptr)
@@ -515,8 +584,8 @@ struct TileQ {
         float s[NL], z[NL];
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
-            s[j] = __shfl(ksm, j * RPW + row);
-            z[j] = BITS == 8 ? 0.f : __shfl(kzq, j * RPW + row);
+            s[j] = __shfl(ksm, slot_token(j, row));
+            z[j] = BITS == 8 ? 0.f : __shfl(kzq, slot_token(j, row));
         }
         if (REFILL) {
             sched_fence();
@@ -528,12 +597,12 @@ struct TileQ {
             float a = dot_codes(k[j], qh);
             if (REFILL) {
                 sched_fence();
-                k[j] = ld_buf<CV>(stream_rsrc(kp2), co, j * STRIDE);
+                load_slot(k, j, stream_rsrc(kp2), co);
                 sched_fence();
             }
             a = row_sum<LPR>(a);
             a = BITS == 8 ? (a + c0) * s[j] : __builtin_fmaf(a, s[j], z[j]);
-            if (MASKED && j * TSTEP + tok0 >= rem) a = kNegBig;
+            if (MASKED && wtok + slot_token(j, row) >= rem) a = kNegBig;
             s[j] = a;
         }
         float tm = s[0];
@@ -556,11 +625,11 @@ struct TileQ {
 #pragma unroll
         for (int j = 0; j < NL; ++j) {
             float p = fast_exp2(s[j] - mn);
-            if (MASKED && j * TSTEP + tok0 >= rem) p = 0.f;
+            if (MASKED && wtok + slot_token(j, row) >= rem) p = 0.f;
             l += p;
-            const float pv24 = p * __shfl(vsm, j * RPW + row);
+            const float pv24 = p * __shfl(vsm, slot_token(j, row));
             aux = BITS == 8 ? __builtin_fmaf(pv24, -128.0f / 16777216.0f, aux)
-                            : __builtin_fmaf(p, __shfl(vz, j * RPW + row), aux);
+                            : __builtin_fmaf(p, __shfl(vz, slot_token(j, row)), aux);
             s[j] = pv24;
         }
         if (REFILL) {
@@ -573,7 +642,7 @@ struct TileQ {
             axpy_codes(v[j], s[j], acc);
             if (REFILL) {
                 sched_fence();
-                v[j] = ld_buf<CV>(stream_rsrc(vp2), co, j * STRIDE);
+                load_slot(v, j, stream_rsrc(vp2), co);
                 sched_fence();
             }
         }
@@ -660,13 +729,14 @@ __device__ __forceinline__ void rpartq_body(const PartialQArgs &a)
                 const int4 it = items[item];
                 const int cap = seq_cap[it.x];
                 // inside this cache's block, and not empty, whatever lengths the plan was made from
-                const int t1 = min(it.z, cap), t0 = min(it.y, max(t1 - 1, 0));
+                // (4 bit: a chunk starts with a pair, as the planner's chunks do)
+                const int t1 = min(it.z, cap), t0 = min(it.y, max(t1 - 1, 0)) & (BITS == 4 ? ~1 : ~0);
                 u.h = (int)(p - (long long)sidx * H);
                 u.b = it.x;
                 u.item = item;
                 u.nch = it.w;
                 u.ntok = t1 - t0;
-                u.row0 = seq_off[it.x] / RB + (int64_t)u.h * cap + t0;   // row index
+                u.row0 = seq_off[it.x] / RB + (int64_t)u.h * head_rows<BITS>(cap) + t0;   // row index
             }
         }
         return u;
@@ -791,23 +861,30 @@ __device__ __forceinline__ void rpartq_body(const PartialQArgs &a)
                 A.template update<false, false>(qh, kmul, qs, m, l, aux, acc, row, 0, 0);
             }
         }
-        // The ragged rest of the unit goes through tiles of one wave load (8 tokens per wave): a
-        // rest of a few tokens then costs a few tokens' arithmetic, not a whole block's (uniform
-        // 2048-token batches leave exactly one token, the one just appended).
+        // The ragged rest of the unit goes through tiles of one memory load per wave (8 tokens, 16
+        // for 4-bit pairs): a rest of a few tokens then costs a few tokens' arithmetic, not a whole
+        // block's (uniform 2048-token batches leave exactly one token, the one just appended).
         {
-            using T1 = TileQ<BITS, D_, 1, WPU>;
-            const unsigned mo1 = (unsigned)(T1::own_token(lane, wave) * MW);
-            const unsigned co1 = T1::lane_offset(lane, wave);
-            const int tok1 = T1::first_token(wave) + row;
+            using T1 = TileQ<BITS, D_, BITS == 4 ? 2 : 1, WPU>;
+            const int wtok1 = T1::first_token(wave);
             for (int t0 = 0; t0 < rem; t0 += T1::BLK_TOK) {
                 const int r1 = min(rem - t0, T1::BLK_TOK);
-                if (T1::first_token(wave) < r1) {          // this wave has at least one valid row
+                if (wtok1 < r1) {                          // this wave has at least one valid row
+                    // The lane-dependent offsets of this path are worked out here, from a copy of
+                    // the lane number that the compiler must take as new: hoisted out of the unit
+                    // loop they would sit in registers all through the streaming loop, which has
+                    // none to spare (nine were spilled to scratch memory; with scratch memory in
+                    // use the kernel ran 4-6 % slower on batches of equal-length sequences).
+                    int lane1 = lane;
+                    asm volatile("" : "+v"(lane1));
+                    const int row1 = lane1 / LPR;
+                    const int own1 = T1::own_token(lane1, wave);
                     const int64_t o = (int64_t)n_blk * T::BLK_BYTES + (int64_t)t0 * RB;
                     const int64_t so = (int64_t)n_blk * MSTEP + (int64_t)t0 * MW;
                     T1 C;
-                    C.load_tail(kp + o, vp + o, kmp + so, vmp + so, co1, mo1, tok1,
-                                T1::own_token(lane, wave), r1);
-                    C.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row, tok1, r1);
+                    C.load_tail(kp + o, vp + o, kmp + so, vmp + so, T1::lane_offset(lane1, wave),
+                                (unsigned)(own1 * MW), row1, wtok1, own1, r1);
+                    C.template update<true, false>(qh, kmul, qs, m, l, aux, acc, row1, wtok1, r1);
                 }
             }
         }

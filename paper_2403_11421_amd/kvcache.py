@@ -91,10 +91,13 @@ class KVCacheQ:
         self.mw = 1 if bits == 8 else 2                 # floats of parameters per row
         self.device = torch.device(device)
         self.caps = [max(1, int(c)) for c in capacities]
+        # rows a head occupies in its sequence's block: 4-bit rows lie in pairs, so their count
+        # is padded to even (the library's head_rows)
+        self.rows = [c if bits == 8 else (c + 1) & ~1 for c in self.caps]
         offs, o = [], 0
-        for c in self.caps:
+        for r in self.rows:
             offs.append(o)
-            o += H * c * self.rb                        # bytes of codes
+            o += H * r * self.rb                        # bytes of codes
             o = (o + 255) // 256 * 256
         self.offs = offs
         self.total_bytes = max(o, 256)
@@ -127,17 +130,25 @@ class KVCacheQ:
         return [self.k_codes, self.v_codes, self.k_scale, self.v_scale]
 
     def codes(self, which: str, b: int) -> torch.Tensor:
-        """View ``[H, cap_b, rb]`` (uint8) of sequence b's K or V code bytes."""
+        """``[H, cap_b, rb]`` (uint8): sequence b's K or V code bytes, row by row.  8 bit: a view of
+        the slab.  4 bit: a copy, taken out of the paired layout (rows 2p and 2p+1 of a head
+        alternate in 8-byte pieces)."""
         slab = self.k_codes if which == "K" else self.v_codes
-        n = self.H * self.caps[b] * self.rb
-        return slab[self.offs[b]: self.offs[b] + n].view(self.H, self.caps[b], self.rb)
+        rows = self.rows[b]
+        blk = slab[self.offs[b]: self.offs[b] + self.H * rows * self.rb]
+        if self.bits == 8:
+            return blk.view(self.H, rows, self.rb)
+        pieces = self.rb // 8
+        v = blk.view(self.H, rows // 2, pieces, 2, 8).permute(0, 1, 3, 2, 4)
+        return v.reshape(self.H, rows, self.rb)[:, : self.caps[b]]
 
     def scales(self, which: str, b: int) -> torch.Tensor:
         """View ``[H, cap_b]`` (8 bit: scale) or ``[H, cap_b, 2]`` (4 bit: scale, zero), float32."""
         slab = self.k_scale if which == "K" else self.v_scale
         o = self.offs[b] // self.rb * self.mw
-        v = slab[o: o + self.H * self.caps[b] * self.mw]
-        return v.view(self.H, self.caps[b]) if self.mw == 1 else v.view(self.H, self.caps[b], 2)
+        rows = self.rows[b]
+        v = slab[o: o + self.H * rows * self.mw]
+        return v.view(self.H, rows) if self.mw == 1 else v.view(self.H, rows, 2)[:, : self.caps[b]]
 
     def fill(self, which: str, b: int, rows: torch.Tensor, t0: int = 0) -> None:
         """Quantise fp16 ``rows [H, L, d]`` into tokens t0..t0+L-1 of sequence b (the library's

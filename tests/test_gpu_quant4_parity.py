@@ -100,6 +100,40 @@ def test_bulk_store_quantises_like_the_oracle():
             assert bool((case.cache.scales(which, b)[:, L:] == 0).all())
 
 
+@pytest.mark.parametrize("d", [128, 64])
+def test_rows_lie_in_pairs_at_the_documented_addresses(d):
+    """The raw slab against the address rule of the header: rows 2p and 2p+1 of a head alternate
+    in 8-byte pieces, a head's rows are padded to an even count, the parameters keep one entry
+    per (padded) row.  Odd and even capacities, appended and bulk-stored rows."""
+    cfg = _cfg("pairs", 3, 2, d)
+    lens, caps = [5, 8, 1], [7, 10, 3]
+    case = Q4Case(cfg, lens, seed=71, extra_cap=2)
+    assert case.cache.caps == caps
+    rpart.fd_kvq_append(case.cache.desc, case.k_new, case.v_new)
+    torch.cuda.synchronize()
+    rb = d // 2
+    raw = case.cache.k_codes.cpu().numpy()
+    raw_meta = case.cache.k_scale.cpu().numpy()
+    off = 0
+    for b, (L, cap) in enumerate(zip(lens, caps)):
+        rows_b = (cap + 1) // 2 * 2
+        assert case.cache.offs[b] == off
+        want, want_sz = O.quantize_rows_u4(bits(W.gen_cache_block(cfg, "K", b, L, 71, "cuda")))    # [H, L, rb]
+        new, new_sz = O.quantize_rows_u4(bits(case.k_new[b]).reshape(cfg.H, 1, d))
+        want = np.concatenate([want, new], axis=1)
+        want_sz = np.concatenate([want_sz, new_sz], axis=1)
+        for h in range(cfg.H):
+            for t in range(L + 1):
+                r = h * rows_b + t
+                for i in range(rb):
+                    a = off + (r // 2) * 2 * rb + (i // 8) * 16 + (r % 2) * 8 + i % 8
+                    assert raw[a] == want[h, t, i], (b, h, t, i)
+                m = (off // rb + r) * 2
+                assert np.array_equal(raw_meta[m: m + 2], want_sz[h, t])
+        off += cfg.H * rows_b * rb
+        off = (off + 255) // 256 * 256
+
+
 EDGE_LENS = [0, 1, 2, 7, 8, 9, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513,
              1000, 2500]
 
