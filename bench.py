@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 METRIC = "R-Part decode attention: achieved KV HBM GB/s (% of peak) and sequences/sec"
 HBM_PEAK_GBPS = 8000.0
+EXTRA_WARM_MS = 50.0          # untimed steps before each entry under extras (see measure_step)
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "rpart_partial_hbm_traffic.json")
 TRAFFIC_JSON_Q = os.path.join(ROOT, "profiles", "rpartq_partial_hbm_traffic.json")
 KERNEL_SRC = os.path.join(ROOT, "paper_2403_11421_amd", "csrc", "fd_rpart.hip")
@@ -177,10 +178,13 @@ def _pct(sorted_vals, p):
 
 
 def measure_step(config, kv, steps, warmup, seed=None, chunk_tokens=0, capacity=0, window=0, sinks=4,
-                 flush_mib=0, copy_calibration_mib=0, fill="values", keep=False):
+                 flush_mib=0, copy_calibration_mib=0, fill="values", keep=False, warm_ms=0.0):
     """One workload, one cache format: whole-step time over exactly `steps` steps (wall clock
     between synchronisations, HIP events around the streaming kernel on every 4th of them), then
-    `steps` more steps with events on every launch for the kernel-time percentiles."""
+    `steps` more steps with events on every launch for the kernel-time percentiles.  warm_ms > 0:
+    after the `warmup` steps, further untimed steps until that much time has passed (the device
+    takes some 20 ms of continuous work to reach its clocks after an idle spell: a short config
+    timed right after five warm-up steps reads up to 10 % low)."""
     import torch
     from paper_2403_11421_amd import rpart, workloads as W
 
@@ -234,6 +238,11 @@ def measure_step(config, kv, steps, warmup, seed=None, chunk_tokens=0, capacity=
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    t_warm = time.perf_counter()
+    while (time.perf_counter() - t_warm) * 1e3 < warm_ms:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(steps):
         if flush is not None:                      # cold caches: time the step alone, by events
@@ -444,7 +453,7 @@ def extras(args):
     """The other configs and cache formats, the schedule loop and the pipeline, each with fewer
     steps than the headline; every entry is measured exactly like the headline."""
     import torch
-    ex = {"steps_each": args.extra_steps}
+    ex = {"steps_each": args.extra_steps, "untimed_warm_ms_each": EXTRA_WARM_MS}
     t0 = time.time()
 
     def short(r):
@@ -455,11 +464,11 @@ def extras(args):
 
     ex["configs_fp16"] = {}
     for name in ("c3_7b_ragged", "c4_13b_geometric", "c5_capacity", "t2_batch1024", "t2_batch1", "c1_tiny"):
-        ex["configs_fp16"][name] = short(measure_step(name, "fp16", args.extra_steps, args.warmup))
+        ex["configs_fp16"][name] = short(measure_step(name, "fp16", args.extra_steps, args.warmup, warm_ms=EXTRA_WARM_MS))
         torch.cuda.empty_cache()
     ex["quantised_kv"] = {}
     for kv in ("int8", "int4"):
-        ex["quantised_kv"][kv] = {name: short(measure_step(name, kv, args.extra_steps, args.warmup))
+        ex["quantised_kv"][kv] = {name: short(measure_step(name, kv, args.extra_steps, args.warmup, warm_ms=EXTRA_WARM_MS))
                                   for name in ("c2_7b_uniform", "c4_13b_geometric")}
         torch.cuda.empty_cache()
     ex["schedule_loop"] = {kind: schedule_result(kind, args.sched_B, args.sched_S, args.sched_F)
@@ -474,7 +483,7 @@ def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--config", default="c2_7b_uniform")
     ap.add_argument("--seed", type=int, default=None)
     ap.add_argument("--chunk-tokens", type=int, default=0, help="split-K chunk length, 0 = library's choice")
@@ -490,7 +499,7 @@ def main() -> int:
     ap.add_argument("--extras", choices=["auto", "all", "none"], default="auto",
                     help="also measure the other configs, cache formats, the schedule loop and the pipeline and "
                          "carry them in the same JSON line (auto: only for the default config and format)")
-    ap.add_argument("--extra-steps", type=int, default=20, help="timed steps of every entry under extras")
+    ap.add_argument("--extra-steps", type=int, default=40, help="timed steps of every entry under extras")
     ap.add_argument("--fill", choices=["values", "pattern"], default="values",
                     help="pattern: fill the cache without dispatching a single torch kernel (for runs under "
                          "rocprofv3 --pmc); implies no CPU baseline, no entropy figure and no extras")
