@@ -469,7 +469,8 @@ def extras(args):
     ex["quantised_kv"] = {}
     for kv in ("int8", "int4"):
         ex["quantised_kv"][kv] = {name: short(measure_step(name, kv, args.extra_steps, args.warmup, warm_ms=EXTRA_WARM_MS))
-                                  for name in ("c2_7b_uniform", "c4_13b_geometric")}
+                                  for name in ("c2_7b_uniform", "c3_7b_ragged", "c4_13b_geometric", "c5_capacity",
+                                               "t2_batch1024")}
         torch.cuda.empty_cache()
     ex["schedule_loop"] = {kind: schedule_result(kind, args.sched_B, args.sched_S, args.sched_F)
                            for kind in ("batch", "sls")}
