@@ -272,6 +272,15 @@ def measure_step(config, kv, steps, warmup, seed=None, chunk_tokens=0, capacity=
         step(p)
     torch.cuda.synchronize()
     kms = sorted(a.elapsed_time(b) for a, b in every)
+    # the same kernel launched back to back on the step's plan, one pair of events around the lot:
+    # the events' own ~10 us, which weigh on a short kernel's single-launch figure, are shared out
+    b2b = events()
+    b2b[0].record()
+    for _ in range(steps):
+        f_partial(desc, vec["q"], out, ws)
+    b2b[1].record()
+    torch.cuda.synchronize()
+    b2b_ms = b2b[0].elapsed_time(b2b[1]) / steps
 
     ms_step = dt / steps * 1e3
     timed = [p for p in ev if p]
@@ -291,6 +300,7 @@ def measure_step(config, kv, steps, warmup, seed=None, chunk_tokens=0, capacity=
         "kernel_ms_p10": _pct(kms, 10), "kernel_ms_p50": _pct(kms, 50), "kernel_ms_p90": _pct(kms, 90),
         "kernel_launches_in_percentiles": len(kms),
         "kernel_gbps_p50": kv_bytes / (_pct(kms, 50) * 1e-3) / 1e9,
+        "kernel_ms_back_to_back": b2b_ms, "kernel_gbps_back_to_back": kv_bytes / (b2b_ms * 1e-3) / 1e9,
         "traffic": counter_traffic(cfg.name, kv) if window == 0 else None,
     }
     if keep:
@@ -459,7 +469,7 @@ def extras(args):
     def short(r):
         keys = ("config", "kv", "total_tokens", "kv_bytes_per_step", "plan", "steps", "ms_per_step", "step_gbps",
                 "seq_per_s", "kernel_ms_avg", "kernel_gbps", "frac", "kernel_ms_p10", "kernel_ms_p50",
-                "kernel_ms_p90")
+                "kernel_ms_p90", "kernel_ms_back_to_back", "kernel_gbps_back_to_back")
         return {k: r[k] for k in keys}
 
     ex["configs_fp16"] = {}
@@ -578,6 +588,8 @@ def main() -> int:
         "kernel_ms_p10": r["kernel_ms_p10"], "kernel_ms_p50": r["kernel_ms_p50"],
         "kernel_ms_p90": r["kernel_ms_p90"],
         "kernel_launches_in_percentiles": r["kernel_launches_in_percentiles"],
+        "kernel_ms_back_to_back": r["kernel_ms_back_to_back"],
+        "kernel_gbps_back_to_back": r["kernel_gbps_back_to_back"],
     }
     # the device's pure-read ceiling, timed beside the kernel over the K slab (context for `frac`)
     res["roofline"]["read_only_ceiling_gbps"] = read_only_ceiling(cache.k_codes if q8 else cache.k)
