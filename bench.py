@@ -140,8 +140,18 @@ def cpu_baseline(cfg, cache, vec, lens_after, n_sample):
         "kind": "oracle",
         "sample": f"{len(batch)} of {cfg.B} sequences (a stride of {step}), all {cfg.H} heads, "
                   f"{int(hl.sum())} cached tokens, decode only, {dt:.2f} s wall",
-        "seq_per_s": len(batch) / dt,
+        "seq_per_s": len(batch) / dt, "cpu_model": _cpu_model(),
     }
+
+
+def _cpu_model():
+    try:
+        for line in open("/proc/cpuinfo", encoding="utf-8", errors="replace"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def softmax_entropy(cfg, cache, vec, lens_after, n_sample=4):
