@@ -238,8 +238,9 @@ __global__ __launch_bounds__(256) void kvq_store_rows_kernel(
 // ---------------------------------------------------------------------------
 // Streaming kernel over codes.  A lane always holds 16 elements of a row (16 B of 8-bit or 8 B of
 // 4-bit codes), so a row is 8 lanes at d = 128 and 4 lanes at d = 64, and a wave load covers
-// RPW = 8 or 16 tokens (1 KB of 8-bit, 512 B of 4-bit codes either way); a workgroup block is
-// 4 waves x NL loads = 4 NL RPW tokens.  The NL RPW tokens of a wave's tile map onto its first
+// RPW = 8 or 16 tokens (1 KB of 8-bit codes; 4-bit rows are read two at a time, see TileQ, so
+// that a memory load is 1 KB there too and fills two of the tile's slots); a workgroup block is
+// 4 waves x NL slots = 4 NL RPW tokens.  The NL RPW tokens of a wave's tile map onto its first
 // NL RPW lanes for the row parameters: each lane loads those of "its" token (the other lanes
 // repeat them) and the values are handed to the lanes that need them with a cross-lane read.
 //
@@ -309,8 +310,9 @@ __device__ inline u32x2 ld_meta64(Rsrc r, unsigned voff)
 // stream 6.9 TB/s at 2048 tokens per sequence and 6.1 TB/s at 256; eight loads per tile with one
 // workgroup per CU (the fp16 kernel's shape) reach 6.2 and 3.3: this kernel has 2.5 x the
 // arithmetic per byte, and a second wave per SIMD is what hides it.
-// The 4-bit kernel takes twice the loads of half the size, so as many bytes are in flight.
-template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }   // wave loads per tile
+// The 4-bit kernel's tile has twice the slots of half the size (two memory loads of row pairs
+// per stream), so as many bytes are in flight.
+template <int BITS> constexpr int q_tile_loads() { return BITS == 8 ? 2 : 4; }   // slots (wave loads of RPW rows) per tile
 // Workgroups per compute unit.  8 bit: two when the sequences are long; the kernel (147 VGPRs)
 // fits a third one, which pays on short sequences (+5 % at 256 tokens per sequence, -5 % at
 // 2048), so the planner switches it on by the same rule as the fp16 kernel's second one.
