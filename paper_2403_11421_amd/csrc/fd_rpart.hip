@@ -337,6 +337,35 @@ __device__ inline void block_sum2(int &x, int &y, int *sm)
     }
 }
 
+// two sums, a minimum and a maximum over the workgroup with one pair of barriers
+__device__ inline void block_sum2_minmax(int &x, int &y, int &lo, int &hi, int *sm)
+{
+    constexpr int NW = kPlanThreads / 64;
+    for (int off = 32; off > 0; off >>= 1) {
+        x += __shfl_xor(x, off);
+        y += __shfl_xor(y, off);
+        lo = min(lo, __shfl_xor(lo, off));
+        hi = max(hi, __shfl_xor(hi, off));
+    }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        const int w = threadIdx.x >> 6;
+        sm[w] = x;
+        sm[NW + w] = y;
+        sm[2 * NW + w] = lo;
+        sm[3 * NW + w] = hi;
+    }
+    __syncthreads();
+    x = 0;
+    y = 0;
+    for (int w = 0; w < NW; ++w) {
+        x += sm[w];
+        y += sm[NW + w];
+        lo = min(lo, sm[2 * NW + w]);
+        hi = max(hi, sm[3 * NW + w]);
+    }
+}
+
 // exclusive prefix sum over the workgroup's threads (two barriers)
 __device__ inline int block_exclusive_scan(int v, int *sm)
 {
@@ -440,12 +469,14 @@ __device__ inline void plan_body(const PlanArgs &a)
     // cached tokens that sits in sequences shorter than short_below tokens (100 %, 14 %, 0, 3.5 %,
     // 5.5 %): above a tenth the larger grid is used.  The host launches the larger number and
     // workgroups at or beyond `grid` leave at once.
-    int total = 0, few = 0;
+    int total = 0, few = 0, lmin = 0x7FFFFFFF, lmax = 0;
     each([&](int, int L) {
         total += L;
         few += L < a.short_below ? L : 0;
+        lmin = min(lmin, L);
+        lmax = max(lmax, L);
     });
-    block_sum2(total, few, sm);
+    block_sum2_minmax(total, few, lmin, lmax, sm);
     if (bad) atomicOr(a.status, FD_ST_BADLEN);
     const bool many_short = (long long)few * 10 > (long long)total;
     const int grid = many_short ? a.grid_short : a.grid_long;
@@ -466,130 +497,177 @@ __device__ inline void plan_body(const PlanArgs &a)
     }
     T = (T + granule - 1) / granule * granule;
 
-    // items in all (the chunk length is doubled until they fit the workspace) and sequences cut
-    // into many chunks; c = this thread's items
-    int count, c, n_big;
-    for (;;) {
-        c = 0;
-        n_big = 0;
-        each([&](int, int L) {
-            const int n = (L + T - 1) / T;
-            c += n;
-            n_big += n > kBigChunks;
-        });
-        count = c;
-        block_sum2(count, n_big, sm);
-        if (count <= max_items || T >= (1 << 30)) break;   // T >= longest sequence gives count <= B
-        T *= 2;
-    }
-    // A sequence cut into many chunks (one that has the device almost to itself) is written out
-    // by the whole workgroup, a chunk per thread, instead of by the one thread that owns it:
-    // 128 chunks walked by one thread took 46 us.  The list is used only when it holds them all.
-    const bool use_list = n_big <= kBigMax;
-    if (tid < kBuckets) hist[tid] = 0;
-    if (tid == 0) { nbig = 0; big_nmax = 0; }
-    const int first = block_exclusive_scan(c, sm);      // its barriers also publish hist = 0
-    int pos = first;
-    each([&](int b, int L) {
-        const int n = (L + T - 1) / T;
-        item0[b] = pos;
-        nchunk[b] = n;
-        if (a.after_append) {
-            // what the append of this launch makes of the sequence's bookkeeping; the streaming
-            // kernel stores it into seq_lens / seq_seen
-            int new_len, new_seen, err;
-            append_rule(a.seq_lens[b], a.seq_cap[b], a.seq_seen != nullptr,
-                        a.seq_seen ? a.seq_seen[b] : 0, a.n_sink, &new_len, &new_seen, &err);
-            a.v.newlen[b] = new_len;
-            a.v.newseen[b] = new_seen;
+    // The order in which the sequences are visited when the schedule is filled.  With `hashed` it
+    // is scrambled (a bijection of [0, B)): equal-length sequences then run side by side in no
+    // regular pattern.  A regular one can put the streams that run in lockstep a constant distance
+    // apart, and for some distances (2^a + 2^(a+8) bytes was seen) they then fight over the same
+    // DRAM banks all the way: -10 % on the int8 kernel.
+    int hbits = 1;
+    while ((1 << hbits) < B) ++hbits;
+    const unsigned hmask = (1u << hbits) - 1u;
+    const int hhalf = (hbits + 1) / 2;
+    auto visit = [&](int j) {
+        if (!a.hashed) return j;
+        unsigned x = (unsigned)j;
+        do {                                                // cycle-walk back into [0, B)
+            x = (x * 0x9E3779B1u) & hmask;
+            x ^= x >> hhalf;
+            x = (x * 0x85EBCA6Bu) & hmask;
+            x ^= x >> hhalf;
+        } while (x >= (unsigned)B);
+        return (int)x;
+    };
+
+    // Equal lengths (a batch decoded in lockstep, a single sequence): every sequence is cut alike,
+    // sequence b's items are b n .. b n + n - 1, and chunk-major order (chunk 0 of every sequence,
+    // then chunk 1, ...) is already longest first, since only a sequence's last chunk can be
+    // shorter than the others.  No counting, no sort, no further barrier: 8.5 -> 5 us for the
+    // fused append + plan launch (about the time of the append alone), a fifth of a batch-1 step.
+    int count = 0;
+    bool uniform = lmin == lmax && lmin > 0;
+    if (uniform) {
+        int n = (lmin + T - 1) / T;
+        while ((long long)B * n > max_items && T < (1 << 30)) {
+            T *= 2;
+            n = (lmin + T - 1) / T;
         }
-        if (use_list && n > kBigChunks) {
-            big[atomicAdd(&nbig, 1)] = make_int4(b, L, n, pos);
-            atomicMax(&big_nmax, n);
-        } else {
-            for (int k = 0; k < n; ++k) {
-                int t0, t1;
-                chunk_span(L, n, granule, k, &t0, &t1);
-                if (pos + k < max_items) {
+        uniform = n <= kBigChunks && (long long)B * n <= max_items;
+        if (uniform) {
+            count = B * n;
+            each([&](int b, int L) {
+                const int pos = b * n;
+                item0[b] = pos;
+                nchunk[b] = n;
+                if (a.after_append) {
+                    int new_len, new_seen, err;
+                    append_rule(a.seq_lens[b], a.seq_cap[b], a.seq_seen != nullptr,
+                                a.seq_seen ? a.seq_seen[b] : 0, a.n_sink, &new_len, &new_seen, &err);
+                    a.v.newlen[b] = new_len;
+                    a.v.newseen[b] = new_seen;
+                }
+                for (int k = 0; k < n; ++k) {
+                    int t0, t1;
+                    chunk_span(L, n, granule, k, &t0, &t1);
                     items[pos + k] = make_int4(b, t0, t1, n);
+                }
+                if (n > 1)
+                    for (int h = 0; h < H; ++h) cnt[(int64_t)pos * H + h] = 0;
+            });
+            for (int j = b0; j < b1; ++j) {
+                const int b = visit(j);
+                for (int k = 0; k < n; ++k) order[(int64_t)k * B + j] = b * n + k;
+            }
+        }
+    }
+    if (!uniform) {
+        // items in all (the chunk length is doubled until they fit the workspace) and sequences cut
+        // into many chunks; c = this thread's items
+        int c, n_big;
+        for (;;) {
+            c = 0;
+            n_big = 0;
+            each([&](int, int L) {
+                const int n = (L + T - 1) / T;
+                c += n;
+                n_big += n > kBigChunks;
+            });
+            count = c;
+            block_sum2(count, n_big, sm);
+            if (count <= max_items || T >= (1 << 30)) break;   // T >= longest sequence gives count <= B
+            T *= 2;
+        }
+        // A sequence cut into many chunks (one that has the device almost to itself) is written out
+        // by the whole workgroup, a chunk per thread, instead of by the one thread that owns it:
+        // 128 chunks walked by one thread took 46 us.  The list is used only when it holds them all.
+        const bool use_list = n_big <= kBigMax;
+        if (tid < kBuckets) hist[tid] = 0;
+        if (tid == 0) { nbig = 0; big_nmax = 0; }
+        const int first = block_exclusive_scan(c, sm);      // its barriers also publish hist = 0
+        int pos = first;
+        each([&](int b, int L) {
+            const int n = (L + T - 1) / T;
+            item0[b] = pos;
+            nchunk[b] = n;
+            if (a.after_append) {
+                // what the append of this launch makes of the sequence's bookkeeping; the streaming
+                // kernel stores it into seq_lens / seq_seen
+                int new_len, new_seen, err;
+                append_rule(a.seq_lens[b], a.seq_cap[b], a.seq_seen != nullptr,
+                            a.seq_seen ? a.seq_seen[b] : 0, a.n_sink, &new_len, &new_seen, &err);
+                a.v.newlen[b] = new_len;
+                a.v.newseen[b] = new_seen;
+            }
+            if (use_list && n > kBigChunks) {
+                big[atomicAdd(&nbig, 1)] = make_int4(b, L, n, pos);
+                atomicMax(&big_nmax, n);
+            } else {
+                for (int k = 0; k < n; ++k) {
+                    int t0, t1;
+                    chunk_span(L, n, granule, k, &t0, &t1);
+                    if (pos + k < max_items) {
+                        items[pos + k] = make_int4(b, t0, t1, n);
+                        atomicAdd(&hist[length_bucket(t1 - t0, T)], 1);
+                    }
+                }
+                // a split sequence's heads count their finished chunks here (see finish_split)
+                if (n > 1 && pos < max_items)
+                    for (int h = 0; h < H; ++h) cnt[(int64_t)pos * H + h] = 0;
+            }
+            pos += n;
+        });
+        __syncthreads();
+        const int n_listed = nbig;
+        for (int s = 0; s < n_listed; ++s) {
+            const int4 e = big[s];                          // (b, L, n, first item)
+            for (int k = tid; k < e.z; k += kPlanThreads) {
+                int t0, t1;
+                chunk_span(e.y, e.z, granule, k, &t0, &t1);
+                if (e.w + k < max_items) {
+                    items[e.w + k] = make_int4(e.x, t0, t1, e.z);
                     atomicAdd(&hist[length_bucket(t1 - t0, T)], 1);
                 }
             }
-            // a split sequence's heads count their finished chunks here (see finish_split)
-            if (n > 1 && pos < max_items)
-                for (int h = 0; h < H; ++h) cnt[(int64_t)pos * H + h] = 0;
+            if (e.w < max_items)
+                for (int h = tid; h < H; h += kPlanThreads) cnt[(int64_t)e.w * H + h] = 0;
         }
-        pos += n;
-    });
-    __syncthreads();
-    const int n_listed = nbig;
-    for (int s = 0; s < n_listed; ++s) {
-        const int4 e = big[s];                          // (b, L, n, first item)
-        for (int k = tid; k < e.z; k += kPlanThreads) {
-            int t0, t1;
-            chunk_span(e.y, e.z, granule, k, &t0, &t1);
-            if (e.w + k < max_items) {
-                items[e.w + k] = make_int4(e.x, t0, t1, e.z);
-                atomicAdd(&hist[length_bucket(t1 - t0, T)], 1);
+        __syncthreads();
+        // bucket starts = exclusive scan of the 256 counters, then scatter
+        {
+            const int n = tid < kBuckets ? hist[tid] : 0;
+            const int start = block_exclusive_scan(n, sm);
+            if (tid < kBuckets) hist[tid] = start;
+        }
+        __syncthreads();
+        // Scatter.  Inside a bucket the order is the arrival order of the atomics, the sequences
+        // being visited in the order of `visit`.
+        for (int j = b0; j < b1; ++j) {
+            const int b = visit(j);
+            const int n = nchunk[b];
+            const int base = item0[b];
+            if (n > 0 && !(use_list && n > kBigChunks)) {
+                const int L = plan_len(a, b, &bad);
+                for (int k = 0; k < n; ++k) {
+                    int t0, t1;
+                    chunk_span(L, n, granule, k, &t0, &t1);
+                    if (base + k < max_items)
+                        order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = base + k;
+                }
             }
         }
-        if (e.w < max_items)
-            for (int h = tid; h < H; h += kPlanThreads) cnt[(int64_t)e.w * H + h] = 0;
-    }
-    __syncthreads();
-    // bucket starts = exclusive scan of the 256 counters, then scatter
-    {
-        const int n = tid < kBuckets ? hist[tid] : 0;
-        const int start = block_exclusive_scan(n, sm);
-        if (tid < kBuckets) hist[tid] = start;
-    }
-    __syncthreads();
-    // Scatter.  Inside a bucket the order is the arrival order of the atomics.  With `hashed` the
-    // sequences are visited in a scrambled order (a bijection of [0, B)): equal-length sequences
-    // then run side by side in no regular pattern.  A regular one can put the streams that run
-    // in lockstep a constant distance apart, and for some distances (2^a + 2^(a+8) bytes was
-    // seen) they then fight over the same DRAM banks all the way: -10 % on the int8 kernel.
-    int bits = 1;
-    while ((1 << bits) < B) ++bits;
-    const unsigned mask = (1u << bits) - 1u;
-    const int half = (bits + 1) / 2;
-    for (int j = b0; j < b1; ++j) {
-        int b = j;
-        if (a.hashed) {
-            unsigned x = (unsigned)j;
-            do {                                            // cycle-walk back into [0, B)
-                x = (x * 0x9E3779B1u) & mask;
-                x ^= x >> half;
-                x = (x * 0x85EBCA6Bu) & mask;
-                x ^= x >> half;
-            } while (x >= (unsigned)B);
-            b = (int)x;
-        }
-        const int n = nchunk[b];
-        const int base = item0[b];
-        if (n > 0 && !(use_list && n > kBigChunks)) {
-            const int L = plan_len(a, b, &bad);
-            for (int k = 0; k < n; ++k) {
-                int t0, t1;
-                chunk_span(L, n, granule, k, &t0, &t1);
-                if (base + k < max_items)
-                    order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = base + k;
-            }
-        }
-    }
-    // listed sequences chunk-major (chunk 0 of each, chunk 1 of each, ...), the order in which
-    // their owner threads, side by side in one wave, would have issued the atomics: units that
-    // run at the same time then belong to different sequences where there are several
-    if (n_listed > 0) {
-        const long long k_end = (long long)big_nmax * n_listed;
-        for (long long i = tid; i < k_end; i += kPlanThreads) {
-            const int k = (int)(i / n_listed);
-            const int4 e = big[(int)(i - (long long)k * n_listed)];
-            if (k < e.z) {
-                int t0, t1;
-                chunk_span(e.y, e.z, granule, k, &t0, &t1);
-                if (e.w + k < max_items)
-                    order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = e.w + k;
+        // listed sequences chunk-major (chunk 0 of each, chunk 1 of each, ...), the order in which
+        // their owner threads, side by side in one wave, would have issued the atomics: units that
+        // run at the same time then belong to different sequences where there are several
+        if (n_listed > 0) {
+            const long long k_end = (long long)big_nmax * n_listed;
+            for (long long i = tid; i < k_end; i += kPlanThreads) {
+                const int k = (int)(i / n_listed);
+                const int4 e = big[(int)(i - (long long)k * n_listed)];
+                if (k < e.z) {
+                    int t0, t1;
+                    chunk_span(e.y, e.z, granule, k, &t0, &t1);
+                    if (e.w + k < max_items)
+                        order[atomicAdd(&hist[length_bucket(t1 - t0, T)], 1)] = e.w + k;
+                }
             }
         }
     }

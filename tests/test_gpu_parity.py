@@ -383,3 +383,19 @@ def test_two_launch_step_equals_append_then_decode(d):
     assert a.cache.seq_lens.cpu().tolist() == want_lens
     assert torch.equal(a.cache.k, k_before)
     assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16))
+
+
+@pytest.mark.parametrize("B,H,L,chunk", [(1, 32, 255, 0), (7, 3, 1000, 256), (300, 2, 129, 64), (5000, 1, 17, 0),
+                                         (4, 2, 5000, 128)])
+def test_equal_lengths_are_planned_without_a_sort(B, H, L, chunk):
+    """Batches of equal-length sequences take the planner's short way (no counting, no sort; items
+    b n .. b n + n - 1, chunk-major order): one sequence alone, forced chunks, more sequences than
+    planner threads and than the threads' length registers, and a cut into more chunks than the
+    short way takes (which must fall back to the general one)."""
+    cfg = _cfg("equal", B, H, 64)
+    case = DeviceCase(cfg, [L] * B, seed=91, chunk_tokens=chunk, extra_cap=2)
+    check_step(case, use_step=True)
+    info = rpart.fd_plan_info(case.ws)
+    T = info["chunk_tokens"]
+    assert info["total_tokens"] == B * (L + 1) and info["items"] == B * math.ceil((L + 1) / T)
+    check_step(case)                                          # and again, one token longer

@@ -294,3 +294,15 @@ def test_config1_shape_with_a_4bit_cache_and_short_batch_modes_at_d64():
     lens = [(37 * i) % 300 for i in range(40)]
     case = Q4Case(_cfg("q4short64", len(lens), 5, 64), lens, seed=3)
     check_q4step(case)
+
+
+@pytest.mark.parametrize("B,H,L,chunk", [(1, 32, 255, 0), (9, 3, 700, 128), (1500, 1, 40, 0)])
+def test_equal_lengths_are_planned_without_a_sort(B, H, L, chunk):
+    """The planner's short way for equal lengths with the scrambled visiting order of the
+    quantised kernels (wave units and workgroup units, split and whole sequences)."""
+    cfg = _cfg("q4equal", B, H, 64)
+    case = Q4Case(cfg, [L] * B, seed=92, chunk_tokens=chunk)
+    check_q4step(case, use_step=True)
+    info = rpart.fd_plan_info(case.ws)
+    assert info["total_tokens"] == B * (L + 1)
+    assert info["items"] == B * -(-(L + 1) // info["chunk_tokens"])
