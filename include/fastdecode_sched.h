@@ -116,6 +116,14 @@ double fd_model_sworker_throughput(int64_t B, double T_B);
 int64_t fd_model_min_rworkers_memory(int64_t B, int64_t S, int64_t C);
 double fd_model_num_rworkers(int64_t B, int64_t S, double R, double T_B);
 
+/*
+ * Identifies the build: a hash of the sources, headers and compiler flags this library was made
+ * from ("unknown" when the build step passed none).  The Python binding compares it with the hash
+ * of the tree it sits in, so that a library left over from other sources is never tested or timed
+ * unnoticed.  Not part of the method.
+ */
+const char *fd_build_id(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,6 @@ HIPCC_FLAGS = [
 
 DEPS = SOURCES + [os.path.join(_PKG, "csrc", "fd_rpartq.h"), os.path.join(INCLUDE, "fastdecode_rpart.h"),
                   os.path.join(INCLUDE, "fastdecode_sched.h")]
-STAMP = LIB + ".srchash"            # written beside the library: what it was built from
 
 
 def source_hash(extra_flags=()) -> str:
@@ -35,17 +34,27 @@ def source_hash(extra_flags=()) -> str:
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every HIP source into the shared library; always recompiles."""
+    """Compile every HIP source into the shared library; always recompiles.  The library carries
+    the hash of what it was built from (fd_build_id)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + ["-I", INCLUDE, "-o", LIB] + SOURCES
+    cmd = ([hipcc] + HIPCC_FLAGS + list(extra_flags) + [f'-DFD_BUILD_ID="{source_hash(extra_flags)}"', "-I", INCLUDE,
+                                                        "-o", LIB] + SOURCES)
     if verbose:
         print(" ".join(cmd), flush=True)
-    if os.path.exists(STAMP):
-        os.remove(STAMP)
     subprocess.check_call(cmd)
-    with open(STAMP, "w") as f:
-        f.write(source_hash(extra_flags) + "\n")
     return LIB
+
+
+def built_from():
+    """The build id the library on disk reports, or None if there is none to ask."""
+    import ctypes
+    try:
+        f = ctypes.CDLL(LIB).fd_build_id
+    except (OSError, AttributeError):
+        return None
+    f.restype = ctypes.c_char_p
+    f.argtypes = []
+    return f().decode()
 
 
 def have_compiler() -> bool:
@@ -56,10 +65,7 @@ def have_compiler() -> bool:
 def is_stale() -> bool:
     """True when the library is missing or was built from other sources than the tree holds now
     (by content, not by file time: a copied tree keeps no reliable times)."""
-    if not os.path.exists(LIB) or not os.path.exists(STAMP):
-        return True
-    with open(STAMP) as f:
-        return f.read().strip() != source_hash()
+    return not os.path.exists(LIB) or built_from() != source_hash()
 
 
 if __name__ == "__main__":

@@ -246,3 +246,10 @@ double fd_model_num_rworkers(int64_t B, int64_t S, double R, double T_B)
 }
 
 } // extern "C"
+
+// What this library was built from: the build step passes a hash of the sources, headers and
+// compiler flags, and the binding refuses (or rebuilds) a library whose hash is not the tree's.
+#ifndef FD_BUILD_ID
+#define FD_BUILD_ID "unknown"
+#endif
+extern "C" const char *fd_build_id(void) { return FD_BUILD_ID; }

@@ -70,7 +70,8 @@ EXPORTS = ("fd_sls_microbatch_size", "fd_sls_peak_load", "fd_sls_step_loads", "f
            "fd_model_sequence_latency", "fd_model_max_batch", "fd_model_sworker_throughput",
            "fd_model_min_rworkers_memory", "fd_model_num_rworkers",
            "fd_slots_create", "fd_slots_destroy", "fd_slots_acquire", "fd_slots_release",
-           "fd_slots_in_use")
+           "fd_slots_in_use",
+           "fd_build_id")
 
 
 def _ok(v: int, where: str) -> int:
